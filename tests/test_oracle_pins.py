@@ -1,0 +1,409 @@
+"""Pins for the CPU oracle: it is checked here against things other than itself.
+
+The paper gives no formula or printed example for the convolution layer (Sec. 4.2
+describes it as a matrix product of the lowered image with the weight matrix), so
+the pins are mathematical: hand-worked cases, identity / shift filters, 1x1 ==
+matmul, explicit lowering + matmul, the adjoint identity, exact finite differences,
+exhaustive rational-arithmetic loops, closed forms.  All run on the CPU.
+"""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1606_04884_amd import synth
+
+
+# ----------------------------------------------------------------------------
+# helpers
+# ----------------------------------------------------------------------------
+def parse_cases(path):
+    cases, cur = [], None
+    with open(path) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            if key == "case":
+                cur = {"name": vals[0]}
+                cases.append(cur)
+            elif key == "geom":
+                cur["geom"] = tuple(int(v) for v in vals)
+            elif key == "scale":
+                cur["scale"] = float(vals[0])
+            else:
+                cur[key] = np.array([float(v) for v in vals])
+    return cases
+
+
+def out_dims(g):
+    N, C, H, W, K, R, S, sh, sw, ph, pw = g
+    return (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
+
+
+def geom(N, C, H, W, K, R, S, s, p):
+    return (N, C, H, W, K, R, S, s, s, p, p)
+
+
+def f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked.txt")
+CASES = parse_cases(GOLDEN)
+
+
+# ----------------------------------------------------------------------------
+# 1. hand-worked examples (tests/golden/hand_worked.txt)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("case", CASES, ids=[c["name"] for c in CASES])
+def test_hand_worked(case):
+    g = case["geom"]
+    N, C, H, W, K, R, S = g[:7]
+    P, Q = out_dims(g)
+    assert oracle.output_dims(g) == (P, Q)
+    x = f32(case["x"].reshape(N, C, H, W))
+    w = f32(case["w"].reshape(K, C, R, S))
+    b = f32(case["b"]) if "b" in case else None
+    scale = case.get("scale", 1.0)
+    if "y" in case:
+        np.testing.assert_array_equal(oracle.fwd(g, x, w, b).ravel(), case["y"])
+        idx = np.arange(N * K * P * Q)
+        np.testing.assert_array_equal(oracle.fwd_at(g, x, w, b, idx), case["y"])
+    if "dy" in case:
+        dy = f32(case["dy"].reshape(N, K, P, Q))
+        if "dx" in case:
+            np.testing.assert_array_equal(oracle.bwd_data(g, dy, w).ravel(), case["dx"])
+            np.testing.assert_array_equal(
+                oracle.bwd_data_at(g, dy, w, np.arange(N * C * H * W)), case["dx"])
+        dw, db = oracle.bwd_weight(g, x, dy, scale)
+        np.testing.assert_array_equal(dw.ravel(), case["dw"])
+        np.testing.assert_array_equal(db, case["db"])
+        np.testing.assert_array_equal(
+            oracle.bwd_weight_at(g, x, dy, np.arange(K * C * R * S), scale), case["dw"])
+
+
+# ----------------------------------------------------------------------------
+# 2. identity filter: y == x bit for bit
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("R", [1, 3, 5])
+def test_identity_filter(R):
+    N, C, H, W = 2, 3, 7, 6
+    g = geom(N, C, H, W, C, R, R, 1, (R - 1) // 2)
+    x = synth.normal((N, C, H, W), 11)
+    w = np.zeros((C, C, R, R), np.float32)
+    for c in range(C):
+        w[c, c, R // 2, R // 2] = 1.0
+    y = oracle.fwd(g, x, w)
+    np.testing.assert_array_equal(y, x.astype(np.float64))
+    # and the transpose of the identity is the identity
+    np.testing.assert_array_equal(oracle.bwd_data(g, x, w), x.astype(np.float64))
+
+
+# ----------------------------------------------------------------------------
+# 3. shift (delta) filter: pins the index arithmetic for every tap, stride, pad
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("s,p", [(1, 0), (1, 1), (2, 1), (3, 2), (4, 2), (2, 0)])
+def test_delta_filter_all_taps(s, p):
+    N, C, H, W, R, S = 2, 2, 9, 8, 3, 4
+    g = (N, C, H, W, 1, R, S, s, s, p, p)
+    P, Q = out_dims(g)
+    x = synth.normal((N, C, H, W), 5)
+    for c0, r0, t0 in itertools.product(range(C), range(R), range(S)):
+        w = np.zeros((1, C, R, S), np.float32)
+        w[0, c0, r0, t0] = 1.0
+        y = oracle.fwd(g, x, w)
+        exp = np.zeros((N, 1, P, Q))
+        for pp in range(P):
+            for qq in range(Q):
+                ih, iw = pp * s - p + r0, qq * s - p + t0
+                if 0 <= ih < H and 0 <= iw < W:
+                    exp[:, 0, pp, qq] = x[:, c0, ih, iw]
+        np.testing.assert_array_equal(y, exp)
+
+
+# ----------------------------------------------------------------------------
+# 4. 1x1 convolution == matrix product per image
+# ----------------------------------------------------------------------------
+def test_1x1_equals_matmul():
+    N, C, H, W, K = 3, 13, 5, 7, 6
+    g = geom(N, C, H, W, K, 1, 1, 1, 0)
+    x = synth.normal((N, C, H, W), 21)
+    w = synth.normal((K, C, 1, 1), 22)
+    b = synth.uniform((K,), 23)
+    y = oracle.fwd(g, x, w, b)
+    wm = w.reshape(K, C).astype(np.float64)
+    for n in range(N):
+        ref = wm @ x[n].reshape(C, H * W).astype(np.float64) + b.astype(np.float64)[:, None]
+        np.testing.assert_allclose(y[n].reshape(K, H * W), ref, rtol=0, atol=1e-13)
+    dy = synth.normal((N, K, H, W), 24)
+    dx = oracle.bwd_data(g, dy, w)
+    dw, db = oracle.bwd_weight(g, x, dy)
+    dwref = np.zeros((K, C))
+    for n in range(N):
+        ref = wm.T @ dy[n].reshape(K, H * W).astype(np.float64)
+        np.testing.assert_allclose(dx[n].reshape(C, H * W), ref, rtol=0, atol=1e-13)
+        dwref += dy[n].reshape(K, -1).astype(np.float64) @ x[n].reshape(C, -1).astype(np.float64).T
+    np.testing.assert_allclose(dw.reshape(K, C), dwref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(db, dy.astype(np.float64).sum(axis=(0, 2, 3)), rtol=0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# 5. explicit lowering (Sec. 4.2 "im2col"): W_mat @ col(x) == oracle fwd
+# ----------------------------------------------------------------------------
+def lower(xn, R, S, s, p, P, Q):
+    C, H, W = xn.shape
+    xp = np.zeros((C, H + 2 * p, W + 2 * p))
+    xp[:, p:p + H, p:p + W] = xn
+    col = np.empty((C * R * S, P * Q))
+    row = 0
+    for c in range(C):
+        for r in range(R):
+            for t in range(S):
+                col[row] = xp[c, r:r + s * P:s, t:t + s * Q:s][:P, :Q].ravel()
+                row += 1
+    return col
+
+
+@pytest.mark.parametrize("R,S,s,p,H,W", [(3, 3, 1, 1, 8, 9), (5, 5, 1, 2, 9, 9), (11, 11, 4, 2, 31, 30),
+                                         (3, 2, 2, 1, 10, 7), (1, 1, 1, 0, 4, 5), (3, 3, 3, 0, 11, 12)])
+def test_lowering_equivalence(R, S, s, p, H, W):
+    N, C, K = 2, 3, 4
+    g = (N, C, H, W, K, R, S, s, s, p, p)
+    P, Q = out_dims(g)
+    x = synth.normal((N, C, H, W), 31)
+    w = synth.normal((K, C, R, S), 32)
+    y = oracle.fwd(g, x, w)
+    wm = w.reshape(K, C * R * S).astype(np.float64)
+    for n in range(N):
+        col = lower(x[n].astype(np.float64), R, S, s, p, P, Q)
+        np.testing.assert_allclose(y[n].reshape(K, P * Q), wm @ col, rtol=0, atol=1e-12)
+        # backward-weight of one image is dy_mat @ col^T (same lowering)
+    dy = synth.normal((N, K, P, Q), 33)
+    dw, _ = oracle.bwd_weight(g, x, dy)
+    ref = sum(dy[n].reshape(K, -1).astype(np.float64) @
+              lower(x[n].astype(np.float64), R, S, s, p, P, Q).T for n in range(N))
+    np.testing.assert_allclose(dw.reshape(K, -1), ref, rtol=0, atol=1e-11)
+
+
+# ----------------------------------------------------------------------------
+# 6. adjoint identity <conv(x,w),dy> = <x,bwdD(dy,w)> = <w,bwdW(x,dy)>
+# ----------------------------------------------------------------------------
+ADJ = [(2, 3, 9, 8, 4, 3, 3, 1, 1), (1, 2, 23, 19, 3, 11, 11, 4, 2), (2, 2, 12, 12, 3, 5, 5, 1, 2),
+       (2, 4, 7, 7, 5, 1, 1, 1, 0), (1, 3, 10, 11, 2, 3, 3, 2, 0), (1, 1, 13, 9, 2, 4, 2, 3, 1),
+       (2, 2, 6, 6, 2, 3, 3, 1, 2), (1, 2, 9, 9, 2, 2, 2, 4, 0)]
+
+
+@pytest.mark.parametrize("N,C,H,W,K,R,S,s,p", ADJ)
+def test_adjoint_identity(N, C, H, W, K, R, S, s, p):
+    g = geom(N, C, H, W, K, R, S, s, p)
+    P, Q = out_dims(g)
+    x = synth.normal((N, C, H, W), 41)
+    w = synth.normal((K, C, R, S), 42)
+    dy = synth.normal((N, K, P, Q), 43)
+    y = oracle.fwd(g, x, w)
+    dx = oracle.bwd_data(g, dy, w)
+    dw, _ = oracle.bwd_weight(g, x, dy)
+    a = float((y * dy).sum())
+    b = float((dx * x).sum())
+    c = float((dw * w).sum())
+    scale = float(np.abs(y * dy).sum()) + 1e-30
+    assert abs(a - b) <= 1e-12 * scale
+    assert abs(a - c) <= 1e-12 * scale
+
+
+# ----------------------------------------------------------------------------
+# 7. finite differences, exact: L = sum(y*dy) is bilinear in (x,w) and affine in
+#    b, so central differences on dyadic inputs reproduce the gradient exactly.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("N,C,H,W,K,R,S,s,p", [(1, 2, 5, 4, 2, 3, 3, 1, 1), (1, 1, 7, 6, 2, 3, 2, 2, 1),
+                                               (2, 1, 5, 5, 1, 2, 2, 1, 0)])
+def test_finite_differences_exact(N, C, H, W, K, R, S, s, p):
+    g = geom(N, C, H, W, K, R, S, s, p)
+    P, Q = out_dims(g)
+    x = synth.dyadic((N, C, H, W), 51)
+    w = synth.dyadic((K, C, R, S), 52)
+    b = synth.dyadic((K,), 53)
+    dy = synth.dyadic((N, K, P, Q), 54)
+    dx = oracle.bwd_data(g, dy, w)
+    dw, db = oracle.bwd_weight(g, x, dy)
+    h = 0.25
+
+    def loss(xx, ww, bb):
+        return float((oracle.fwd(g, xx, ww, bb) * dy).sum())
+
+    for i in range(x.size):
+        xp, xm = x.copy(), x.copy()
+        xp.flat[i] += h
+        xm.flat[i] -= h
+        assert (loss(xp, w, b) - loss(xm, w, b)) / (2 * h) == dx.flat[i]
+    for i in range(w.size):
+        wp, wm = w.copy(), w.copy()
+        wp.flat[i] += h
+        wm.flat[i] -= h
+        assert (loss(x, wp, b) - loss(x, wm, b)) / (2 * h) == dw.flat[i]
+    for i in range(b.size):
+        bp, bm = b.copy(), b.copy()
+        bp[i] += h
+        bm[i] -= h
+        assert (loss(x, w, bp) - loss(x, w, bm)) / (2 * h) == db[i]
+
+
+# ----------------------------------------------------------------------------
+# 8. linearity and bias
+# ----------------------------------------------------------------------------
+def test_linearity_and_bias():
+    g = geom(2, 3, 8, 8, 4, 3, 3, 1, 1)
+    x = synth.dyadic((2, 3, 8, 8), 61)
+    w = synth.dyadic((4, 3, 3, 3), 62)
+    b = synth.dyadic((4,), 63)
+    y0 = oracle.fwd(g, x, w)
+    yb = oracle.fwd(g, x, w, b)
+    np.testing.assert_array_equal(yb - y0, np.broadcast_to(b.astype(np.float64)[None, :, None, None], y0.shape))
+    np.testing.assert_array_equal(oracle.fwd(g, f32(2 * x), w), 2 * y0)
+    x2 = synth.dyadic((2, 3, 8, 8), 64)
+    np.testing.assert_array_equal(oracle.fwd(g, f32(x + x2), w), y0 + oracle.fwd(g, x2, w))
+    dy = synth.dyadic((2, 4, 8, 8), 65)
+    dw1, db1 = oracle.bwd_weight(g, x, dy, 1.0)
+    dw3, db3 = oracle.bwd_weight(g, x, dy, 0.375)
+    np.testing.assert_array_equal(dw3, 0.375 * dw1)
+    np.testing.assert_array_equal(db3, 0.375 * db1)
+
+
+# ----------------------------------------------------------------------------
+# 9. exhaustive rational-arithmetic loops (a second, differently ordered
+#    implementation in pure Python) over strides 1..4 and pads 0..2
+# ----------------------------------------------------------------------------
+def brute(g, x, w, b, dy):
+    N, C, H, W, K, R, S, sh, sw, ph, pw = g
+    P, Q = out_dims(g)
+    F = Fraction
+    y = {}
+    dx = {(n, c, h, u): F(0) for n in range(N) for c in range(C) for h in range(H) for u in range(W)}
+    dw = {(k, c, r, t): F(0) for k in range(K) for c in range(C) for r in range(R) for t in range(S)}
+    for q in range(Q):                      # deliberately a different loop order
+        for k in range(K):
+            for n in range(N):
+                for p in range(P):
+                    acc = F(float(b[k]))
+                    g_out = F(float(dy[n, k, p, q]))
+                    for t in range(S):
+                        for c in range(C):
+                            for r in range(R):
+                                ih, iw = p * sh + r - ph, q * sw + t - pw
+                                if ih < 0 or iw < 0 or ih >= H or iw >= W:
+                                    continue
+                                xv, wv = F(float(x[n, c, ih, iw])), F(float(w[k, c, r, t]))
+                                acc += xv * wv
+                                dx[n, c, ih, iw] += g_out * wv
+                                dw[k, c, r, t] += g_out * xv
+                    y[n, k, p, q] = acc
+    return y, dx, dw
+
+
+@pytest.mark.parametrize("s", [1, 2, 3, 4])
+@pytest.mark.parametrize("p", [0, 1, 2])
+def test_bruteforce_rational(s, p):
+    N, C, H, W, K, R, S = 2, 2, 7, 6, 2, 3, 2
+    g = (N, C, H, W, K, R, S, s, s, p, p)
+    P, Q = out_dims(g)
+    x = synth.dyadic((N, C, H, W), 71 + s)
+    w = synth.dyadic((K, C, R, S), 72 + p)
+    b = synth.dyadic((K,), 73)
+    dy = synth.dyadic((N, K, P, Q), 74)
+    y, dx, dw = brute(g, x, w, b, dy)
+    yo = oracle.fwd(g, x, w, b)
+    dxo = oracle.bwd_data(g, dy, w)
+    dwo, dbo = oracle.bwd_weight(g, x, dy)
+    for key, v in y.items():
+        assert Fraction(float(yo[key])) == v
+    for key, v in dx.items():
+        assert Fraction(float(dxo[key])) == v
+    for key, v in dw.items():
+        assert Fraction(float(dwo[key])) == v
+    for k in range(K):
+        assert dbo[k] == float(dy[:, k].astype(np.float64).sum())
+
+
+def test_bruteforce_rational_mixed_stride_pad():
+    g = (1, 2, 8, 5, 3, 3, 2, 2, 1, 1, 0)      # stride_h != stride_w, pad_h != pad_w
+    N, C, H, W, K, R, S = g[:7]
+    P, Q = out_dims(g)
+    x = synth.dyadic((N, C, H, W), 81)
+    w = synth.dyadic((K, C, R, S), 82)
+    b = synth.dyadic((K,), 83)
+    dy = synth.dyadic((N, K, P, Q), 84)
+    y, dx, dw = brute(g, x, w, b, dy)
+    yo, dxo = oracle.fwd(g, x, w, b), oracle.bwd_data(g, dy, w)
+    dwo, _ = oracle.bwd_weight(g, x, dy)
+    assert all(Fraction(float(yo[k_])) == v for k_, v in y.items())
+    assert all(Fraction(float(dxo[k_])) == v for k_, v in dx.items())
+    assert all(Fraction(float(dwo[k_])) == v for k_, v in dw.items())
+
+
+# ----------------------------------------------------------------------------
+# 10. closed form: all-ones input and filter count the in-range taps
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("R,s,p", [(3, 1, 1), (5, 1, 2), (3, 2, 1), (11, 4, 2)])
+def test_closed_form_ones(R, s, p):
+    N, C, H, W, K = 1, 4, 25, 23, 2
+    g = geom(N, C, H, W, K, R, R, s, p)
+    P, Q = out_dims(g)
+    y = oracle.fwd(g, np.ones((N, C, H, W), np.float32), np.ones((K, C, R, R), np.float32))
+    rows = np.array([sum(0 <= pp * s - p + r < H for r in range(R)) for pp in range(P)])
+    cols = np.array([sum(0 <= qq * s - p + t < W for t in range(R)) for qq in range(Q)])
+    exp = C * np.outer(rows, cols)
+    for k in range(K):
+        np.testing.assert_array_equal(y[0, k], exp)
+    assert y.max() == C * R * R
+
+
+# ----------------------------------------------------------------------------
+# 11. single-element evaluators agree with the full-tensor loops (two
+#     formulations of bwd_data: scatter vs gather with divisibility tests)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("N,C,H,W,K,R,S,s,p", ADJ)
+def test_elementwise_evaluators(N, C, H, W, K, R, S, s, p):
+    g = geom(N, C, H, W, K, R, S, s, p)
+    P, Q = out_dims(g)
+    x = synth.normal((N, C, H, W), 91)
+    w = synth.normal((K, C, R, S), 92)
+    b = synth.uniform((K,), 93)
+    dy = synth.normal((N, K, P, Q), 94)
+    y = oracle.fwd(g, x, w, b).ravel()
+    dx = oracle.bwd_data(g, dy, w).ravel()
+    dw = oracle.bwd_weight(g, x, dy, 0.5)[0].ravel()
+    rng = np.random.default_rng(7)
+    for full, fn in ((y, lambda i: oracle.fwd_at(g, x, w, b, i)),
+                     (dx, lambda i: oracle.bwd_data_at(g, dy, w, i)),
+                     (dw, lambda i: oracle.bwd_weight_at(g, x, dy, i, 0.5))):
+        idx = rng.integers(0, full.size, size=min(full.size, 200))
+        np.testing.assert_allclose(fn(idx), full[idx], rtol=0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# 12. geometry: output size floors, invalid geometry is refused
+# ----------------------------------------------------------------------------
+def test_output_dims_and_errors():
+    assert oracle.output_dims(geom(1, 3, 224, 224, 64, 11, 11, 4, 2)) == (55, 55)
+    assert oracle.output_dims(geom(1, 3, 231, 231, 96, 11, 11, 4, 0)) == (56, 56)
+    assert oracle.output_dims(geom(1, 96, 24, 24, 256, 5, 5, 1, 0)) == (20, 20)
+    assert oracle.output_dims(geom(1, 3, 224, 224, 64, 3, 3, 1, 1)) == (224, 224)
+    with pytest.raises(ValueError):
+        oracle.output_dims(geom(1, 1, 2, 2, 1, 5, 5, 1, 0))
+    with pytest.raises(ValueError):
+        oracle.output_dims(geom(1, 1, 4, 4, 1, 3, 3, 0, 0))
+
+
+def test_trailing_rows_get_zero_gradient():
+    # H=8, R=3, stride 4, no pad: P=2, windows cover rows 0..6; row 7 is never read
+    g = geom(1, 1, 8, 8, 1, 3, 3, 4, 0)
+    dy = np.ones((1, 1, 2, 2), np.float32)
+    w = np.ones((1, 1, 3, 3), np.float32)
+    dx = oracle.bwd_data(g, dy, w)
+    assert (dx[0, 0, 7, :] == 0).all() and (dx[0, 0, :, 7] == 0).all()
+    assert dx[0, 0, 3, 3] == 0 and dx[0, 0, 0, 0] == 1 and dx[0, 0, 4, 4] == 1
