@@ -1,0 +1,127 @@
+/*
+ * mi355conv -- fp32 NCHW 2-D convolution layer (forward, backward-data,
+ * backward-weight) for AMD Instinct MI355X (gfx950).  Plain C ABI.
+ *
+ * The paper's analysis (Sec. 4.1) singles out the convolution layers as where
+ * convnet training time goes, and its Sec. 4.4 proposes that a framework call a
+ * single hardware-specific `conv` entry point loaded at run time.  This header is
+ * that entry point for one piece of hardware.  The algorithms behind it are the
+ * two the paper recommends in Sec. 4.2: "implicitgemm" (the lowered matrix exists
+ * only on chip) and "winograd" (minimal filtering, for 3x3 stride-1 filters).
+ *
+ * Operation (cross-correlation, zero padding; the element-wise reading of the
+ * Sec. 4.2 "im2col" statement that one image convolved with the weights is one
+ * matrix product W[K x CRS] * lowered(x)[CRS x PQ]):
+ *
+ *   P = floor((H + 2*pad_h - R) / stride_h) + 1,  Q likewise
+ *   y [n,k,p,q] = bias[k] + sum_{c,r,s} x[n,c,p*stride_h-pad_h+r,q*stride_w-pad_w+s] * w[k,c,r,s]
+ *   dx[n,c,h,v] = sum of dy[n,k,p,q] * w[k,c,r,s] over every (k,p,q,r,s) whose tap
+ *                 lands on (h,v)                              (transpose of the above)
+ *   dw[k,c,r,s] = scale * sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*stride_h-pad_h+r,q*stride_w-pad_w+s]
+ *   db[k]       = scale * sum_{n,p,q} dy[n,k,p,q]
+ *
+ * Layout: every tensor is dense, contiguous fp32 in DEVICE memory:
+ *   x, dx : [N][C][H][W]     w, dw : [K][C][R][S]     y, dy : [N][K][P][Q]
+ *   bias, dbias : [K]
+ * Pointers need 4-byte alignment (16-byte alignment of the tensors' bases lets
+ * the library use wider accesses).  Inputs and outputs must not alias.  Each
+ * tensor must have fewer than 2^31 elements.  Dilation 1, one group.
+ *
+ * Ownership: the caller owns every buffer, including the workspace.  The library
+ * allocates no device memory and keeps no state between calls; it only enqueues
+ * kernels on the caller's stream and returns without synchronising.  Concurrent
+ * calls on different streams are safe if their buffers (and workspaces) differ.
+ *
+ * Errors: every function returns CONV2D_OK (0) or a negative code; on error
+ * nothing has been enqueued.  No exceptions cross this boundary.
+ */
+#ifndef MI355CONV_H
+#define MI355CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t N, C, H, W;          /* input batch, channels, height, width          */
+    int32_t K, R, S;             /* filters, filter height, filter width          */
+    int32_t stride_h, stride_w;  /* >= 1                                          */
+    int32_t pad_h, pad_w;        /* >= 0, zeros, applied on both sides            */
+} conv2d_desc;
+
+typedef enum {
+    CONV2D_ALGO_AUTO = 0,        /* library picks (see conv2d_pick_algo)          */
+    CONV2D_ALGO_IGEMM = 1,       /* implicit GEMM on fp32 MFMA, any geometry      */
+    CONV2D_ALGO_WINOGRAD = 2     /* F(2x2,3x3): R=S=3, stride 1 only              */
+} conv2d_algo;
+
+typedef enum {
+    CONV2D_FWD = 0,
+    CONV2D_BWD_DATA = 1,
+    CONV2D_BWD_WEIGHT = 2
+} conv2d_op;
+
+enum {
+    CONV2D_OK = 0,
+    CONV2D_ERR_NULL = -1,        /* null descriptor or required pointer           */
+    CONV2D_ERR_GEOMETRY = -2,    /* non-positive size, stride < 1, pad < 0,
+                                    H+2*pad_h < R (or W), tensor >= 2^31 elements */
+    CONV2D_ERR_ALGO = -3,        /* algorithm cannot do this geometry / unknown   */
+    CONV2D_ERR_WORKSPACE = -4,   /* workspace null or smaller than required       */
+    CONV2D_ERR_LAUNCH = -5       /* HIP reported a launch error                   */
+};
+
+/* Output height P and width Q (Sec. 4.2 lowering: one column per output pixel).
+ * Host-only, touches no device. */
+int conv2d_output_dims(const conv2d_desc *d, int32_t *P, int32_t *Q);
+
+/* The algorithm AUTO resolves to for this op and geometry.  Returns a
+ * conv2d_algo value, or a negative error code. */
+int conv2d_pick_algo(const conv2d_desc *d, conv2d_op op);
+
+/* Bytes of device workspace `op` needs with `algo` (AUTO = whatever AUTO picks).
+ * Returns 0 for an invalid descriptor or unsupported algo.  Host-only.
+ * The workspace holds the re-laid-out filter matrix and gather table of the
+ * implicit GEMM, transformed filters/tiles for Winograd, and the partial sums of
+ * the weight-gradient reduction over the batch. */
+size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo algo);
+
+/* Forward (Torch's updateOutput; Sec. 4.1/4.2).  Overwrites all of y.
+ * bias may be NULL (no bias); it is added in the kernel's epilogue, before the
+ * only store of y ("fully fused kernels", Sec. 4.2 "Neon").
+ * ws: device pointer to >= conv2d_workspace_bytes(d, CONV2D_FWD, algo) bytes,
+ * 256-byte aligned; contents are scratch.  hip_stream: a hipStream_t (NULL = the
+ * default stream). */
+int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias,
+               float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
+
+/* Backward w.r.t. the input (Torch's updateGradInput; the benchmarks of Sec. 3.4
+ * time forward plus backward).  Overwrites all of dx, including pixels no
+ * output window covers (they get 0). */
+int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float *dx,
+                    void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
+
+/* Backward w.r.t. the weights (Torch's accGradParameters), including the
+ * reduction over the batch (Sec. 4.2 "im2col": per-image products are small;
+ * lowering many images into one product is what makes them efficient).
+ * accumulate == 0: dw = scale*grad, dbias = scale*grad_b.
+ * accumulate != 0: dw += scale*grad, dbias += scale*grad_b.
+ * dbias may be NULL (bias gradient not computed).  The result is deterministic:
+ * partial sums are combined in a fixed order, never with atomics. */
+int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy,
+                      float *dw, float *dbias, float scale, int accumulate,
+                      void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
+
+/* Static, never-NULL description of a status code. */
+const char *conv2d_status_string(int status);
+
+/* Library version string (static). */
+const char *conv2d_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355CONV_H */

@@ -1,0 +1,376 @@
+// C-ABI entry points of libmi355conv: argument checks, algorithm choice,
+// workspace layout and kernel launches.  See include/mi355conv.h for the contract.
+
+#include "../../include/mi355conv.h"
+#include "conv_internal.h"
+
+using namespace mi355conv;
+
+namespace {
+
+constexpr int32_t kMaxDim = 16383;          // tap displacements are packed in 16 bits
+constexpr int64_t kMaxElems = (int64_t(1) << 31) - 1;
+
+struct Geom {
+    int32_t N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
+};
+
+int check_desc(const conv2d_desc *d, Geom *g)
+{
+    if (!d) return CONV2D_ERR_NULL;
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->K < 1 || d->R < 1 || d->S < 1)
+        return CONV2D_ERR_GEOMETRY;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return CONV2D_ERR_GEOMETRY;
+    if (d->H > kMaxDim || d->W > kMaxDim || d->R > kMaxDim || d->S > kMaxDim ||
+        d->pad_h > kMaxDim || d->pad_w > kMaxDim || d->stride_h > kMaxDim || d->stride_w > kMaxDim)
+        return CONV2D_ERR_GEOMETRY;
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return CONV2D_ERR_GEOMETRY;
+    g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->K = d->K; g->R = d->R; g->S = d->S;
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    g->Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    if (g->P > kMaxDim || g->Q > kMaxDim) return CONV2D_ERR_GEOMETRY;
+    const int64_t nx = (int64_t)g->N * g->C * g->H * g->W;
+    const int64_t ny = (int64_t)g->N * g->K * g->P * g->Q;
+    const int64_t nw = (int64_t)g->K * g->C * g->R * g->S;
+    if (nx > kMaxElems || ny > kMaxElems || nw > kMaxElems) return CONV2D_ERR_GEOMETRY;
+    // padded pixel counts are also held in 32 bits
+    if ((int64_t)g->N * g->P * g->Q > kMaxElems - 512 || (int64_t)g->N * g->H * g->W > kMaxElems - 512)
+        return CONV2D_ERR_GEOMETRY;
+    return CONV2D_OK;
+}
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+int round_up(int a, int b) { return ceil_div(a, b) * b; }
+
+// Filter-tile choice of the gather kernel: least padded filters, with a small
+// handicap for the narrower tiles (they re-gather the same pixels more often).
+int pick_gather_tile(int filters)
+{
+    static const double handicap[3] = {1.0, 1.03, 1.10};
+    int best = 0;
+    double best_cost = 1e30;
+    for (int t = 0; t < 3; ++t) {
+        const double cost = round_up(filters, gemmconv_filter_tile(t)) * handicap[t];
+        if (cost < best_cost) { best_cost = cost; best = t; }
+    }
+    return best;
+}
+
+int pick_wgrad_tile(int filters)
+{
+    static const double handicap[3] = {1.0, 1.03, 1.10};
+    int best = 0;
+    double best_cost = 1e30;
+    for (int t = 0; t < 3; ++t) {
+        const double cost = round_up(filters, wgrad_filter_tile(t)) * handicap[t];
+        if (cost < best_cost) { best_cost = cost; best = t; }
+    }
+    return best;
+}
+
+// ---- workspace plans -------------------------------------------------------
+struct GatherPlan {
+    int tile, Kpad;             // Kpad: columns of the filter matrix
+    int nphases;                // all phases (may exceed kMaxPhases: launched in groups)
+    int64_t rows_total;         // padded rows over all phases
+    size_t wt_bytes, tab_bytes, total_bytes;
+};
+
+struct PhaseGeom {
+    int r0, nr, t0, nt, rows, rows_pad, in_base_h, in_base_w, a, b, Hs, Ws;
+};
+
+// phase (a, b) of backward-data: output pixels h = a + i*sh, v = b + j*sw
+PhaseGeom bwd_phase(const Geom &g, int a, int b)
+{
+    PhaseGeom p;
+    p.a = a; p.b = b;
+    p.r0 = (a + g.ph) % g.sh;
+    p.t0 = (b + g.pw) % g.sw;
+    p.nr = p.r0 < g.R ? ceil_div(g.R - p.r0, g.sh) : 0;
+    p.nt = p.t0 < g.S ? ceil_div(g.S - p.t0, g.sw) : 0;
+    p.rows = g.K * p.nr * p.nt;
+    p.rows_pad = round_up(p.rows, kDepthTile);
+    p.in_base_h = (a + g.ph - p.r0) / g.sh;
+    p.in_base_w = (b + g.pw - p.t0) / g.sw;
+    p.Hs = a < g.H ? ceil_div(g.H - a, g.sh) : 0;
+    p.Ws = b < g.W ? ceil_div(g.W - b, g.sw) : 0;
+    return p;
+}
+
+GatherPlan plan_fwd(const Geom &g)
+{
+    GatherPlan p;
+    p.tile = pick_gather_tile(g.K);
+    p.Kpad = round_up(g.K, gemmconv_filter_tile(p.tile));
+    p.nphases = 1;
+    p.rows_total = round_up(g.C * g.R * g.S, kDepthTile);
+    p.wt_bytes = align_up((size_t)p.rows_total * p.Kpad * sizeof(float), 256);
+    p.tab_bytes = align_up((size_t)p.rows_total * sizeof(DepthEntry), 256);
+    p.total_bytes = p.wt_bytes + p.tab_bytes;
+    return p;
+}
+
+GatherPlan plan_bwd_data(const Geom &g)
+{
+    GatherPlan p;
+    p.tile = pick_gather_tile(g.C);
+    p.Kpad = round_up(g.C, gemmconv_filter_tile(p.tile));
+    p.nphases = g.sh * g.sw;
+    p.rows_total = 0;
+    for (int a = 0; a < g.sh; ++a)
+        for (int b = 0; b < g.sw; ++b) p.rows_total += bwd_phase(g, a, b).rows_pad;
+    if (p.rows_total == 0) p.rows_total = kDepthTile;
+    p.wt_bytes = align_up((size_t)p.rows_total * p.Kpad * sizeof(float), 256);
+    p.tab_bytes = align_up((size_t)p.rows_total * sizeof(DepthEntry), 256);
+    p.total_bytes = p.wt_bytes + p.tab_bytes;
+    return p;
+}
+
+struct WgradPlan {
+    int tile, tiles_k, tiles_j, splits, chunk, bias_splits;
+    size_t part_bytes, bias_bytes, total_bytes;
+};
+
+WgradPlan plan_wgrad(const Geom &g)
+{
+    WgradPlan p;
+    const int CRS = g.C * g.R * g.S;
+    const int64_t M = (int64_t)g.N * g.P * g.Q;
+    p.tile = pick_wgrad_tile(g.K);
+    p.tiles_k = ceil_div(g.K, wgrad_filter_tile(p.tile));
+    p.tiles_j = ceil_div(CRS, wgrad_col_tile(p.tile));
+    const int tiles = p.tiles_k * p.tiles_j;
+    // enough workgroups for ~4 per compute unit, at least 256 pixels of depth each
+    int64_t want = ceil_div(1024, tiles);
+    const int64_t max_by_depth = (M + 255) / 256;
+    if (want > max_by_depth) want = max_by_depth;
+    if (want < 1) want = 1;
+    int64_t chunk = (M + want - 1) / want;
+    chunk = (chunk + 31) / 32 * 32;
+    p.chunk = (int)chunk;
+    p.splits = (int)((M + chunk - 1) / chunk);
+    p.bias_splits = 1024 / g.K;
+    if (p.bias_splits > g.N) p.bias_splits = g.N;
+    if (p.bias_splits < 1) p.bias_splits = 1;
+    p.part_bytes = align_up((size_t)p.splits * g.K * CRS * sizeof(float), 256);
+    p.bias_bytes = align_up((size_t)p.bias_splits * g.K * sizeof(float), 256);
+    p.total_bytes = p.part_bytes + p.bias_bytes;
+    return p;
+}
+
+int resolve_algo(const Geom &g, conv2d_op op, int algo)
+{
+    (void)op;
+    const bool wino_ok = false && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1;
+    switch (algo) {
+    case CONV2D_ALGO_AUTO: return CONV2D_ALGO_IGEMM;
+    case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;
+    case CONV2D_ALGO_WINOGRAD: return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ERR_ALGO;
+    default: return CONV2D_ERR_ALGO;
+    }
+}
+
+int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+int conv2d_output_dims(const conv2d_desc *d, int32_t *P, int32_t *Q)
+{
+    Geom g;
+    if (!P || !Q) return CONV2D_ERR_NULL;
+    const int rc = check_desc(d, &g);
+    if (rc) return rc;
+    *P = g.P;
+    *Q = g.Q;
+    return CONV2D_OK;
+}
+
+int conv2d_pick_algo(const conv2d_desc *d, conv2d_op op)
+{
+    Geom g;
+    const int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (op != CONV2D_FWD && op != CONV2D_BWD_DATA && op != CONV2D_BWD_WEIGHT) return CONV2D_ERR_ALGO;
+    return resolve_algo(g, op, CONV2D_ALGO_AUTO);
+}
+
+size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo algo)
+{
+    Geom g;
+    if (check_desc(d, &g)) return 0;
+    const int al = resolve_algo(g, op, (int)algo);
+    if (al < 0) return 0;
+    switch (op) {
+    case CONV2D_FWD: return plan_fwd(g).total_bytes;
+    case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
+    case CONV2D_BWD_WEIGHT: return plan_wgrad(g).total_bytes;
+    default: return 0;
+    }
+}
+
+int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
+               void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream)
+{
+    Geom g;
+    int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (!x || !w || !y) return CONV2D_ERR_NULL;
+    const int al = resolve_algo(g, CONV2D_FWD, (int)algo);
+    if (al < 0) return al;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    const GatherPlan p = plan_fwd(g);
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *wt = (float *)ws;
+    DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);
+
+    PrepArgs pa = {};
+    pa.w = w; pa.wt = wt; pa.tab = tab; pa.mode = 0;
+    pa.K = g.K; pa.C = g.C; pa.R = g.R; pa.S = g.S; pa.Kpad = p.Kpad;
+    pa.gather_chan_stride = g.H * g.W; pa.gather_W = g.W;
+    pa.stride_h = g.sh; pa.stride_w = g.sw;
+    pa.rows_total = (int32_t)p.rows_total; pa.nphases = 1;
+    pa.ph[0].row0 = 0; pa.ph[0].rows = g.C * g.R * g.S; pa.ph[0].rows_pad = (int32_t)p.rows_total;
+    rc = launch_status(launch_gemmconv_prep(pa, s));
+    if (rc) return rc;
+
+    GemmConvArgs a = {};
+    a.in = x; a.wt = wt; a.tab = tab; a.bias = bias; a.out = y;
+    a.N = g.N; a.Hin = g.H; a.Win = g.W; a.in_img_stride = g.C * g.H * g.W;
+    a.Kout = g.K; a.Kpad = p.Kpad; a.Hout = g.P; a.Wout = g.Q;
+    a.out_chan_stride = g.P * g.Q; a.out_img_stride = g.K * g.P * g.Q;
+    a.in_step_h = g.sh; a.in_step_w = g.sw; a.out_step_h = 1; a.out_step_w = 1;
+    a.tiles_k = p.Kpad / gemmconv_filter_tile(p.tile);
+    a.tiles_pix = ceil_div(g.N * g.P * g.Q, gemmconv_pixel_tile(p.tile));
+    a.phase[0].row0 = 0;
+    a.phase[0].depth_tiles = (int32_t)(p.rows_total / kDepthTile);
+    a.phase[0].in_base_h = -g.ph; a.phase[0].in_base_w = -g.pw;
+    a.phase[0].out_base_h = 0; a.phase[0].out_base_w = 0;
+    a.phase[0].Hs = g.P; a.phase[0].Ws = g.Q;
+    return launch_status(launch_gemmconv(a, p.tile, 1, s));
+}
+
+int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float *dx, void *ws,
+                    size_t ws_bytes, conv2d_algo algo, void *hip_stream)
+{
+    Geom g;
+    int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (!dy || !w || !dx) return CONV2D_ERR_NULL;
+    const int al = resolve_algo(g, CONV2D_BWD_DATA, (int)algo);
+    if (al < 0) return al;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    const GatherPlan p = plan_bwd_data(g);
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *wt = (float *)ws;
+    DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);
+    const int BN = gemmconv_pixel_tile(p.tile);
+
+    GemmConvArgs a = {};
+    a.in = dy; a.wt = wt; a.tab = tab; a.bias = nullptr; a.out = dx;
+    a.N = g.N; a.Hin = g.P; a.Win = g.Q; a.in_img_stride = g.K * g.P * g.Q;
+    a.Kout = g.C; a.Kpad = p.Kpad; a.Hout = g.H; a.Wout = g.W;
+    a.out_chan_stride = g.H * g.W; a.out_img_stride = g.C * g.H * g.W;
+    a.in_step_h = 1; a.in_step_w = 1; a.out_step_h = g.sh; a.out_step_w = g.sw;
+    a.tiles_k = p.Kpad / gemmconv_filter_tile(p.tile);
+
+    // phases are prepared and launched in groups of at most kMaxPhases
+    int64_t row_cursor = 0;
+    for (int first = 0; first < p.nphases; first += kMaxPhases) {
+        const int cnt = (p.nphases - first) < kMaxPhases ? (p.nphases - first) : kMaxPhases;
+        PrepArgs pa = {};
+        pa.w = w; pa.wt = wt + row_cursor * p.Kpad; pa.tab = tab + row_cursor; pa.mode = 1;
+        pa.K = g.K; pa.C = g.C; pa.R = g.R; pa.S = g.S; pa.Kpad = p.Kpad;
+        pa.gather_chan_stride = g.P * g.Q; pa.gather_W = g.Q;
+        pa.stride_h = g.sh; pa.stride_w = g.sw;
+        pa.nphases = cnt;
+        int32_t group_rows = 0;
+        int tiles_pix = 1;
+        for (int i = 0; i < cnt; ++i) {
+            const int id = first + i;
+            const PhaseGeom pg = bwd_phase(g, id / g.sw, id % g.sw);
+            pa.ph[i].row0 = group_rows; pa.ph[i].rows = pg.rows; pa.ph[i].rows_pad = pg.rows_pad;
+            pa.ph[i].r0 = pg.r0; pa.ph[i].nr = pg.nr; pa.ph[i].t0 = pg.t0; pa.ph[i].nt = pg.nt;
+            a.phase[i].row0 = (int32_t)(row_cursor + group_rows);
+            a.phase[i].depth_tiles = pg.rows_pad / kDepthTile;
+            a.phase[i].in_base_h = pg.in_base_h; a.phase[i].in_base_w = pg.in_base_w;
+            a.phase[i].out_base_h = pg.a; a.phase[i].out_base_w = pg.b;
+            a.phase[i].Hs = pg.Hs; a.phase[i].Ws = pg.Ws;
+            const int tp = ceil_div(g.N * pg.Hs * pg.Ws, BN);
+            if (tp > tiles_pix) tiles_pix = tp;
+            group_rows += pg.rows_pad;
+        }
+        pa.rows_total = group_rows;
+        if (group_rows > 0) {
+            rc = launch_status(launch_gemmconv_prep(pa, s));
+            if (rc) return rc;
+        }
+        a.tiles_pix = tiles_pix;
+        rc = launch_status(launch_gemmconv(a, p.tile, cnt, s));
+        if (rc) return rc;
+        row_cursor += group_rows;
+    }
+    return CONV2D_OK;
+}
+
+int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, float *dw,
+                      float *dbias, float scale, int accumulate, void *ws, size_t ws_bytes,
+                      conv2d_algo algo, void *hip_stream)
+{
+    Geom g;
+    int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (!x || !dy || !dw) return CONV2D_ERR_NULL;
+    const int al = resolve_algo(g, CONV2D_BWD_WEIGHT, (int)algo);
+    if (al < 0) return al;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    const WgradPlan p = plan_wgrad(g);
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *part = (float *)ws;
+    float *bias_part = (float *)((char *)ws + p.part_bytes);
+
+    WgradArgs a = {};
+    a.x = x; a.dy = dy; a.part = part;
+    a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.R = g.R; a.S = g.S; a.P = g.P; a.Q = g.Q;
+    a.stride_h = g.sh; a.stride_w = g.sw; a.pad_h = g.ph; a.pad_w = g.pw;
+    a.PQ = g.P * g.Q; a.CRS = g.C * g.R * g.S; a.M = g.N * g.P * g.Q;
+    a.chunk = p.chunk; a.tiles_k = p.tiles_k; a.tiles_j = p.tiles_j; a.splits = p.splits;
+    a.div_PQ = make_fastdiv((uint32_t)a.PQ);
+    a.div_Q = make_fastdiv((uint32_t)g.Q);
+    a.div_RS = make_fastdiv((uint32_t)(g.R * g.S));
+    a.div_S = make_fastdiv((uint32_t)g.S);
+    rc = launch_status(launch_wgrad(a, p.tile, s));
+    if (rc) return rc;
+    rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * a.CRS, p.splits, scale,
+                                           accumulate, s));
+    if (rc) return rc;
+    if (dbias) {
+        rc = launch_status(launch_bias_grad(dy, bias_part, dbias, g.N, g.K, a.PQ, p.bias_splits,
+                                            scale, accumulate, s));
+        if (rc) return rc;
+    }
+    return CONV2D_OK;
+}
+
+const char *conv2d_status_string(int status)
+{
+    switch (status) {
+    case CONV2D_OK: return "ok";
+    case CONV2D_ERR_NULL: return "null descriptor or pointer";
+    case CONV2D_ERR_GEOMETRY: return "invalid convolution geometry";
+    case CONV2D_ERR_ALGO: return "algorithm not applicable to this geometry";
+    case CONV2D_ERR_WORKSPACE: return "workspace missing or too small";
+    case CONV2D_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown status";
+    }
+}
+
+const char *conv2d_version(void) { return "mi355conv 0.1 (gfx950)"; }
+
+}  // extern "C"

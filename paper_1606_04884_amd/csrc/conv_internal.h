@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of libmi355conv.
+// Nothing here is part of the C ABI (see include/mi355conv.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mi355conv {
+
+// ---------------------------------------------------------------------------
+// Division by a run-time constant for numerators below 2^31 (Granlund &
+// Montgomery round-up method): q = (mulhi(n, mul) + n) >> shift.
+// ---------------------------------------------------------------------------
+struct FastDiv {
+    uint32_t d, mul, shift;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((uint64_t(1) << l) < d) ++l;
+    f.mul = (uint32_t)(((uint64_t(1) << 32) * ((uint64_t(1) << l) - d)) / d + 1);
+    f.shift = l;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv &f)
+{
+    return (__umulhi(n, f.mul) + n) >> f.shift;
+}
+
+// ---------------------------------------------------------------------------
+// Implicit GEMM, "gather" form, used by forward and backward-data.
+//
+//   out[n, ko, h, v] = bias[ko] + sum_d  Wt[d][ko] * in[n, chan(d), ih0+dr(d), iw0+dt(d)]
+//
+// d runs over the rows of the lowered matrix (Sec. 4.2 "implicitgemm": the
+// lowered matrix is only ever formed on chip).  A row is described by a table
+// entry: the element offset chan*Hin*Win + dr*Win + dt and the signed tap
+// displacement (dr, dt) used for the zero-padding test.  Output pixels are
+// enumerated on a sub-grid ("phase"): (oh', ow') -> h = oh'*out_step + out_base,
+// ih0 = oh'*in_step + in_base.  Forward has one phase (out_step 1, in_step =
+// stride, in_base = -pad).  Backward-data has stride_h*stride_w phases, each a
+// stride-1 gather from dy with its own subset of the filter taps.
+// ---------------------------------------------------------------------------
+constexpr int kDepthTile = 16;   // rows of the lowered matrix per main-loop step
+constexpr int kMaxPhases = 16;   // phases per launch
+
+struct DepthEntry {
+    int32_t off;    // chan*Hin*Win + dr*Win + dt   (elements)
+    int32_t drdt;   // (dr << 16) | (dt & 0xffff), both signed 16-bit
+};
+constexpr int32_t kInvalidDr = 0x4000;   // a dr no image height reaches
+
+struct Phase {
+    int32_t row0;          // first row of this phase in Wt / the table
+    int32_t depth_tiles;   // padded rows / kDepthTile
+    int32_t in_base_h, in_base_w;
+    int32_t out_base_h, out_base_w;
+    int32_t Hs, Ws;        // sub-grid size
+};
+
+struct GemmConvArgs {
+    const float *in;
+    const float *wt;           // [rows_total][Kpad]
+    const DepthEntry *tab;     // [rows_total]
+    const float *bias;         // nullable
+    float *out;
+    int32_t N, Hin, Win, in_img_stride;
+    int32_t Kout, Kpad, Hout, Wout, out_chan_stride, out_img_stride;
+    int32_t in_step_h, in_step_w, out_step_h, out_step_w;
+    int32_t tiles_k, tiles_pix;   // grid.x = tiles_k * tiles_pix (max over phases)
+    Phase phase[kMaxPhases];
+};
+
+struct PrepPhase {
+    int32_t row0, rows, rows_pad;
+    int32_t r0, nr, t0, nt;     // backward-data: taps r = r0 + i*stride_h, i < nr
+};
+
+struct PrepArgs {
+    const float *w;
+    float *wt;
+    DepthEntry *tab;
+    int32_t mode;               // 0 forward, 1 backward-data
+    int32_t K, C, R, S, Kpad;   // Kpad = row pitch of wt
+    int32_t gather_chan_stride, gather_W;   // of the tensor the main kernel gathers from
+    int32_t stride_h, stride_w;
+    int32_t rows_total, nphases;
+    PrepPhase ph[kMaxPhases];
+};
+
+// tile = 0: 128 filters x 128 pixels, 1: 64 x 256, 2: 32 x 256
+int gemmconv_filter_tile(int tile);
+int gemmconv_pixel_tile(int tile);
+hipError_t launch_gemmconv_prep(const PrepArgs &a, hipStream_t s);
+hipError_t launch_gemmconv(const GemmConvArgs &a, int tile, int nphases, hipStream_t s);
+
+// ---------------------------------------------------------------------------
+// Backward-weight implicit GEMM:  D[k][j] = sum_m dy[m][k] * lowered(x)[m][j],
+// m = (n,p,q) output pixels (the reduction over the batch), j = (c,r,s).
+// The reduction range is split over `splits` workgroups per output tile; each
+// writes its partial tile to `part` and a second kernel adds them in order.
+// ---------------------------------------------------------------------------
+struct WgradArgs {
+    const float *x;
+    const float *dy;
+    float *part;               // [splits][K][CRS]
+    int32_t N, C, H, W, K, R, S, P, Q;
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t PQ, CRS, M;        // M = N*P*Q
+    int32_t chunk;             // pixels per split (multiple of the depth step)
+    int32_t tiles_k, tiles_j, splits;
+    FastDiv div_PQ, div_Q, div_RS, div_S;
+};
+
+int wgrad_filter_tile(int tile);
+int wgrad_col_tile(int tile);
+hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s);
+// dst[i] = scale * sum_s part[s][i] (+ dst[i] if accumulate)
+hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
+                               float scale, int accumulate, hipStream_t s);
+// db[k] = scale * sum_{n,pq} dy[n,k,pq] (+ db[k]); part holds nsplit*K floats
+hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,
+                            int nsplit, float scale, int accumulate, hipStream_t s);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace mi355conv

@@ -1,0 +1,259 @@
+// Implicit-GEMM convolution on fp32 MFMA for gfx950: forward and backward-data.
+//
+// Sec. 4.2 "implicitgemm" of the paper: lower the convolution onto a matrix
+// product but form the lowered matrix lazily in on-chip memory.  Here the
+// product is  out[Kout x pixels] = Wt^T[Kout x depth] * lowered[depth x pixels]:
+//   * filters are the MFMA "A" rows, output pixels the "B" columns, so that in
+//     the 32x32 accumulator layout the 32 lanes of a half-wave hold 32
+//     consecutive output pixels of one filter: NCHW stores are 128-byte rows;
+//   * the lowered tile (kDepthTile rows x BN pixels) is gathered straight from
+//     the NCHW tensor into LDS, lanes running along the pixel axis (W is the
+//     contiguous axis, so stride-1 gathers coalesce);
+//   * the filter matrix is pre-transposed to [depth][Kpad] so its tiles are
+//     plain 16-byte row reads;
+//   * bias is added in the epilogue before the only store ("fully fused").
+// 256 threads = 4 waves; LDS tiles are double buffered, one barrier per step.
+
+#include "conv_internal.h"
+
+namespace mi355conv {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------ prep ---
+// Writes the filter matrix Wt[row][col] (zero padded) and the gather table.
+__global__ __launch_bounds__(256) void gemmconv_prep_kernel(PrepArgs a)
+{
+    const int64_t total = (int64_t)a.rows_total * a.Kpad;
+    const int RS = a.R * a.S;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int row = (int)(i / a.Kpad);
+        const int col = (int)(i - (int64_t)row * a.Kpad);
+        int p = 0;
+        while (p + 1 < a.nphases && row >= a.ph[p + 1].row0) ++p;
+        const PrepPhase ph = a.ph[p];
+        const int d = row - ph.row0;
+        float v = 0.f;
+        DepthEntry e;
+        e.off = 0;
+        e.drdt = kInvalidDr << 16;
+        if (d < ph.rows) {
+            if (a.mode == 0) {
+                // forward: row d = (c, r, t), column = filter k
+                const int c = d / RS, rt = d - c * RS, r = rt / a.S, t = rt - r * a.S;
+                e.off = c * a.gather_chan_stride + r * a.gather_W + t;
+                e.drdt = (int32_t)(((uint32_t)r << 16) | ((uint32_t)t & 0xffffu));
+                if (col < a.K) v = a.w[(int64_t)col * a.C * RS + d];
+            } else {
+                // backward-data: row d = (k, r', t') of this phase, column = channel c
+                const int nrt = ph.nr * ph.nt;
+                const int k = d / nrt, rt = d - k * nrt, ri = rt / ph.nt, ti = rt - ri * ph.nt;
+                const int r = ph.r0 + ri * a.stride_h, t = ph.t0 + ti * a.stride_w;
+                e.off = k * a.gather_chan_stride - ri * a.gather_W - ti;
+                e.drdt = (int32_t)(((uint32_t)(-ri) << 16) | ((uint32_t)(-ti) & 0xffffu));
+                if (col < a.C) v = a.w[(((int64_t)k * a.C + col) * a.R + r) * a.S + t];
+            }
+        }
+        a.wt[i] = v;
+        if (col == 0) a.tab[row] = e;
+    }
+}
+
+hipError_t launch_gemmconv_prep(const PrepArgs &a, hipStream_t s)
+{
+    const int64_t total = (int64_t)a.rows_total * a.Kpad;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(gemmconv_prep_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ main ---
+// XCD-aware block order: hardware deals consecutive workgroup ids round-robin to
+// the 8 XCDs (each with its own L2).  Remap so every XCD works on one contiguous
+// run of logical tiles; logical order has the filter tile fastest, so the blocks
+// that gather the same pixels run next to each other on the same L2.
+__device__ __forceinline__ int xcd_remap(int id, int nb)
+{
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = id & 7, local = id >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + local;
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
+{
+    constexpr int BK = kDepthTile;
+    constexpr int WAVES_N = BN / WN;
+    static_assert((BM / WM) * WAVES_N == 4, "4 waves per workgroup");
+    constexpr int MI = WM / 32, NI = WN / 32;
+    constexpr int TPP = 256 / BN;            // threads per pixel column: 1 or 2
+    constexpr int B_ROWS = BK / TPP;         // gathered rows per thread
+    constexpr int A_VECS = BK * BM / 4;      // float4 per filter tile
+    constexpr int A_PER_THREAD = (A_VECS + 255) / 256;
+    static_assert(BN >= 64 && 256 % BN == 0, "pixel tile");
+
+    __shared__ float As[2][BK][BM];
+    __shared__ float Bs[2][BK][BN];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const Phase ph = a.phase[blockIdx.y];
+
+    const int logical = xcd_remap(blockIdx.x, gridDim.x);
+    const int kt = logical % a.tiles_k;
+    const int pt = logical / a.tiles_k;
+    const int HWs = ph.Hs * ph.Ws;
+    const int Mpix = a.N * HWs;
+    if (pt * BN >= Mpix) return;             // phase with fewer pixel tiles
+
+    // ---- gather set-up: this thread's pixel column ----
+    const int pcol = tid % BN;
+    const int prow0 = __builtin_amdgcn_readfirstlane(tid / BN);   // wave-uniform (BN >= 64)
+    int gbase = 0, ih0 = -(1 << 24), iw0 = 0;
+    {
+        const int m = pt * BN + pcol;
+        if (m < Mpix) {
+            const int n = m / HWs, rem = m - n * HWs;
+            const int oh = rem / ph.Ws, ow = rem - oh * ph.Ws;
+            ih0 = oh * a.in_step_h + ph.in_base_h;
+            iw0 = ow * a.in_step_w + ph.in_base_w;
+            gbase = n * a.in_img_stride + ih0 * a.Win + iw0;
+        }
+    }
+    const DepthEntry *tab = a.tab + ph.row0;
+    const float *wt = a.wt + (int64_t)ph.row0 * a.Kpad + kt * BM;
+
+    float breg[B_ROWS];
+    floatx4 areg[A_PER_THREAD];
+
+    auto load_tile = [&](int tile) {
+        const int d0 = tile * BK;
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i) {
+            const DepthEntry e = tab[d0 + prow0 + i * TPP];
+            const int dr = e.drdt >> 16;
+            const int dt = (int)(short)(e.drdt & 0xffff);
+            const bool ok = ((unsigned)(ih0 + dr) < (unsigned)a.Hin) &&
+                            ((unsigned)(iw0 + dt) < (unsigned)a.Win);
+            const int idx = ok ? gbase + e.off : 0;
+            const float v = a.in[idx];
+            breg[i] = ok ? v : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) {
+            const int vi = tid + i * 256;
+            if (A_VECS % 256 == 0 || vi < A_VECS) {
+                const int row = vi / (BM / 4), c4 = vi - row * (BM / 4);
+                areg[i] = *reinterpret_cast<const floatx4 *>(wt + (int64_t)(d0 + row) * a.Kpad + c4 * 4);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i) Bs[buf][prow0 + i * TPP][pcol] = breg[i];
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) {
+            const int vi = tid + i * 256;
+            if (A_VECS % 256 == 0 || vi < A_VECS) {
+                const int row = vi / (BM / 4), c4 = vi - row * (BM / 4);
+                *reinterpret_cast<floatx4 *>(&As[buf][row][c4 * 4]) = areg[i];
+            }
+        }
+    };
+
+    floatx16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+    const int wm0 = (wave / WAVES_N) * WM;
+    const int wn0 = (wave % WAVES_N) * WN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    const int ntiles = ph.depth_tiles;
+    if (ntiles > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_tile(t + 1);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float av[MI], bv[NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) av[mi] = As[buf][kk + lhi][wm0 + mi * 32 + l32];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) bv[ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (t + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: bias + store.  Accumulator element v of lane L is
+    // row 8*(v/4) + 4*(L/32) + v%4, column L%32 of the 32x32 tile. ----
+    float bz[MI][16];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+            bz[mi][v] = (a.bias && k < a.Kout) ? a.bias[k] : 0.f;
+        }
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int m = pt * BN + wn0 + ni * 32 + l32;
+        if (m >= Mpix) continue;
+        const int n = m / HWs, rem = m - n * HWs;
+        const int oh = rem / ph.Ws, ow = rem - oh * ph.Ws;
+        const int h = oh * a.out_step_h + ph.out_base_h;
+        const int v_ = ow * a.out_step_w + ph.out_base_w;
+        float *op = a.out + (int64_t)n * a.out_img_stride + h * a.Wout + v_;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                if (k < a.Kout) op[(int64_t)k * a.out_chan_stride] = acc[mi][ni][v] + bz[mi][v];
+            }
+        }
+    }
+}
+
+static const int kFilterTile[3] = {128, 64, 32};
+static const int kPixelTile[3] = {128, 256, 256};
+int gemmconv_filter_tile(int tile) { return kFilterTile[tile]; }
+int gemmconv_pixel_tile(int tile) { return kPixelTile[tile]; }
+
+hipError_t launch_gemmconv(const GemmConvArgs &a, int tile, int nphases, hipStream_t s)
+{
+    const dim3 grid((unsigned)(a.tiles_k * a.tiles_pix), (unsigned)nphases);
+    switch (tile) {
+    case 0:
+        hipLaunchKernelGGL((gemmconv_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, a);
+        break;
+    case 1:
+        hipLaunchKernelGGL((gemmconv_kernel<64, 256, 64, 64>), grid, dim3(256), 0, s, a);
+        break;
+    default:
+        hipLaunchKernelGGL((gemmconv_kernel<32, 256, 32, 64>), grid, dim3(256), 0, s, a);
+        break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace mi355conv

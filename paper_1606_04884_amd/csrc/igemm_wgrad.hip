@@ -1,0 +1,267 @@
+// Backward-weight implicit GEMM on fp32 MFMA for gfx950, plus the reductions
+// across the batch (split partial sums, bias gradient).
+//
+// dw[k][j] = sum_m dy[m][k] * lowered(x)[m][j],  m = (n,p,q),  j = (c,r,s).
+// Sec. 4.2 "im2col" of the paper notes that per-image products are small and
+// that lowering many images into one product is what pays; here the batch and
+// the output pixels together form the reduction axis of ONE product, which is
+// cut into `splits` ranges so that a small filter gradient (e.g. 64 x 576)
+// still fills 256 compute units.  Every workgroup reduces its range in
+// registers and writes a partial tile; split_reduce_kernel adds the partials in
+// a fixed order (deterministic, no atomics).
+//
+// Filters k are the MFMA "A" rows and lowered columns j the "B" columns, so the
+// 32 lanes of a half-wave hold 32 consecutive (c,r,s) of one filter: KCRS stores
+// are contiguous.  Both operands are read with lanes along the pixel axis (the
+// contiguous axis of dy and x) and written to LDS transposed, with an odd row
+// pitch so that neither the transposed writes nor the MFMA operand reads
+// conflict.
+
+#include "conv_internal.h"
+
+namespace mi355conv {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ int xcd_remap_w(int id, int nb)
+{
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = id & 7, local = id >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + local;
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
+{
+    constexpr int BK = 32;                   // pixels per main-loop step
+    constexpr int WAVES_N = BN / WN;
+    static_assert((BM / WM) * WAVES_N == 4, "4 waves per workgroup");
+    constexpr int MI = WM / 32, NI = WN / 32;
+    constexpr int A_PER_THREAD = BM / 8;     // 8 thread rows x 32 pixels
+    constexpr int B_PER_THREAD = BN / 8;
+
+    __shared__ float As[2][BK][BM + 1];
+    __shared__ float Bs[2][BK][BN + 1];
+    __shared__ int2 coltab[BN];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int ntile = a.tiles_k * a.tiles_j;
+    const int logical = xcd_remap_w(blockIdx.x, gridDim.x);
+    const int tile_id = logical % ntile;     // tiles of one split are neighbours
+    const int split = logical / ntile;
+    const int kt = tile_id % a.tiles_k;
+    const int jt = tile_id / a.tiles_k;
+
+    // column table: lowered column j -> element offset and tap (r, t)
+    if (tid < BN) {
+        const int j = jt * BN + tid;
+        int2 e;
+        e.x = 0;
+        e.y = kInvalidDr << 16;
+        if (j < a.CRS) {
+            const int c = (int)fast_div((uint32_t)j, a.div_RS);
+            const int rt = j - c * a.R * a.S;
+            const int r = (int)fast_div((uint32_t)rt, a.div_S);
+            const int t = rt - r * a.S;
+            e.x = c * a.H * a.W + r * a.W + t;
+            e.y = (r << 16) | t;
+        }
+        coltab[tid] = e;
+    }
+    __syncthreads();
+
+    const int pp = tid & 31;       // pixel within the step
+    const int trow = tid >> 5;     // 0..7: first filter / column handled
+    const int m_begin = split * a.chunk;
+    const int m_end = min(a.M, m_begin + a.chunk);
+    const int nsteps = (m_end - m_begin + BK - 1) / BK;
+
+    float areg[A_PER_THREAD], breg[B_PER_THREAD];
+
+    auto load_step = [&](int step) {
+        const int m = m_begin + step * BK + pp;
+        const bool pv = m < m_end;
+        const int mm = pv ? m : 0;
+        const int n = (int)fast_div((uint32_t)mm, a.div_PQ);
+        const int pq = mm - n * a.PQ;
+        const int p = (int)fast_div((uint32_t)pq, a.div_Q);
+        const int q = pq - p * a.Q;
+        // dy[n][k][pq]
+        const int dy_base = n * a.K * a.PQ + pq;
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) {
+            const int k = kt * BM + trow + i * 8;
+            const bool ok = pv && k < a.K;
+            const float v = a.dy[ok ? dy_base + k * a.PQ : 0];
+            areg[i] = ok ? v : 0.f;
+        }
+        const int ih_true = p * a.stride_h - a.pad_h;
+        const int ih0 = pv ? ih_true : -(1 << 24);      // a row no tap can bring in range
+        const int iw0 = q * a.stride_w - a.pad_w;
+        const int x_base = n * a.C * a.H * a.W + ih_true * a.W + iw0;
+#pragma unroll
+        for (int i = 0; i < B_PER_THREAD; ++i) {
+            const int2 e = coltab[trow + i * 8];
+            const int r = e.y >> 16, t = e.y & 0xffff;
+            const bool ok = ((unsigned)(ih0 + r) < (unsigned)a.H) && ((unsigned)(iw0 + t) < (unsigned)a.W);
+            const float v = a.x[ok ? x_base + e.x : 0];
+            breg[i] = ok ? v : 0.f;
+        }
+    };
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) As[buf][pp][trow + i * 8] = areg[i];
+#pragma unroll
+        for (int i = 0; i < B_PER_THREAD; ++i) Bs[buf][pp][trow + i * 8] = breg[i];
+    };
+
+    floatx16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+    const int wm0 = (wave / WAVES_N) * WM;
+    const int wn0 = (wave % WAVES_N) * WN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    if (nsteps > 0) {
+        load_step(0);
+        store_step(0);
+    }
+    __syncthreads();
+    for (int st = 0; st < nsteps; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nsteps) load_step(st + 1);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float av[MI], bv[NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) av[mi] = As[buf][kk + lhi][wm0 + mi * 32 + l32];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) bv[ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (st + 1 < nsteps) store_step(buf ^ 1);
+        __syncthreads();
+    }
+
+    // partial tile -> part[split][k][j]
+    float *out = a.part + (int64_t)split * a.K * a.CRS;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int j = jt * BN + wn0 + ni * 32 + l32;
+        if (j >= a.CRS) continue;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                if (k < a.K) out[(int64_t)k * a.CRS + j] = acc[mi][ni][v];
+            }
+    }
+}
+
+static const int kWFilterTile[3] = {128, 64, 32};
+static const int kWColTile[3] = {128, 128, 128};
+int wgrad_filter_tile(int tile) { return kWFilterTile[tile]; }
+int wgrad_col_tile(int tile) { return kWColTile[tile]; }
+
+hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s)
+{
+    const dim3 grid((unsigned)(a.tiles_k * a.tiles_j * a.splits));
+    switch (tile) {
+    case 0:
+        hipLaunchKernelGGL((wgrad_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, a);
+        break;
+    case 1:
+        hipLaunchKernelGGL((wgrad_kernel<64, 128, 32, 64>), grid, dim3(256), 0, s, a);
+        break;
+    default:
+        hipLaunchKernelGGL((wgrad_kernel<32, 128, 32, 32>), grid, dim3(256), 0, s, a);
+        break;
+    }
+    return hipGetLastError();
+}
+
+// dst[i] = scale * (part[0][i] + part[1][i] + ...) (+ dst[i])
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ part,
+                                                           float *__restrict__ dst, int64_t count,
+                                                           int splits, float scale, int accumulate)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        float s = 0.f;
+        for (int k = 0; k < splits; ++k) s += part[(int64_t)k * count + i];
+        s *= scale;
+        dst[i] = accumulate ? dst[i] + s : s;
+    }
+}
+
+hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
+                               float scale, int accumulate, hipStream_t s)
+{
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, dst,
+                       count, splits, scale, accumulate);
+    return hipGetLastError();
+}
+
+// Bias gradient, stage 1: block (k, split) sums dy[n][k][:] over its images.
+__global__ __launch_bounds__(256) void bias_grad_partial_kernel(const float *__restrict__ dy,
+                                                                float *__restrict__ part, int N,
+                                                                int K, int PQ, int nsplit)
+{
+    __shared__ float red[256];
+    const int k = blockIdx.x, sp = blockIdx.y;
+    const int per = (N + nsplit - 1) / nsplit;
+    const int n0 = sp * per, n1 = min(N, n0 + per);
+    float s = 0.f;
+    for (int n = n0; n < n1; ++n) {
+        const float *p = dy + ((int64_t)n * K + k) * PQ;
+        for (int i = threadIdx.x; i < PQ; i += 256) s += p[i];
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[sp * K + k] = red[0];
+}
+
+__global__ __launch_bounds__(256) void bias_grad_final_kernel(const float *__restrict__ part,
+                                                              float *__restrict__ db, int K,
+                                                              int nsplit, float scale, int accumulate)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    float s = 0.f;
+    for (int i = 0; i < nsplit; ++i) s += part[i * K + k];
+    s *= scale;
+    db[k] = accumulate ? db[k] + s : s;
+}
+
+hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,
+                            int nsplit, float scale, int accumulate, hipStream_t s)
+{
+    hipLaunchKernelGGL(bias_grad_partial_kernel, dim3((unsigned)K, (unsigned)nsplit), dim3(256), 0,
+                       s, dy, part, N, K, PQ, nsplit);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s,
+                       part, db, K, nsplit, scale, accumulate);
+    return hipGetLastError();
+}
+
+}  // namespace mi355conv

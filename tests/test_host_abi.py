@@ -1,0 +1,98 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol,
+and its host-side logic (shape maths, workspace sizing, argument validation)
+behaves as include/mi355conv.h states.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1606_04884_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mi355conv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv2d_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_binding_has_same_names():
+    for n in declared_symbols():
+        assert callable(getattr(B, n))
+
+
+@pytest.mark.parametrize("geom,pq", [
+    ((128, 3, 224, 224, 64, 11, 11, 4, 4, 2, 2), (55, 55)),
+    ((128, 3, 231, 231, 96, 11, 11, 4, 4, 0, 0), (56, 56)),
+    ((128, 96, 24, 24, 256, 5, 5, 1, 1, 0, 0), (20, 20)),
+    ((64, 512, 14, 14, 512, 3, 3, 1, 1, 1, 1), (14, 14)),
+    ((1, 1, 7, 9, 1, 3, 2, 2, 3, 1, 0), (4, 3)),
+])
+def test_output_dims(geom, pq):
+    assert B.conv2d_output_dims(geom) == pq
+
+
+@pytest.mark.parametrize("geom", [
+    (0, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1), (1, 3, 8, 8, 4, 3, 3, 0, 1, 1, 1),
+    (1, 3, 8, 8, 4, 3, 3, 1, 1, -1, 1), (1, 3, 2, 2, 4, 5, 5, 1, 1, 0, 0),
+    (1, 3, 8, 8, 0, 3, 3, 1, 1, 1, 1), (1, 3, 20000, 8, 4, 3, 3, 1, 1, 1, 1),
+    (4096, 1024, 64, 64, 4, 3, 3, 1, 1, 1, 1),      # x has 2^34 elements
+])
+def test_bad_geometry_is_refused(geom):
+    with pytest.raises(B.Conv2dError) as e:
+        B.conv2d_output_dims(geom)
+    assert e.value.status == -2
+    for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+        assert B.conv2d_workspace_bytes(geom, op) == 0
+
+
+def test_null_and_workspace_errors_enqueue_nothing():
+    lib = B.load()
+    d = B.make_desc((2, 3, 16, 16, 8, 3, 3, 1, 1, 1, 1))
+    assert lib.conv2d_fwd(None, 1, 1, None, 1, 1, 1 << 20, 0, None) == -1
+    assert lib.conv2d_fwd(C.byref(d), None, 1, None, 1, 1, 1 << 20, 0, None) == -1
+    assert lib.conv2d_bwd_data(C.byref(d), 1, None, 1, 1, 1 << 20, 0, None) == -1
+    assert lib.conv2d_bwd_weight(C.byref(d), 1, 1, None, None, 1.0, 0, 1, 1 << 20, 0, None) == -1
+    # workspace: missing, or one byte short
+    for op, call in ((B.OP_FWD, lambda ws, n: lib.conv2d_fwd(C.byref(d), 1, 1, None, 1, ws, n, 0, None)),
+                     (B.OP_BWD_DATA, lambda ws, n: lib.conv2d_bwd_data(C.byref(d), 1, 1, 1, ws, n, 0, None)),
+                     (B.OP_BWD_WEIGHT, lambda ws, n: lib.conv2d_bwd_weight(C.byref(d), 1, 1, 1, None, 1.0, 0, ws, n, 0, None))):
+        need = B.conv2d_workspace_bytes(d, op)
+        assert need > 0
+        assert call(None, need) == -4
+        assert call(1, need - 1) == -4
+    # unknown algorithm / Winograd on a geometry it cannot do
+    assert lib.conv2d_fwd(C.byref(d), 1, 1, None, 1, 1, 1 << 20, 7, None) == -3
+    d5 = B.make_desc((2, 3, 16, 16, 8, 5, 5, 1, 1, 2, 2))
+    assert lib.conv2d_fwd(C.byref(d5), 1, 1, None, 1, 1, 1 << 30, B.ALGO_WINOGRAD, None) == -3
+    d2 = B.make_desc((2, 3, 16, 16, 8, 3, 3, 2, 2, 1, 1))
+    assert lib.conv2d_bwd_data(C.byref(d2), 1, 1, 1, 1, 1 << 30, B.ALGO_WINOGRAD, None) == -3
+    assert B.conv2d_workspace_bytes(d5, B.OP_FWD, B.ALGO_WINOGRAD) == 0
+
+
+def test_status_strings_and_version():
+    seen = set()
+    for s in (0, -1, -2, -3, -4, -5, -99):
+        t = B.conv2d_status_string(s)
+        assert t
+        seen.add(t)
+    assert len(seen) == 7
+    assert "gfx950" in B.conv2d_version()
+
+
+def test_pick_algo_is_consistent_with_workspace():
+    for geom in ((64, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1), (8, 3, 32, 32, 16, 5, 5, 2, 2, 2, 2)):
+        for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+            algo = B.conv2d_pick_algo(geom, op)
+            assert algo in (B.ALGO_IGEMM, B.ALGO_WINOGRAD)
+            assert B.conv2d_workspace_bytes(geom, op, algo) == B.conv2d_workspace_bytes(geom, op, B.ALGO_AUTO)
