@@ -83,6 +83,15 @@ __device__ __forceinline__ int xcd_remap(int id, int nb)
     return xcd * per + (xcd < rem ? xcd : rem) + local;
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads already in flight
+// (the register prefetch of a later tile) are not waited for.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
 {
@@ -130,39 +139,40 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
 
     float breg[B_ROWS];
     floatx4 areg[A_PER_THREAD];
+    uint32_t bmask = 0;    // bit i: gathered element i is inside the image
+    DepthEntry ent[B_ROWS];   // table rows of the tile being gathered (wave-uniform: SGPRs)
 
-    auto load_tile = [&](int tile) {
-        const int d0 = tile * BK;
+    // This thread gathers rows prow0*B_ROWS .. +B_ROWS-1 of a depth tile: one
+    // contiguous run of table entries, fetched with wide scalar loads.
+    auto table_fetch = [&](int tile) {
 #pragma unroll
-        for (int i = 0; i < B_ROWS; ++i) {
-            const DepthEntry e = tab[d0 + prow0 + i * TPP];
-            const int dr = e.drdt >> 16;
-            const int dt = (int)(short)(e.drdt & 0xffff);
-            const bool ok = ((unsigned)(ih0 + dr) < (unsigned)a.Hin) &&
-                            ((unsigned)(iw0 + dt) < (unsigned)a.Win);
-            const int idx = ok ? gbase + e.off : 0;
-            const float v = a.in[idx];
-            breg[i] = ok ? v : 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int vi = tid + i * 256;
-            if (A_VECS % 256 == 0 || vi < A_VECS) {
-                const int row = vi / (BM / 4), c4 = vi - row * (BM / 4);
-                areg[i] = *reinterpret_cast<const floatx4 *>(wt + (int64_t)(d0 + row) * a.Kpad + c4 * 4);
-            }
+        for (int i = 0; i < B_ROWS; ++i) ent[i] = tab[tile * BK + prow0 * B_ROWS + i];
+    };
+    auto gather_issue = [&](int i) {
+        const DepthEntry e = ent[i];
+        const int dr = e.drdt >> 16;
+        const int dt = (int)(short)(e.drdt & 0xffff);
+        const bool ok = ((unsigned)(ih0 + dr) < (unsigned)a.Hin) &&
+                        ((unsigned)(iw0 + dt) < (unsigned)a.Win);
+        const int idx = ok ? gbase + e.off : 0;
+        breg[i] = a.in[idx];
+        bmask = (bmask & ~(1u << i)) | (ok ? (1u << i) : 0u);
+    };
+    auto filter_issue = [&](int tile, int i) {
+        const int vi = tid + i * 256;
+        if (A_VECS % 256 == 0 || vi < A_VECS) {
+            const int row = vi / (BM / 4), c4 = vi - row * (BM / 4);
+            areg[i] = *reinterpret_cast<const floatx4 *>(wt + (int64_t)(tile * BK + row) * a.Kpad + c4 * 4);
         }
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < B_ROWS; ++i) Bs[buf][prow0 + i * TPP][pcol] = breg[i];
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int vi = tid + i * 256;
-            if (A_VECS % 256 == 0 || vi < A_VECS) {
-                const int row = vi / (BM / 4), c4 = vi - row * (BM / 4);
-                *reinterpret_cast<floatx4 *>(&As[buf][row][c4 * 4]) = areg[i];
-            }
+    auto store_b = [&](int buf, int i) {
+        Bs[buf][prow0 * B_ROWS + i][pcol] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
+    };
+    auto store_a = [&](int buf, int i) {
+        const int vi = tid + i * 256;
+        if (A_VECS % 256 == 0 || vi < A_VECS) {
+            const int row = vi / (BM / 4), c4 = vi - row * (BM / 4);
+            *reinterpret_cast<floatx4 *>(&As[buf][row][c4 * 4]) = areg[i];
         }
     };
 
@@ -178,30 +188,84 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
     const int wn0 = (wave % WAVES_N) * WN;
     const int l32 = lane & 31, lhi = lane >> 5;
 
+    float av[2][MI], bv[2][NI];
+    auto read_ops = [&](int buf, int kk, int slot) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) av[slot][mi] = As[buf][kk + lhi][wm0 + mi * 32 + l32];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bv[slot][ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
+    };
+
+    // Software pipeline.  A depth tile is NSTEP MFMA steps of depth 2; each step
+    // issues NMF MFMAs, and between consecutive MFMAs sits one "slot" of other
+    // work, so that this work issues while the matrix pipe is busy:
+    //   step 0     : registers holding tile t+1 go to the other LDS buffer; the
+    //                table rows of tile t+2 are fetched (scalar)
+    //   steps 1..4 : the global loads of tile t+2 are issued into those registers
+    //   every step : operands of the next step are read from LDS first; the last
+    //                step waits for its own operand reads, passes the workgroup
+    //                barrier and reads the first operands of tile t+1, so barrier
+    //                and LDS latency sit under that step's MFMAs.
+    // The barrier orders LDS traffic only; global loads stay in flight across it.
+    // Tile indices past the end are clamped (loading or storing a tile nobody
+    // consumes is harmless), which keeps the loop free of branches.
+    constexpr int NSTEP = BK / 2;
+    constexpr int NMF = MI * NI;
+    constexpr int GSLOTS = 4 * NMF;          // slots of steps 1..4
     const int ntiles = ph.depth_tiles;
+    const int last = ntiles - 1;
     if (ntiles > 0) {
-        load_tile(0);
-        store_tile(0);
+        table_fetch(0);
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i) gather_issue(i);
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) filter_issue(0, i);
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i) store_b(0, i);
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) store_a(0, i);
+        const int t1 = last < 1 ? last : 1;
+        table_fetch(t1);
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i) gather_issue(i);
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) filter_issue(t1, i);
     }
-    __syncthreads();
+    lds_barrier();
+    if (ntiles > 0) read_ops(0, 0, 0);
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
-        if (t + 1 < ntiles) load_tile(t + 1);
+        const int t2 = (t + 2 < ntiles) ? t + 2 : last;
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float av[MI], bv[NI];
+        for (int j = 0; j < NSTEP; ++j) {
+            const int cur = j & 1, nxt = cur ^ 1;
+            if (j + 1 < NSTEP) {
+                read_ops(buf, 2 * (j + 1), nxt);
+            } else {
+                lds_barrier();
+                read_ops(buf ^ 1, 0, nxt);
+            }
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) av[mi] = As[buf][kk + lhi][wm0 + mi * 32 + l32];
+            for (int q = 0; q < NMF; ++q) {
+                if (j == 0) {
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) bv[ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
+                    for (int i = 0; i < B_ROWS; ++i)
+                        if (i * NMF / B_ROWS == q) store_b(buf ^ 1, i);
+                    if (q < A_PER_THREAD) store_a(buf ^ 1, q);
+                    if (q == NMF - 1) table_fetch(t2);
+                } else if (j <= 4) {
+                    const int sidx = (j - 1) * NMF + q;
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+                    for (int i = 0; i < B_ROWS; ++i)
+                        if (i * GSLOTS / B_ROWS == sidx) gather_issue(i);
+                    if (sidx < A_PER_THREAD) filter_issue(t2, sidx);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                    av[cur][q / NI], bv[cur][q % NI], acc[q / NI][q % NI], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
-        __syncthreads();
     }
 
     // ---- epilogue: bias + store.  Accumulator element v of lane L is

@@ -80,10 +80,13 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
     const int nsteps = (m_end - m_begin + BK - 1) / BK;
 
     float areg[A_PER_THREAD], breg[B_PER_THREAD];
+    uint32_t amask = 0, bmask = 0;   // validity bits, applied when the values reach LDS
 
     auto load_step = [&](int step) {
         const int m = m_begin + step * BK + pp;
         const bool pv = m < m_end;
+        amask = 0;
+        bmask = 0;
         const int mm = pv ? m : 0;
         const int n = (int)fast_div((uint32_t)mm, a.div_PQ);
         const int pq = mm - n * a.PQ;
@@ -95,8 +98,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
         for (int i = 0; i < A_PER_THREAD; ++i) {
             const int k = kt * BM + trow + i * 8;
             const bool ok = pv && k < a.K;
-            const float v = a.dy[ok ? dy_base + k * a.PQ : 0];
-            areg[i] = ok ? v : 0.f;
+            areg[i] = a.dy[ok ? dy_base + k * a.PQ : 0];
+            amask |= ok ? (1u << i) : 0u;
         }
         const int ih_true = p * a.stride_h - a.pad_h;
         const int ih0 = pv ? ih_true : -(1 << 24);      // a row no tap can bring in range
@@ -107,15 +110,15 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
             const int2 e = coltab[trow + i * 8];
             const int r = e.y >> 16, t = e.y & 0xffff;
             const bool ok = ((unsigned)(ih0 + r) < (unsigned)a.H) && ((unsigned)(iw0 + t) < (unsigned)a.W);
-            const float v = a.x[ok ? x_base + e.x : 0];
-            breg[i] = ok ? v : 0.f;
+            breg[i] = a.x[ok ? x_base + e.x : 0];
+            bmask |= ok ? (1u << i) : 0u;
         }
     };
     auto store_step = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) As[buf][pp][trow + i * 8] = areg[i];
+        for (int i = 0; i < A_PER_THREAD; ++i) As[buf][pp][trow + i * 8] = ((amask >> i) & 1u) ? areg[i] : 0.f;
 #pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) Bs[buf][pp][trow + i * 8] = breg[i];
+        for (int i = 0; i < B_PER_THREAD; ++i) Bs[buf][pp][trow + i * 8] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
     };
 
     floatx16 acc[MI][NI];
@@ -138,18 +141,27 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
     for (int st = 0; st < nsteps; ++st) {
         const int buf = st & 1;
         if (st + 1 < nsteps) load_step(st + 1);
+        float av[2][MI], bv[2][NI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) av[0][mi] = As[buf][lhi][wm0 + mi * 32 + l32];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bv[0][ni] = Bs[buf][lhi][wn0 + ni * 32 + l32];
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            float av[MI], bv[NI];
+            const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
+            if (kk + 2 < BK) {
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) av[mi] = As[buf][kk + lhi][wm0 + mi * 32 + l32];
+                for (int mi = 0; mi < MI; ++mi) av[nxt][mi] = As[buf][kk + 2 + lhi][wm0 + mi * 32 + l32];
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) bv[ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
+                for (int ni = 0; ni < NI; ++ni) bv[nxt][ni] = Bs[buf][kk + 2 + lhi][wn0 + ni * 32 + l32];
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the LDS prefetch ahead of the MFMAs
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mi], bv[cur][ni], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (st + 1 < nsteps) store_step(buf ^ 1);
         __syncthreads();
