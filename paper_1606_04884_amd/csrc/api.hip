@@ -142,12 +142,28 @@ WgradPlan plan_wgrad(const Geom &g)
     p.tiles_k = ceil_div(g.K, wgrad_filter_tile(p.tile));
     p.tiles_j = ceil_div(CRS, wgrad_col_tile(p.tile));
     const int tiles = p.tiles_k * p.tiles_j;
-    // enough workgroups for ~4 per compute unit, at least 256 pixels of depth each
-    int64_t want = ceil_div(1024, tiles);
-    const int64_t max_by_depth = (M + 255) / 256;
-    if (want > max_by_depth) want = max_by_depth;
-    if (want < 1) want = 1;
-    int64_t chunk = (M + want - 1) / want;
+    // Choose the number of ranges the reduction axis is cut into.  All workgroups
+    // take equally long, so the grid should fill the machine's resident slots
+    // (256 compute units x 2 workgroups) a whole number of times; more splits
+    // also mean more partial tiles to write and add up again.  Minimise an
+    // estimate of MFMA time / slot efficiency + partial-sum traffic time.
+    const double slots = 512.0;
+    const double flops = 2.0 * (double)M * g.K * CRS;
+    int64_t max_splits = (M + 255) / 256;            // at least 256 pixels of depth each
+    if (max_splits > 4096) max_splits = 4096;
+    if (max_splits < 1) max_splits = 1;
+    int best = 1;
+    double best_t = 1e300;
+    for (int64_t sp = 1; sp <= max_splits; ++sp) {
+        const double blocks = (double)tiles * sp;
+        const double rounds = (double)((int64_t)((blocks + slots - 1) / slots));
+        const double eff = blocks / (rounds * slots);
+        const double t_mfma = flops / (0.65 * 155e12) / eff;
+        const double t_part = 2.0 * sp * g.K * (double)CRS * 4.0 / 3.0e12;
+        const double t = t_mfma + t_part;
+        if (t < best_t) { best_t = t; best = (int)sp; }
+    }
+    int64_t chunk = (M + best - 1) / best;
     chunk = (chunk + 31) / 32 * 32;
     p.chunk = (int)chunk;
     p.splits = (int)((M + chunk - 1) / chunk);

@@ -30,6 +30,14 @@ __device__ __forceinline__ int xcd_remap_w(int id, int nb)
     return xcd * per + (xcd < rem ? xcd : rem) + local;
 }
 
+// Workgroup barrier that orders LDS traffic only (global loads stay in flight).
+__device__ __forceinline__ void lds_barrier_w()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
 {
@@ -81,44 +89,45 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
 
     float areg[A_PER_THREAD], breg[B_PER_THREAD];
     uint32_t amask = 0, bmask = 0;   // validity bits, applied when the values reach LDS
+    int2 col[B_PER_THREAD];          // this thread's lowered columns, fixed for the whole kernel
+#pragma unroll
+    for (int i = 0; i < B_PER_THREAD; ++i) col[i] = coltab[trow + i * 8];
 
-    auto load_step = [&](int step) {
+    // per-step pixel state of the tile being loaded
+    bool pv = false;
+    int dy_base = 0, x_base = 0, ih0 = 0, iw0 = 0;
+    auto pixel_setup = [&](int step) {
         const int m = m_begin + step * BK + pp;
-        const bool pv = m < m_end;
-        amask = 0;
-        bmask = 0;
+        pv = m < m_end;
         const int mm = pv ? m : 0;
         const int n = (int)fast_div((uint32_t)mm, a.div_PQ);
         const int pq = mm - n * a.PQ;
         const int p = (int)fast_div((uint32_t)pq, a.div_Q);
         const int q = pq - p * a.Q;
-        // dy[n][k][pq]
-        const int dy_base = n * a.K * a.PQ + pq;
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int k = kt * BM + trow + i * 8;
-            const bool ok = pv && k < a.K;
-            areg[i] = a.dy[ok ? dy_base + k * a.PQ : 0];
-            amask |= ok ? (1u << i) : 0u;
-        }
+        dy_base = n * a.K * a.PQ + pq;                   // dy[n][k][pq]
         const int ih_true = p * a.stride_h - a.pad_h;
-        const int ih0 = pv ? ih_true : -(1 << 24);      // a row no tap can bring in range
-        const int iw0 = q * a.stride_w - a.pad_w;
-        const int x_base = n * a.C * a.H * a.W + ih_true * a.W + iw0;
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) {
-            const int2 e = coltab[trow + i * 8];
-            const int r = e.y >> 16, t = e.y & 0xffff;
-            const bool ok = ((unsigned)(ih0 + r) < (unsigned)a.H) && ((unsigned)(iw0 + t) < (unsigned)a.W);
-            breg[i] = a.x[ok ? x_base + e.x : 0];
-            bmask |= ok ? (1u << i) : 0u;
-        }
+        ih0 = pv ? ih_true : -(1 << 24);                 // a row no tap can bring in range
+        iw0 = q * a.stride_w - a.pad_w;
+        x_base = n * a.C * a.H * a.W + ih_true * a.W + iw0;
     };
-    auto store_step = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) As[buf][pp][trow + i * 8] = ((amask >> i) & 1u) ? areg[i] : 0.f;
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) Bs[buf][pp][trow + i * 8] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
+    auto load_a = [&](int i) {
+        const int k = kt * BM + trow + i * 8;
+        const bool ok = pv && k < a.K;
+        areg[i] = a.dy[ok ? dy_base + k * a.PQ : 0];
+        amask = (amask & ~(1u << i)) | (ok ? (1u << i) : 0u);
+    };
+    auto load_b = [&](int i) {
+        const int2 e = col[i];
+        const int r = e.y >> 16, t = e.y & 0xffff;
+        const bool ok = ((unsigned)(ih0 + r) < (unsigned)a.H) && ((unsigned)(iw0 + t) < (unsigned)a.W);
+        breg[i] = a.x[ok ? x_base + e.x : 0];
+        bmask = (bmask & ~(1u << i)) | (ok ? (1u << i) : 0u);
+    };
+    auto store_a = [&](int buf, int i) {
+        As[buf][pp][trow + i * 8] = ((amask >> i) & 1u) ? areg[i] : 0.f;
+    };
+    auto store_b = [&](int buf, int i) {
+        Bs[buf][pp][trow + i * 8] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
     };
 
     floatx16 acc[MI][NI];
@@ -133,38 +142,71 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
     const int wn0 = (wave % WAVES_N) * WN;
     const int l32 = lane & 31, lhi = lane >> 5;
 
+    float av[2][MI], bv[2][NI];
+    auto read_ops = [&](int buf, int kk, int slot) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) av[slot][mi] = As[buf][kk + lhi][wm0 + mi * 32 + l32];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bv[slot][ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
+    };
+
+    // Software pipeline, same shape as the gather kernel's: per 32-pixel tile,
+    // 16 MFMA steps; between consecutive MFMAs one slot of other work.
+    //   steps 0..1  : registers holding tile t+1 go to the other LDS buffer
+    //   step  2     : pixel coordinates of tile t+2
+    //   steps 3..10 : global loads of tile t+2
+    //   last step   : LDS-only barrier, then the first operands of tile t+1
+    constexpr int NSTEP = BK / 2;
+    constexpr int NMF = MI * NI;
+    constexpr int NEL = A_PER_THREAD + B_PER_THREAD;
+    constexpr int SSLOTS = 2 * NMF, LSLOTS = 8 * NMF;
+    auto load_el = [&](int e) { if (e < A_PER_THREAD) load_a(e); else load_b(e - A_PER_THREAD); };
+    auto store_el = [&](int buf, int e) { if (e < A_PER_THREAD) store_a(buf, e); else store_b(buf, e - A_PER_THREAD); };
+
     if (nsteps > 0) {
-        load_step(0);
-        store_step(0);
+        pixel_setup(0);
+#pragma unroll
+        for (int e = 0; e < NEL; ++e) load_el(e);
+#pragma unroll
+        for (int e = 0; e < NEL; ++e) store_el(0, e);
+        pixel_setup(1);          // past the end: every element masked off
+#pragma unroll
+        for (int e = 0; e < NEL; ++e) load_el(e);
     }
-    __syncthreads();
+    lds_barrier_w();
+    if (nsteps > 0) read_ops(0, 0, 0);
     for (int st = 0; st < nsteps; ++st) {
         const int buf = st & 1;
-        if (st + 1 < nsteps) load_step(st + 1);
-        float av[2][MI], bv[2][NI];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) av[0][mi] = As[buf][lhi][wm0 + mi * 32 + l32];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bv[0][ni] = Bs[buf][lhi][wn0 + ni * 32 + l32];
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
-            if (kk + 2 < BK) {
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi) av[nxt][mi] = As[buf][kk + 2 + lhi][wm0 + mi * 32 + l32];
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) bv[nxt][ni] = Bs[buf][kk + 2 + lhi][wn0 + ni * 32 + l32];
+        for (int j = 0; j < NSTEP; ++j) {
+            const int cur = j & 1, nxt = cur ^ 1;
+            if (j + 1 < NSTEP) {
+                read_ops(buf, 2 * (j + 1), nxt);
+            } else {
+                lds_barrier_w();
+                read_ops(buf ^ 1, 0, nxt);
             }
-            __builtin_amdgcn_sched_barrier(0);   // keep the LDS prefetch ahead of the MFMAs
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
+            for (int q = 0; q < NMF; ++q) {
+                if (j < 2) {
+                    const int sidx = j * NMF + q;
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mi], bv[cur][ni], acc[mi][ni], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                    for (int e = 0; e < NEL; ++e)
+                        if (e * SSLOTS / NEL == sidx) store_el(buf ^ 1, e);
+                } else if (j == 2) {
+                    if (q == 0) pixel_setup(st + 2);
+                } else if (j <= 10) {
+                    const int sidx = (j - 3) * NMF + q;
+#pragma unroll
+                    for (int e = 0; e < NEL; ++e)
+                        if (e * LSLOTS / NEL == sidx) load_el(e);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                    av[cur][q / NI], bv[cur][q % NI], acc[q / NI][q % NI], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (st + 1 < nsteps) store_step(buf ^ 1);
-        __syncthreads();
     }
 
     // partial tile -> part[split][k][j]
