@@ -1,0 +1,75 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (same entry points, same AUTO algorithm choice).
+The full tensors are too large for the oracle's full loops, so the oracle
+computes randomly sampled output elements one by one (each output element is an
+independent sum, so a sampled oracle is still the exact definition)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_1606_04884_amd import binding as B          # noqa: E402
+from paper_1606_04884_amd import synth                 # noqa: E402
+import oracle                                          # noqa: E402
+from gpu_util import TOL_IGEMM, TOL_WINOGRAD           # noqa: E402
+
+# every layer of every full-size configuration (AlexNet, VGG-16, inception, Overfeat)
+CASES = [(cfg, li) for cfg in (1, 2, 3, 4) for li in range(len(synth.config_layers(cfg)))]
+MAC_BUDGET = 1.5e9          # oracle multiply-adds per sampled tensor
+
+
+def tol_for(geom, op):
+    return TOL_WINOGRAD if B.conv2d_pick_algo(geom, op) == B.ALGO_WINOGRAD else TOL_IGEMM
+
+
+@pytest.mark.parametrize("cfg,li", CASES, ids=["cfg%d_layer%d" % c for c in CASES])
+def test_fullsize_sampled(cfg, li):
+    L = synth.config_layers(cfg)[li]
+    geom = L.desc()
+    print("case", cfg, li, L, flush=True)
+    P, Q = B.conv2d_output_dims(geom)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.layer_seed(cfg, li, 0))
+    x = torch.randn((L.N, L.C, L.H, L.W), device=dev, generator=gen)
+    w = torch.randn((L.K, L.C, L.R, L.S), device=dev, generator=gen) * (2.0 / (L.C * L.R * L.S)) ** 0.5
+    b = (torch.rand((L.K,), device=dev, generator=gen) - 0.5) * 0.2
+    dy = torch.randn((L.N, L.K, P, Q), device=dev, generator=gen)
+    y = torch.full_like(dy, float("nan"))
+    dx = torch.full_like(x, float("nan"))
+    dw = torch.full_like(w, float("nan"))
+    db = torch.full_like(b, float("nan"))
+    B.conv2d_fwd(geom, x, w, b, y)
+    B.conv2d_bwd_data(geom, dy, w, dx)
+    B.conv2d_bwd_weight(geom, x, dy, dw, db)
+    torch.cuda.synchronize()
+    hx, hw, hb, hdy = (t.cpu().numpy() for t in (x, w, b, dy))
+    rng = np.random.default_rng(1000 * cfg + li)
+
+    def check(name, got_t, n_total, macs_per_elem, fn, tol):
+        n = int(max(64, min(50000, MAC_BUDGET // max(1, macs_per_elem))))
+        idx = rng.integers(0, n_total, size=n)
+        ref = fn(idx)
+        got = got_t.reshape(-1)[torch.from_numpy(idx).to(dev)].cpu().numpy().astype(np.float64)
+        # the tolerance is relative to max|ref| of the tensor; the sample's max
+        # is a lower bound of it, so this check is at least as strict
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(got - ref).max())
+        assert np.isfinite(got).all(), name
+        assert err <= tol * scale, "%s: err %.3e vs %.3e*%.3e" % (name, err, tol, scale)
+
+    check("y", y, y.numel(), L.C * L.R * L.S, lambda i: oracle.fwd_at(geom, hx, hw, hb, i),
+          tol_for(geom, B.OP_FWD))
+    check("dx", dx, dx.numel(), L.K * L.R * L.S, lambda i: oracle.bwd_data_at(geom, hdy, hw, i),
+          tol_for(geom, B.OP_BWD_DATA))
+    check("dw", dw, dw.numel(), L.N * P * Q, lambda i: oracle.bwd_weight_at(geom, hx, hdy, i),
+          tol_for(geom, B.OP_BWD_WEIGHT))
+    # bias gradient: exact definition is cheap (a plain sum), take all of it
+    ref_db = hdy.astype(np.float64).sum(axis=(0, 2, 3))
+    err = np.abs(db.cpu().numpy().astype(np.float64) - ref_db).max()
+    assert err <= TOL_IGEMM * np.abs(ref_db).max()
+    # no element of any output was left unwritten
+    for t in (y, dx, dw, db):
+        assert not torch.isnan(t).any()
