@@ -176,12 +176,59 @@ WgradPlan plan_wgrad(const Geom &g)
     return p;
 }
 
+// ---- Winograd F(2x2,3x3) ---------------------------------------------------
+struct WinoPlan {
+    int Cin, Kout, Cpad, Kpad, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, tiles_t, tiles_k;
+    size_t total_bytes;
+};
+
+// The fused kernel handles 3x3 stride-1 layers whose reduction channels are a
+// multiple of its 8-channel chunk and whose gathered tensor fits 32-bit byte
+// offsets.  Backward-data is the forward kernel on dy with pad' = 2 - pad.
+bool wino_applicable(const Geom &g, conv2d_op op)
+{
+    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1) return false;
+    if (op == CONV2D_BWD_WEIGHT) return false;
+    if (g.ph > 2 || g.pw > 2) return false;
+    const int cin = op == CONV2D_FWD ? g.C : g.K;
+    if (cin % wino_chan_chunk() != 0) return false;
+    const int64_t in_elems = op == CONV2D_FWD ? (int64_t)g.N * g.C * g.H * g.W
+                                              : (int64_t)g.N * g.K * g.P * g.Q;
+    return in_elems * 4 < (int64_t(1) << 31);   // buffer offsets: see winograd.hip
+}
+
+WinoPlan plan_wino(const Geom &g, conv2d_op op)
+{
+    WinoPlan p;
+    const bool fwd = op == CONV2D_FWD;
+    p.Cin = fwd ? g.C : g.K;
+    p.Kout = fwd ? g.K : g.C;
+    p.Hin = fwd ? g.H : g.P;
+    p.Win = fwd ? g.W : g.Q;
+    p.Hout = fwd ? g.P : g.H;
+    p.Wout = fwd ? g.Q : g.W;
+    p.pad_h = fwd ? g.ph : 2 - g.ph;
+    p.pad_w = fwd ? g.pw : 2 - g.pw;
+    p.Cpad = p.Cin;
+    p.Kpad = round_up(p.Kout, wino_filter_tile());
+    p.TH = ceil_div(p.Hout, 2);
+    p.TW = ceil_div(p.Wout, 2);
+    p.T = g.N * p.TH * p.TW;
+    p.tiles_t = ceil_div(p.T, wino_tile_block());
+    p.tiles_k = p.Kpad / wino_filter_tile();
+    p.total_bytes = align_up((size_t)16 * p.Cpad * p.Kpad * sizeof(float), 256);
+    return p;
+}
+
 int resolve_algo(const Geom &g, conv2d_op op, int algo)
 {
-    (void)op;
-    const bool wino_ok = false && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1;
+    const bool wino_ok = wino_applicable(g, op);
     switch (algo) {
-    case CONV2D_ALGO_AUTO: return CONV2D_ALGO_IGEMM;
+    case CONV2D_ALGO_AUTO: {
+        // Winograd pays once the 16 GEMMs are deep enough to amortise the transforms
+        const int cin = op == CONV2D_FWD ? g.C : g.K;
+        return (wino_ok && cin >= 32) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
+    }
     case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;
     case CONV2D_ALGO_WINOGRAD: return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ERR_ALGO;
     default: return CONV2D_ERR_ALGO;
@@ -189,6 +236,27 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
 }
 
 int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
+
+int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias,
+             float *out, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const WinoPlan p = plan_wino(g, op);
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *U = (float *)ws;
+    int rc = launch_status(launch_wino_filter(w, U, g.K, g.C, p.Cin, p.Kout, p.Cpad, p.Kpad,
+                                              op == CONV2D_FWD ? 0 : 1, s));
+    if (rc) return rc;
+    WinoArgs a = {};
+    a.in = in; a.U = U; a.bias = bias; a.out = out;
+    a.N = g.N; a.Cin = p.Cin; a.Cpad = p.Cpad; a.Hin = p.Hin; a.Win = p.Win;
+    a.Kout = p.Kout; a.Kpad = p.Kpad; a.Hout = p.Hout; a.Wout = p.Wout;
+    a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T;
+    a.tiles_t = p.tiles_t; a.tiles_k = p.tiles_k;
+    a.in_bytes = (int32_t)((int64_t)g.N * p.Cin * p.Hin * p.Win * 4);
+    a.u_bytes = (int32_t)((int64_t)16 * p.Cpad * p.Kpad * 4);
+    a.vec2 = (p.Wout % 2 == 0) && (((uintptr_t)out & 7) == 0);
+    return launch_status(launch_wino_fused(a, s));
+}
 
 }  // namespace
 
@@ -220,6 +288,7 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     if (check_desc(d, &g)) return 0;
     const int al = resolve_algo(g, op, (int)algo);
     if (al < 0) return 0;
+    if (al == CONV2D_ALGO_WINOGRAD) return plan_wino(g, op).total_bytes;
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
@@ -238,6 +307,7 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
     const int al = resolve_algo(g, CONV2D_FWD, (int)algo);
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (al == CONV2D_ALGO_WINOGRAD) return run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s);
 
     const GatherPlan p = plan_fwd(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
@@ -280,6 +350,7 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
     const int al = resolve_algo(g, CONV2D_BWD_DATA, (int)algo);
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (al == CONV2D_ALGO_WINOGRAD) return run_wino(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
 
     const GatherPlan p = plan_bwd_data(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;

@@ -127,6 +127,31 @@ hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int
 hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,
                             int nsplit, float scale, int accumulate, hipStream_t s);
 
+// ---------------------------------------------------------------------------
+// Winograd F(2x2,3x3), fused (see winograd.hip).  `in` is the tensor the 4x4
+// patches are read from (x for forward, dy for backward-data), U the
+// transformed filters [16][Cpad][Kpad].
+// ---------------------------------------------------------------------------
+struct WinoArgs {
+    const float *in;
+    const float *U;
+    const float *bias;       // nullable
+    float *out;
+    int32_t N, Cin, Cpad, Hin, Win, Kout, Kpad, Hout, Wout;
+    int32_t pad_h, pad_w;    // patch origin = 2*tile - pad
+    int32_t TH, TW, T;       // tiles per image (rows, cols), tiles in total
+    int32_t tiles_t, tiles_k;
+    int32_t vec2;            // output rows can be stored as aligned float2
+    int32_t in_bytes, u_bytes;   // sizes of `in` and `U` (both below 2^31)
+};
+
+int wino_filter_tile();
+int wino_tile_block();
+int wino_chan_chunk();
+hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
+                              int Kpad, int mode, hipStream_t s);
+hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace mi355conv

@@ -1,0 +1,357 @@
+// Winograd F(2x2,3x3) convolution on fp32 MFMA for gfx950: forward and
+// backward-data of 3x3 stride-1 layers, fused into one kernel per call.
+//
+// Sec. 4.2 "Winograd" of the paper: minimal filtering cuts the multiplications
+// of a 3x3 convolution by 2.25 but "still relies on GEMM"; Sec. 4.2 "Neon" adds
+// that the fast implementations fuse the transforms into that GEMM.  The paper
+// prints no transform matrices; the standard ones for the points {0,1,-1,inf}
+// are used:
+//   B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1]     (input tile d, 4x4)
+//   G   = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]          (filter g, 3x3)
+//   A^T = [1 1 1 0; 0 1 -1 -1]                         (output, 2x2)
+//   Y = A^T [ sum_c (G g G^T) .* (B^T d B) ] A
+// The sum over c at each of the 16 positions is a GEMM  M[pos] = U[pos]^T V[pos]
+// with U[pos] : [C x K] (filters), V[pos] : [C x tiles].
+//
+// One workgroup (4 waves) owns 64 filters x 64 tiles at all 16 positions: each
+// wave keeps 16 accumulator tiles of 32x32 (256 accumulator registers), so the
+// output transform needs no exchange: the 16 values of one (filter, tile) sit in
+// the same lane and register index of the 16 accumulators.  Per 8-channel chunk
+// the input patches are loaded from NCHW, transformed in registers and written
+// to LDS as V; the pre-transformed filters U are copied to LDS; nothing
+// transformed ever goes to HBM except U (16*C*K floats, written once per call).
+// One wave per SIMD, so the whole latency hiding is the in-wave software
+// pipeline: LDS operand prefetch one position pair ahead, LDS writes of chunk
+// t+1 and global loads of chunk t+2 interleaved between the MFMAs of chunk t,
+// LDS-only barrier hidden under the last position pair.
+
+#include "conv_internal.h"
+
+namespace mi355conv {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// --------------------------------------------------------- filter transform
+// U[pos][c][k] (k contiguous, zero padded to Cpad x Kpad).
+// mode 0: forward, filters g = w[k][c].  mode 1: backward-data, the layer that
+// maps dy to dx has filters g'[c][k][r][s] = w[k][c][2-r][2-s]; its "k" is c.
+__global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w,
+                                                          float *__restrict__ U, int K, int C,
+                                                          int Cin, int Kout, int Cpad, int Kpad,
+                                                          int mode)
+{
+    const int64_t total = (int64_t)Cpad * Kpad;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int ci = (int)(i / Kpad), ko = (int)(i - (int64_t)ci * Kpad);
+        float g[3][3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) g[r][s] = 0.f;
+        if (ci < Cin && ko < Kout) {
+            if (mode == 0) {
+                const float *p = w + ((int64_t)ko * C + ci) * 9;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) g[r][s] = p[r * 3 + s];
+            } else {
+                const float *p = w + ((int64_t)ci * C + ko) * 9;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) g[r][s] = p[(2 - r) * 3 + (2 - s)];
+            }
+        }
+        float t[4][3];
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            t[0][s] = g[0][s];
+            t[1][s] = 0.5f * (g[0][s] + g[1][s] + g[2][s]);
+            t[2][s] = 0.5f * (g[0][s] - g[1][s] + g[2][s]);
+            t[3][s] = g[2][s];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float u0 = t[r][0];
+            const float u1 = 0.5f * (t[r][0] + t[r][1] + t[r][2]);
+            const float u2 = 0.5f * (t[r][0] - t[r][1] + t[r][2]);
+            const float u3 = t[r][2];
+            U[(int64_t)(4 * r + 0) * total + i] = u0;
+            U[(int64_t)(4 * r + 1) * total + i] = u1;
+            U[(int64_t)(4 * r + 2) * total + i] = u2;
+            U[(int64_t)(4 * r + 3) * total + i] = u3;
+        }
+    }
+}
+
+hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
+                              int Kpad, int mode, hipStream_t s)
+{
+    int64_t blocks = ((int64_t)Cpad * Kpad + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, K, C, Cin,
+                       Kout, Cpad, Kpad, mode);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------- fused kernel
+__device__ __forceinline__ void lds_barrier_wg()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ int xcd_remap_wino(int id, int nb)
+{
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = id & 7, local = id >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + local;
+}
+
+constexpr int kWinoKB = 64, kWinoTB = 64, kWinoCB = 8;
+constexpr int kWinoLdsBytes = 2 * 16 * kWinoCB * (kWinoKB + kWinoTB) * (int)sizeof(float);
+
+__global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
+{
+    constexpr int KB = kWinoKB, TB = kWinoTB, CB = kWinoCB;
+    extern __shared__ float lds[];
+    // Us[buf][pos][c][k], Vs[buf][pos][c][tile]
+    float *const Us = lds;
+    float *const Vs = lds + 2 * 16 * CB * KB;
+    auto us_at = [&](int buf, int pos, int c, int k) -> float & { return Us[((buf * 16 + pos) * CB + c) * KB + k]; };
+    auto vs_at = [&](int buf, int pos, int c, int t) -> float & { return Vs[((buf * 16 + pos) * CB + c) * TB + t]; };
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // filter tile slowest: an XCD's contiguous run of blocks shares one slice of U
+    const int logical = xcd_remap_wino(blockIdx.x, gridDim.x);
+    const int tt = logical % a.tiles_t;
+    const int kt = logical / a.tiles_t;
+
+    // ---- this thread's input tile (fixed for the whole kernel) ----
+    // Patch elements are fetched with buffer loads: the per-thread byte offset of
+    // each element (inside channel 0 of its image) never changes, the channel
+    // advances through the scalar offset, and elements outside the image carry
+    // an offset beyond the buffer, for which the hardware range check returns 0:
+    // zero padding costs no instruction.
+    const int HW = a.Hin * a.Win;
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ursrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.U, 0, a.u_bytes, 0x00020000);
+    uint32_t eoff[16];
+    {
+        const int tile = tt * TB + lane;
+        const bool tv = tile < a.T;
+        const int tl = tv ? tile : 0;
+        const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
+        const int th = rem / a.TW, tw = rem - th * a.TW;
+        const int ih0 = 2 * th - a.pad_h, iw0 = 2 * tw - a.pad_w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool ok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin &&
+                                (unsigned)(iw0 + j) < (unsigned)a.Win;
+                const int idx = n * a.Cin * HW + (ih0 + i) * a.Win + (iw0 + j);
+                eoff[4 * i + j] = ok ? (uint32_t)idx * 4u : 0x80000000u;
+            }
+    }
+    // wave w transforms channels w and w+4 of every chunk
+    const int x_chunk = CB * HW * 4;                  // bytes per chunk of channels
+    const int xs0 = wave * HW * 4, xs1 = xs0 + 4 * HW * 4;
+
+    // U tile copy: 8 float4 per thread per chunk; vector v = tid + 256*i ->
+    // pos = 2*i + tid/128, row = (tid%128)/16, column quad = tid%16
+    const int u_row = (tid & 127) >> 4, u_c4 = tid & 15, u_p0 = tid >> 7;
+    uint32_t uoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        uoff[i] = (uint32_t)((((int64_t)(2 * i + u_p0) * a.Cpad + u_row) * a.Kpad + kt * KB + u_c4 * 4) * 4);
+    const int u_chunk = CB * a.Kpad * 4;
+
+    float xr[2][16];
+    floatx4 ur[8];
+
+    auto load_x = [&](int it, int e, int chunk) {
+        xr[it][e] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[e], chunk * x_chunk + (it ? xs1 : xs0), 0));
+    };
+    auto load_u = [&](int i, int chunk) {
+        ur[i] = __builtin_bit_cast(floatx4,
+                                   __builtin_amdgcn_raw_buffer_load_b128(ursrc, uoff[i], chunk * u_chunk, 0));
+    };
+
+    // input transform of item `it`, in two stages of four pieces each
+    float tr[2][16];
+    auto xform_col = [&](int it, int j) {     // stage 1 on patch column j: t = B^T d
+        const float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
+        tr[it][0 + j] = d0 - d2;
+        tr[it][4 + j] = d1 + d2;
+        tr[it][8 + j] = d2 - d1;
+        tr[it][12 + j] = d1 - d3;
+    };
+    auto xform_row_store = [&](int buf, int it, int i) {   // stage 2 on row i: V = t B, to LDS
+        const float t0 = tr[it][4 * i + 0], t1 = tr[it][4 * i + 1], t2 = tr[it][4 * i + 2], t3 = tr[it][4 * i + 3];
+        const int c = wave + 4 * it;
+        vs_at(buf, 4 * i + 0, c, lane) = t0 - t2;
+        vs_at(buf, 4 * i + 1, c, lane) = t1 + t2;
+        vs_at(buf, 4 * i + 2, c, lane) = t2 - t1;
+        vs_at(buf, 4 * i + 3, c, lane) = t1 - t3;
+    };
+    auto store_u = [&](int buf, int i) {
+        *reinterpret_cast<floatx4 *>(&us_at(buf, 2 * i + u_p0, u_row, u_c4 * 4)) = ur[i];
+    };
+
+    floatx16 acc[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+    float ao[2][2][4], bo[2][2][4];     // [register set][position of the pair][k-step]
+    auto read_pair = [&](int buf, int pair, int set) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                ao[set][u][ks] = us_at(buf, 2 * pair + u, 2 * ks + lhi, wm0 + l32);
+                bo[set][u][ks] = vs_at(buf, 2 * pair + u, 2 * ks + lhi, wn0 + l32);
+            }
+    };
+
+    const int nchunks = a.Cin / CB;
+    const int lastc = nchunks - 1;
+    // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 into registers ----
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) load_x(it, e, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) load_u(i, 0);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xform_col(it, j);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xform_row_store(0, it, i);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) store_u(0, i);
+    {
+        const int c1 = lastc < 1 ? lastc : 1;
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) load_x(it, e, c1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_u(i, c1);
+    }
+    lds_barrier_wg();
+    read_pair(0, 0, 0);
+
+    for (int t = 0; t < nchunks; ++t) {
+        const int buf = t & 1;
+        const int t2 = (t + 2 < nchunks) ? t + 2 : lastc;
+#pragma unroll
+        for (int pair = 0; pair < 8; ++pair) {
+            const int cur = pair & 1, nxt = cur ^ 1;
+            if (pair + 1 < 8) {
+                read_pair(buf, pair + 1, nxt);
+            } else {
+                lds_barrier_wg();
+                read_pair(buf ^ 1, 0, nxt);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int s = pair * 8 + q;      // MFMA slot 0..63 of this chunk
+                // slots 0..15: transform + LDS write of the two items of chunk t+1
+                if (s < 16) {
+                    const int it = s >> 3, piece = s & 7;
+                    if (piece < 4) xform_col(it, piece); else xform_row_store(buf ^ 1, it, piece - 4);
+                } else if (s < 24) {
+                    store_u(buf ^ 1, s - 16);
+                } else if (s < 56) {
+                    // global loads of chunk t+2, in the order they are consumed
+                    // (item, patch column, row)
+                    const int l = s - 24, it = l >> 4, j = (l >> 2) & 3, i = l & 3;
+                    load_x(it, 4 * i + j, t2);
+                } else {
+                    load_u(s - 56, t2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const int u = q & 1, ks = q >> 1;
+                acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ao[cur][u][ks], bo[cur][u][ks],
+                                                                          acc[2 * pair + u], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // ---- epilogue: output transform in registers, bias, store ----
+    // accumulator element v of lane L: filter row 8*(v/4) + 4*(L/32) + v%4,
+    // tile column L%32 of this wave's 32x32 sub-tile
+    const int tile = tt * TB + wn0 + l32;
+    if (tile >= a.T) return;
+    const int n = tile / (a.TH * a.TW), rem = tile - n * (a.TH * a.TW);
+    const int th = rem / a.TW, tw = rem - th * a.TW;
+    const int oh = 2 * th, ow = 2 * tw;
+    const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+    const int HWo = a.Hout * a.Wout;
+    float *obase = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int k = kt * KB + wm0 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+        if (k >= a.Kout) continue;
+        float s0[4], s1[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+            s0[j] = m0 + m1 + m2;
+            s1[j] = m1 - m2 - m3;
+        }
+        const float bz = a.bias ? a.bias[k] : 0.f;
+        const float y00 = s0[0] + s0[1] + s0[2] + bz, y01 = s0[1] - s0[2] - s0[3] + bz;
+        const float y10 = s1[0] + s1[1] + s1[2] + bz, y11 = s1[1] - s1[2] - s1[3] + bz;
+        float *o = obase + (int64_t)k * HWo;
+        if (a.vec2) {
+            *reinterpret_cast<float2 *>(o) = make_float2(y00, y01);
+            if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10, y11);
+        } else {
+            o[0] = y00;
+            if (col1) o[1] = y01;
+            if (row1) {
+                o[a.Wout] = y10;
+                if (col1) o[a.Wout + 1] = y11;
+            }
+        }
+    }
+}
+
+int wino_filter_tile() { return kWinoKB; }
+int wino_tile_block() { return kWinoTB; }
+int wino_chan_chunk() { return kWinoCB; }
+
+hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s)
+{
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWinoLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(wino_fused_kernel, dim3((unsigned)(a.tiles_t * a.tiles_k)), dim3(256),
+                       kWinoLdsBytes, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace mi355conv

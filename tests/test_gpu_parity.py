@@ -125,3 +125,43 @@ def test_large_split_reduction_depth():
     dw, db = oracle.bwd_weight(geom, x, dy)
     assert max_err_ratio(got["dw"], dw) <= TOL_IGEMM
     assert max_err_ratio(got["db"], db) <= TOL_IGEMM
+
+
+# ---------------------------------------------------------------------------
+# Winograd F(2x2,3x3) path (3x3, stride 1): bar 1e-3 * max|ref|
+# ---------------------------------------------------------------------------
+WINO_SHAPES = [
+    G(2, 8, 16, 16, 8, 3, 3, 1, 1),
+    G(3, 16, 19, 23, 40, 3, 3, 1, 1),        # odd map: half-filled edge tiles
+    G(2, 64, 14, 14, 96, 3, 3, 1, 1),
+    G(4, 24, 13, 13, 72, 3, 3, 1, 1),        # AlexNet-sized odd map
+    G(1, 136, 12, 12, 296, 3, 3, 1, 1),      # K and tiles not multiples of 64
+    G(2, 32, 9, 9, 64, 3, 3, 1, 0),          # no padding
+    G(2, 16, 10, 7, 16, 3, 3, 1, 2),         # full padding
+    (2, 8, 11, 12, 24, 3, 3, 1, 1, 0, 2),    # pad_h != pad_w
+    G(5, 40, 28, 28, 136, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("geom", WINO_SHAPES, ids=[("x".join(map(str, g))) for g in WINO_SHAPES])
+def test_winograd_parity(geom):
+    from gpu_util import TOL_WINOGRAD
+    x, w, b, dy = random_layer(geom, 2000 + sum(geom))
+    print("geom", geom, flush=True)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, passes=("fwd", "bwd_data"))
+    ref = {"y": oracle.fwd(geom, x, w, b), "dx": oracle.bwd_data(geom, dy, w)}
+    for name in ("y", "dx"):
+        assert np.isfinite(got[name]).all(), name
+        r = max_err_ratio(got[name], ref[name])
+        assert r <= TOL_WINOGRAD, "%s: max err ratio %.3e" % (name, r)
+
+
+def test_winograd_refused_where_it_does_not_apply():
+    dev = torch.device("cuda:0")
+    geom = G(1, 4, 8, 8, 8, 3, 3, 1, 1)      # C not a multiple of the channel chunk
+    x = torch.zeros((1, 4, 8, 8), device=dev)
+    w = torch.zeros((8, 4, 3, 3), device=dev)
+    y = torch.zeros((1, 8, 8, 8), device=dev)
+    with pytest.raises(B.Conv2dError) as e:
+        B.conv2d_fwd(geom, x, w, None, y, algo=B.ALGO_WINOGRAD, ws=B.alloc_workspace(1 << 20))
+    assert e.value.status == -3

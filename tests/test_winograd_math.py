@@ -1,0 +1,80 @@
+"""The Winograd F(2x2,3x3) transform matrices the HIP path uses, checked on the
+CPU against direct correlation.  The paper (Sec. 4.2 "Winograd") names the
+algorithm but prints no matrices; these are the standard ones for the points
+{0, 1, -1, inf}.  Exact rational arithmetic: the identity must hold exactly."""
+import os
+from fractions import Fraction as F
+
+import numpy as np
+
+BT = [[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]]
+G = [[1, 0, 0], [F(1, 2), F(1, 2), F(1, 2)], [F(1, 2), F(-1, 2), F(1, 2)], [0, 0, 1]]
+AT = [[1, 1, 1, 0], [0, 1, -1, -1]]
+
+
+def mm(a, b):
+    return [[sum(F(a[i][k]) * F(b[k][j]) for k in range(len(b))) for j in range(len(b[0]))]
+            for i in range(len(a))]
+
+
+def tr(a):
+    return [list(r) for r in zip(*a)]
+
+
+def parse(path):
+    out = {}
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            k, *v = line.split()
+            out[k] = [F(x) for x in v]
+    return out
+
+
+def test_golden_1d(golden_dir):
+    g = parse(os.path.join(golden_dir, "winograd_f2x3_1d.txt"))
+    Gg = [sum(F(G[i][k]) * g["g"][k] for k in range(3)) for i in range(4)]
+    Btd = [sum(F(BT[i][k]) * g["d"][k] for k in range(4)) for i in range(4)]
+    prod = [x * y for x, y in zip(Gg, Btd)]
+    y = [sum(F(AT[i][k]) * prod[k] for k in range(4)) for i in range(2)]
+    assert Gg == g["Gg"] and Btd == g["Btd"] and prod == g["prod"] and y == g["y"]
+    direct = [sum(g["d"][i + k] * g["g"][k] for k in range(3)) for i in range(2)]
+    assert y == direct
+
+
+def test_2d_identity_exact():
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        C = 3
+        d = rng.integers(-9, 10, size=(C, 4, 4))
+        g = rng.integers(-9, 10, size=(C, 3, 3))
+        M = [[F(0)] * 4 for _ in range(4)]
+        for c in range(C):
+            U = mm(mm(G, g[c].tolist()), tr(G))
+            V = mm(mm(BT, d[c].tolist()), tr(BT))
+            for i in range(4):
+                for j in range(4):
+                    M[i][j] += U[i][j] * V[i][j]
+        Y = mm(mm(AT, M), tr(AT))
+        for p in range(2):
+            for q in range(2):
+                direct = sum(int(d[c, p + r, q + s]) * int(g[c, r, s])
+                             for c in range(C) for r in range(3) for s in range(3))
+                assert Y[p][q] == direct
+
+
+def test_backward_data_is_forward_with_rotated_filter():
+    """dx = correlation of dy (zero-extended by 2-pad) with the 180-degree rotated,
+    k<->c swapped filter: the identity the Winograd backward-data call relies on."""
+    import oracle
+    from paper_1606_04884_amd import synth
+    for pad in (0, 1, 2):
+        N, C, H, W, K = 1, 2, 6, 7, 3
+        geom = (N, C, H, W, K, 3, 3, 1, 1, pad, pad)
+        P, Q = oracle.output_dims(geom)
+        dy = synth.dyadic((N, K, P, Q), 5 + pad)
+        w = synth.dyadic((K, C, 3, 3), 9)
+        dx = oracle.bwd_data(geom, dy, w)
+        wr = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+        g2 = (N, K, P, Q, C, 3, 3, 1, 1, 2 - pad, 2 - pad)
+        np.testing.assert_array_equal(oracle.fwd(g2, dy, wr), dx)
