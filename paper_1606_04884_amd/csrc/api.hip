@@ -188,8 +188,13 @@ struct WinoPlan {
 bool wino_applicable(const Geom &g, conv2d_op op)
 {
     if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1) return false;
-    if (op == CONV2D_BWD_WEIGHT) return false;
     if (g.ph > 2 || g.pw > 2) return false;
+    if (op == CONV2D_BWD_WEIGHT) {
+        // 64x64 output tiles handled as two halves of 32: C and K multiples of 32
+        if (g.C % 32 != 0 || g.K % 32 != 0) return false;
+        return (int64_t)g.N * g.C * g.H * g.W * 4 < (int64_t(1) << 31) &&
+               (int64_t)g.N * g.K * g.P * g.Q * 4 < (int64_t(1) << 31);
+    }
     const int cin = op == CONV2D_FWD ? g.C : g.K;
     if (cin % wino_chan_chunk() != 0) return false;
     const int64_t in_elems = op == CONV2D_FWD ? (int64_t)g.N * g.C * g.H * g.W
@@ -220,12 +225,54 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
     return p;
 }
 
+struct WinoWgradPlan {
+    int TH, TW, T, tiles_k, tiles_c, splits, tiles_per_split, bias_splits;
+    size_t part_bytes, bias_bytes, total_bytes;
+};
+
+WinoWgradPlan plan_wino_wgrad(const Geom &g)
+{
+    WinoWgradPlan p;
+    p.TH = ceil_div(g.P, 2);
+    p.TW = ceil_div(g.Q, 2);
+    p.T = g.N * p.TH * p.TW;
+    p.tiles_k = ceil_div(g.K, wino_wgrad_tile());
+    p.tiles_c = ceil_div(g.C, wino_wgrad_tile());
+    const int tiles = p.tiles_k * p.tiles_c;
+    const int step = wino_wgrad_step();
+    // one workgroup per compute unit is resident: fill 256 slots a whole number of times
+    const double slots = 256.0;
+    int max_splits = ceil_div(p.T, 8 * step);       // at least 8 steps each
+    if (max_splits > 2048) max_splits = 2048;
+    if (max_splits < 1) max_splits = 1;
+    const double flops = 32.0 * (double)p.T * g.K * g.C;
+    int best = 1;
+    double best_t = 1e300;
+    for (int sp = 1; sp <= max_splits; ++sp) {
+        const double blocks = (double)tiles * sp;
+        const double rounds = (double)((int64_t)((blocks + slots - 1) / slots));
+        const double eff = blocks / (rounds * slots);
+        const double t = flops / (0.6 * 155e12) / eff + 2.0 * sp * g.K * (double)g.C * 36.0 / 3.0e12;
+        if (t < best_t) { best_t = t; best = sp; }
+    }
+    p.tiles_per_split = round_up(ceil_div(p.T, best), step);
+    p.splits = ceil_div(p.T, p.tiles_per_split);
+    p.bias_splits = 1024 / g.K;
+    if (p.bias_splits > g.N) p.bias_splits = g.N;
+    if (p.bias_splits < 1) p.bias_splits = 1;
+    p.part_bytes = align_up((size_t)p.splits * g.K * g.C * 9 * sizeof(float), 256);
+    p.bias_bytes = align_up((size_t)p.bias_splits * g.K * sizeof(float), 256);
+    p.total_bytes = p.part_bytes + p.bias_bytes;
+    return p;
+}
+
 int resolve_algo(const Geom &g, conv2d_op op, int algo)
 {
     const bool wino_ok = wino_applicable(g, op);
     switch (algo) {
     case CONV2D_ALGO_AUTO: {
         // Winograd pays once the 16 GEMMs are deep enough to amortise the transforms
+        if (op == CONV2D_BWD_WEIGHT) return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
         const int cin = op == CONV2D_FWD ? g.C : g.K;
         return (wino_ok && cin >= 32) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
     }
@@ -288,7 +335,8 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     if (check_desc(d, &g)) return 0;
     const int al = resolve_algo(g, op, (int)algo);
     if (al < 0) return 0;
-    if (al == CONV2D_ALGO_WINOGRAD) return plan_wino(g, op).total_bytes;
+    if (al == CONV2D_ALGO_WINOGRAD)
+        return op == CONV2D_BWD_WEIGHT ? plan_wino_wgrad(g).total_bytes : plan_wino(g, op).total_bytes;
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
@@ -416,6 +464,33 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     const int al = resolve_algo(g, CONV2D_BWD_WEIGHT, (int)algo);
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
+
+    if (al == CONV2D_ALGO_WINOGRAD) {
+        const WinoWgradPlan p = plan_wino_wgrad(g);
+        if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+        float *part = (float *)ws;
+        float *bias_part = (float *)((char *)ws + p.part_bytes);
+        WinoWgradArgs a = {};
+        a.x = x; a.dy = dy; a.part = part;
+        a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q;
+        a.pad_h = g.ph; a.pad_w = g.pw;
+        a.TH = p.TH; a.TW = p.TW; a.T = p.T;
+        a.tiles_per_split = p.tiles_per_split;
+        a.tiles_k = p.tiles_k; a.tiles_c = p.tiles_c; a.splits = p.splits;
+        a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+        a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+        a.div_THW = make_fastdiv((uint32_t)(p.TH * p.TW));
+        a.div_TW = make_fastdiv((uint32_t)p.TW);
+        rc = launch_status(launch_wino_wgrad(a, s));
+        if (rc) return rc;
+        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale,
+                                               accumulate, s));
+        if (rc) return rc;
+        if (dbias)
+            rc = launch_status(launch_bias_grad(dy, bias_part, dbias, g.N, g.K, g.P * g.Q,
+                                                p.bias_splits, scale, accumulate, s));
+        return rc;
+    }
 
     const WgradPlan p = plan_wgrad(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;

@@ -152,6 +152,23 @@ hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, i
                               int Kpad, int mode, hipStream_t s);
 hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s);
 
+// Winograd backward-weight F(3x3,2x2) (see winograd_wgrad.hip).
+struct WinoWgradArgs {
+    const float *x;
+    const float *dy;
+    float *part;               // [splits][K][C][9]
+    int32_t N, C, H, W, K, P, Q, pad_h, pad_w;
+    int32_t TH, TW, T;         // 2x2 output tiles per image (rows, cols), in total
+    int32_t tiles_per_split;   // multiple of the 8-tile step
+    int32_t tiles_k, tiles_c, splits;
+    int32_t x_bytes, dy_bytes; // both below 2^31
+    FastDiv div_THW, div_TW;
+};
+
+int wino_wgrad_tile();
+int wino_wgrad_step();
+hipError_t launch_wino_wgrad(const WinoWgradArgs &a, hipStream_t s);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace mi355conv

@@ -1,0 +1,298 @@
+// Winograd backward-weight for 3x3 stride-1 layers on fp32 MFMA (gfx950).
+//
+// The forward tile relation  Y = A^T [ (G g G^T) .* (B^T d B) ] A  (Sec. 4.2
+// "Winograd" of the paper; matrices as in winograd.hip) is bilinear in (g, d),
+// so the gradient with respect to the filter is its transpose in g:
+//   dg = G^T [ sum over tiles of (A dy A^T) .* (B^T d B) ] G          F(3x3,2x2)
+// with dy the 2x2 output-gradient tile and d the 4x4 input tile.  At each of the
+// 16 positions the sum over tiles (and over the batch: tiles enumerate all
+// images) is a GEMM  M[pos] = DY'[pos] (K x T) * V[pos]^T (T x C): 2.25x fewer
+// multiplications than the direct 9-tap form.
+//
+// One workgroup owns 64 filters x 64 channels at all 16 positions (256
+// accumulator registers per lane, as in the forward kernel) and a contiguous
+// range of tiles; per step of 8 tiles both operands are loaded from NCHW with
+// buffer loads (out-of-image elements: offset beyond the buffer -> hardware
+// returns 0), transformed in registers and written to LDS.  The output
+// transform G^T M G happens in registers; the 3x3 partial gradients go to
+// part[split][K][C][9] and the ordinary split reduction adds them up
+// (deterministic order).
+
+#include "conv_internal.h"
+
+namespace mi355conv {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void lds_barrier_ww()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ int xcd_remap_ww(int id, int nb)
+{
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = id & 7, local = id >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + local;
+}
+
+constexpr int kWwKB = 64, kWwCB = 64, kWwTS = 8, kWwPitch = 72;
+constexpr int kWwLdsBytes = 2 * 2 * 16 * kWwTS * kWwPitch * (int)sizeof(float);
+
+__global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
+{
+    constexpr int KB = kWwKB, CB = kWwCB, TS = kWwTS, PITCH = kWwPitch;
+    extern __shared__ float lds[];
+    // As[buf][pos][tile][filter], Bs[buf][pos][tile][channel]; row pitch 72 floats so
+    // the writes (8 tiles x 8 columns per wave) spread over all banks
+    float *const As = lds;
+    float *const Bs = lds + 2 * 16 * TS * PITCH;
+    auto as_at = [&](int buf, int pos, int t, int k) -> float & { return As[((buf * 16 + pos) * TS + t) * PITCH + k]; };
+    auto bs_at = [&](int buf, int pos, int t, int c) -> float & { return Bs[((buf * 16 + pos) * TS + t) * PITCH + c]; };
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    const int ntile = a.tiles_k * a.tiles_c;
+    const int logical = xcd_remap_ww(blockIdx.x, gridDim.x);
+    const int tile_id = logical % ntile;
+    const int split = logical / ntile;
+    const int kt = tile_id % a.tiles_k;
+    const int ct = tile_id / a.tiles_k;
+    const int t_begin = split * a.tiles_per_split;
+    const int t_end = min(a.T, t_begin + a.tiles_per_split);
+    const int nsteps = (t_end - t_begin + TS - 1) / TS;
+
+    // this thread: tile (lane % 8) of every step; channels / filters sub, sub + 32
+    const int tile_l = lane & 7;
+    const int sub = tid >> 3;
+    const int c0 = ct * CB + sub, k0 = kt * KB + sub;
+    const int HW = a.H * a.W, PQ = a.P * a.Q;
+    const bool c0ok = c0 < a.C, k0ok = k0 < a.K;
+    // the "+32" items exist or not for the whole workgroup (C, K multiples of 32):
+    // a descriptor of size 0 makes every load of a missing item return 0
+    const __amdgpu_buffer_rsrc_t xrs0 = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xrs1 =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (ct * CB + 32 < a.C) ? a.x_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t drs0 = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.dy_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t drs1 =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, (kt * KB + 32 < a.K) ? a.dy_bytes : 0, 0x00020000);
+    const int xs1 = 32 * HW * 4, ds1 = 32 * PQ * 4;
+
+    uint32_t eoff[16], doff[4];
+    float xr[2][16], dr[2][4];
+
+    auto setup = [&](int step) {
+        const int tile = t_begin + step * TS + tile_l;
+        const bool tv = tile < t_end;
+        const int tl = tv ? tile : 0;
+        const int n = (int)fast_div((uint32_t)tl, a.div_THW);
+        const int rem = tl - n * (a.TH * a.TW);
+        const int th = (int)fast_div((uint32_t)rem, a.div_TW);
+        const int tw = rem - th * a.TW;
+        const int ih0 = 2 * th - a.pad_h, iw0 = 2 * tw - a.pad_w;
+        const int xbase = ((n * a.C + c0) * a.H + ih0) * a.W + iw0;
+        bool rok[4], cok[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            rok[i] = tv && c0ok && (unsigned)(ih0 + i) < (unsigned)a.H;
+            cok[i] = (unsigned)(iw0 + i) < (unsigned)a.W;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                eoff[4 * i + j] = (rok[i] && cok[j]) ? (uint32_t)(xbase + i * a.W + j) * 4u : 0x80000000u;
+        const int dbase = ((n * a.K + k0) * a.P + 2 * th) * a.Q + 2 * tw;
+        const bool r1 = 2 * th + 1 < a.P, q1 = 2 * tw + 1 < a.Q, dv = tv && k0ok;
+        doff[0] = dv ? (uint32_t)dbase * 4u : 0x80000000u;
+        doff[1] = (dv && q1) ? (uint32_t)(dbase + 1) * 4u : 0x80000000u;
+        doff[2] = (dv && r1) ? (uint32_t)(dbase + a.Q) * 4u : 0x80000000u;
+        doff[3] = (dv && r1 && q1) ? (uint32_t)(dbase + a.Q + 1) * 4u : 0x80000000u;
+    };
+    auto load_x = [&](int it, int e) {
+        xr[it][e] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(it ? xrs1 : xrs0, eoff[e], it ? xs1 : 0, 0));
+    };
+    auto load_d = [&](int it, int e) {
+        dr[it][e] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(it ? drs1 : drs0, doff[e], it ? ds1 : 0, 0));
+    };
+
+    // input transform V = B^T d B of item `it`: four column pieces, four row pieces
+    float tr[2][16];
+    auto xform_col = [&](int it, int j) {
+        const float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
+        tr[it][0 + j] = d0 - d2;
+        tr[it][4 + j] = d1 + d2;
+        tr[it][8 + j] = d2 - d1;
+        tr[it][12 + j] = d1 - d3;
+    };
+    auto xform_row_store = [&](int buf, int it, int i) {
+        const float t0 = tr[it][4 * i + 0], t1 = tr[it][4 * i + 1], t2 = tr[it][4 * i + 2], t3 = tr[it][4 * i + 3];
+        const int c = sub + 32 * it;
+        bs_at(buf, 4 * i + 0, tile_l, c) = t0 - t2;
+        bs_at(buf, 4 * i + 1, tile_l, c) = t1 + t2;
+        bs_at(buf, 4 * i + 2, tile_l, c) = t2 - t1;
+        bs_at(buf, 4 * i + 3, tile_l, c) = t1 - t3;
+    };
+    // gradient-tile transform DY' = A dy A^T, A = [1 0; 1 1; 1 -1; 0 -1]; piece i = row i
+    auto dyform_row_store = [&](int buf, int it, int i) {
+        const float y00 = dr[it][0], y01 = dr[it][1], y10 = dr[it][2], y11 = dr[it][3];
+        float t0, t1;       // row i of A dy
+        if (i == 0) { t0 = y00; t1 = y01; }
+        else if (i == 1) { t0 = y00 + y10; t1 = y01 + y11; }
+        else if (i == 2) { t0 = y00 - y10; t1 = y01 - y11; }
+        else { t0 = -y10; t1 = -y11; }
+        const int k = sub + 32 * it;
+        as_at(buf, 4 * i + 0, tile_l, k) = t0;
+        as_at(buf, 4 * i + 1, tile_l, k) = t0 + t1;
+        as_at(buf, 4 * i + 2, tile_l, k) = t0 - t1;
+        as_at(buf, 4 * i + 3, tile_l, k) = -t1;
+    };
+
+    floatx16 acc[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+    float ao[2][2][4], bo[2][2][4];
+    auto read_pair = [&](int buf, int pair, int set) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                ao[set][u][ks] = as_at(buf, 2 * pair + u, 2 * ks + lhi, wm0 + l32);
+                bo[set][u][ks] = bs_at(buf, 2 * pair + u, 2 * ks + lhi, wn0 + l32);
+            }
+    };
+    auto load_all = [&]() {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) load_x(it, e);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) load_d(it, e);
+        }
+    };
+
+    // ---- prologue: step 0 into LDS buffer 0, step 1 into registers ----
+    setup(0);
+    load_all();
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xform_col(it, j);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xform_row_store(0, it, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dyform_row_store(0, it, i);
+    }
+    setup(1);            // steps past the end: every offset out of range, all zeros
+    load_all();
+    lds_barrier_ww();
+    read_pair(0, 0, 0);
+
+    // Software pipeline, as in the forward kernel: 64 MFMA slots per step.
+    //   slots  0..15 : input transform + LDS writes of step t+1 (two items)
+    //   slots 16..23 : gradient-tile transform + LDS writes of step t+1
+    //   slots 24..25 : tile coordinates and buffer offsets of step t+2
+    //   slots 26..63 : the 40 buffer loads of step t+2
+    for (int t = 0; t < nsteps; ++t) {
+        const int buf = t & 1;
+#pragma unroll
+        for (int pair = 0; pair < 8; ++pair) {
+            const int cur = pair & 1, nxt = cur ^ 1;
+            if (pair + 1 < 8) {
+                read_pair(buf, pair + 1, nxt);
+            } else {
+                lds_barrier_ww();
+                read_pair(buf ^ 1, 0, nxt);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int s = pair * 8 + q;
+                if (s < 16) {
+                    const int it = s >> 3, piece = s & 7;
+                    if (piece < 4) xform_col(it, piece); else xform_row_store(buf ^ 1, it, piece - 4);
+                } else if (s < 24) {
+                    const int it = (s - 16) >> 2, i = (s - 16) & 3;
+                    dyform_row_store(buf ^ 1, it, i);
+                } else if (s == 24) {
+                    setup(t + 2);
+                } else if (s >= 26) {
+                    // 40 loads over 38 slots, in consumption order: x item 0 (column
+                    // major), x item 1, then the gradient tiles
+                    const int l0 = s - 26;
+#pragma unroll
+                    for (int l = 0; l < 40; ++l) {
+                        if (l * 38 / 40 != l0) continue;
+                        if (l < 32) {
+                            const int it = l >> 4, j = (l >> 2) & 3, i = l & 3;
+                            load_x(it, 4 * i + j);
+                        } else {
+                            load_d((l - 32) >> 2, (l - 32) & 3);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const int u = q & 1, ks = q >> 1;
+                acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ao[cur][u][ks], bo[cur][u][ks],
+                                                                          acc[2 * pair + u], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // ---- epilogue: dg = G^T M G in registers, partial 3x3 gradients out ----
+    const int c = ct * CB + wn0 + l32;
+    if (c >= a.C) return;
+    float *out = a.part + (int64_t)split * a.K * a.C * 9;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int k = kt * KB + wm0 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+        if (k >= a.K) continue;
+        float tt[3][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+            const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
+            tt[0][j] = m0 + hs;
+            tt[1][j] = hd;
+            tt[2][j] = hs + m3;
+        }
+        float *o = out + ((int64_t)k * a.C + c) * 9;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const float hs = 0.5f * (tt[r][1] + tt[r][2]), hd = 0.5f * (tt[r][1] - tt[r][2]);
+            o[3 * r + 0] = tt[r][0] + hs;
+            o[3 * r + 1] = hd;
+            o[3 * r + 2] = hs + tt[r][3];
+        }
+    }
+}
+
+int wino_wgrad_tile() { return kWwKB; }
+int wino_wgrad_step() { return kWwTS; }
+
+hipError_t launch_wino_wgrad(const WinoWgradArgs &a, hipStream_t s)
+{
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWwLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(wino_wgrad_kernel, dim3((unsigned)(a.tiles_k * a.tiles_c * a.splits)), dim3(256),
+                       kWwLdsBytes, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace mi355conv

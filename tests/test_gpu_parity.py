@@ -165,3 +165,34 @@ def test_winograd_refused_where_it_does_not_apply():
     with pytest.raises(B.Conv2dError) as e:
         B.conv2d_fwd(geom, x, w, None, y, algo=B.ALGO_WINOGRAD, ws=B.alloc_workspace(1 << 20))
     assert e.value.status == -3
+
+
+WINO_WGRAD_SHAPES = [
+    G(2, 32, 16, 16, 32, 3, 3, 1, 1),
+    G(3, 64, 19, 23, 96, 3, 3, 1, 1),        # odd map, K = 64 + 32
+    G(2, 96, 14, 14, 64, 3, 3, 1, 1),        # C = 64 + 32
+    G(4, 160, 13, 13, 224, 3, 3, 1, 1),
+    G(2, 32, 9, 9, 64, 3, 3, 1, 0),
+    G(2, 32, 10, 7, 32, 3, 3, 1, 2),
+    (2, 32, 11, 12, 32, 3, 3, 1, 1, 0, 2),
+    G(7, 64, 28, 28, 128, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("geom", WINO_WGRAD_SHAPES, ids=[("x".join(map(str, g))) for g in WINO_WGRAD_SHAPES])
+def test_winograd_wgrad_parity(geom):
+    from gpu_util import TOL_WINOGRAD
+    x, w, b, dy = random_layer(geom, 3000 + sum(geom))
+    print("geom", geom, flush=True)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, passes=("bwd_weight",))
+    dw, db = oracle.bwd_weight(geom, x, dy)
+    assert np.isfinite(got["dw"]).all()
+    r = max_err_ratio(got["dw"], dw)
+    assert r <= TOL_WINOGRAD, "dw: max err ratio %.3e" % r
+    assert max_err_ratio(got["db"], db) <= TOL_IGEMM
+    # scale / accumulate go through the same split reduction
+    dw0 = synth.normal(dw.shape, 8, std=5.0)
+    db0 = synth.normal(db.shape, 9, std=5.0)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, scale=0.5, dw0=dw0.copy(), db0=db0.copy(),
+                    passes=("bwd_weight",))
+    assert max_err_ratio(got["dw"], 0.5 * dw + dw0) <= TOL_WINOGRAD

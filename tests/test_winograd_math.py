@@ -78,3 +78,20 @@ def test_backward_data_is_forward_with_rotated_filter():
         wr = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
         g2 = (N, K, P, Q, C, 3, 3, 1, 1, 2 - pad, 2 - pad)
         np.testing.assert_array_equal(oracle.fwd(g2, dy, wr), dx)
+
+
+def test_weight_gradient_identity_exact():
+    """dg = G^T [(A dy A^T) .* (B^T d B)] G equals sum_{p,q} dy[p][q] d[p+r][q+s]."""
+    A = tr(AT)
+    rng = np.random.default_rng(4)
+    for _ in range(20):
+        d = rng.integers(-9, 10, size=(4, 4)).tolist()
+        dy = rng.integers(-9, 10, size=(2, 2)).tolist()
+        Dp = mm(mm(A, dy), AT)
+        V = mm(mm(BT, d), tr(BT))
+        M = [[Dp[i][j] * V[i][j] for j in range(4)] for i in range(4)]
+        dg = mm(mm(tr(G), M), G)
+        for r in range(3):
+            for s in range(3):
+                direct = sum(dy[p][q] * d[p + r][q + s] for p in range(2) for q in range(2))
+                assert dg[r][s] == direct
