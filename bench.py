@@ -32,7 +32,19 @@ WORKLOADS = {"tiny": 0, "alexnet": 1, "vgg16": 2, "inception": 3, "overfeat": 4}
 
 
 def layer_flops(L, P, Q):
+    """Direct-equivalent flops of one pass over one layer."""
     return 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
+
+
+def executed_flops(L, P, Q, op, algo):
+    """MFMA flops the chosen algorithm itself has to execute for one pass: the
+    direct count for the implicit GEMM; for Winograd F(2x2,3x3) the 16 GEMMs,
+    2*16*K*C per 2x2 tile (tiles of the pass's output: y for fwd/bwd_weight, dx for
+    bwd_data)."""
+    if algo != 2:
+        return layer_flops(L, P, Q)
+    th, tw = (-(-L.H // 2), -(-L.W // 2)) if op == "bwd_data" else (-(-P // 2), -(-Q // 2))
+    return 32.0 * L.N * th * tw * L.K * L.C
 
 
 def main() -> int:
@@ -45,6 +57,9 @@ def main() -> int:
     ap.add_argument("--algo", type=int, default=0, help="0 auto, 1 implicit GEMM, 2 Winograd")
     ap.add_argument("--detail", action="store_true", help="per-layer table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="run one device-to-device copy of this many MiB before the warm-up (a kernel of "
+                         "known traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -80,6 +95,12 @@ def main() -> int:
         rec = dict(L=L, geom=B.make_desc(geom), P=P, Q=Q, x=x, w=w, b=b, dy=dy,
                    y=torch.empty_like(dy), dx=torch.empty_like(x), dw=torch.empty_like(w),
                    db=torch.empty_like(b), flops=layer_flops(L, P, Q))
+        rec["algo"] = {}
+        rec["xflops"] = {}
+        for name, op in (("fwd", B.OP_FWD), ("bwd_data", B.OP_BWD_DATA), ("bwd_weight", B.OP_BWD_WEIGHT)):
+            al = args.algo if args.algo else B.conv2d_pick_algo(rec["geom"], op)
+            rec["algo"][name] = al
+            rec["xflops"][name] = executed_flops(L, P, Q, name, al)
         for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
             ws_need = max(ws_need, B.conv2d_workspace_bytes(rec["geom"], op, args.algo))
         recs.append(rec)
@@ -112,6 +133,12 @@ def main() -> int:
                 ev.append(("bwd_data", li, e0, e1))
                 ev.append(("bwd_weight", li, e1, e2))
 
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib * (1 << 18), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -129,41 +156,64 @@ def main() -> int:
     per = {}
     for op, li, e0, e1 in ev:
         per.setdefault((op, li), []).append(e0.elapsed_time(e1))
-    fam_ms = {"fwd": 0.0, "bwd_data": 0.0, "bwd_weight": 0.0}
-    fam_flops = {"fwd": 0.0, "bwd_data": 0.0, "bwd_weight": 0.0}
-    fam_calls = {"fwd": 0, "bwd_data": 0, "bwd_weight": 0}
+    # kernel families: which main kernel served the call
+    def family(op, li):
+        wino = recs[li]["algo"][op] == 2
+        if op == "bwd_weight":
+            return "wino_wgrad_kernel (Winograd bwd_weight calls)" if wino else "wgrad_kernel (implicit-GEMM bwd_weight calls)"
+        return "wino_fused_kernel (Winograd fwd + bwd_data calls)" if wino else "gemmconv_kernel (implicit-GEMM fwd + bwd_data calls)"
+
+    fam = {}
+    op_ms = {"fwd": 0.0, "bwd_data": 0.0, "bwd_weight": 0.0}
     for (op, li), ts in per.items():
-        fam_ms[op] += sum(ts)
-        fam_flops[op] += recs[li]["flops"] * len(ts)
-        fam_calls[op] += len(ts)
+        f = fam.setdefault(family(op, li), dict(ms=0.0, xflops=0.0, dflops=0.0, calls=0))
+        f["ms"] += sum(ts)
+        f["xflops"] += recs[li]["xflops"][op] * len(ts)
+        f["dflops"] += recs[li]["flops"] * len(ts)
+        f["calls"] += len(ts)
+        op_ms[op] += sum(ts)
     if args.detail:
-        print("%-12s %-10s %9s %9s %8s" % ("layer", "op", "ms(avg)", "TFLOP/s", "%peak"), file=sys.stderr)
+        print("%-12s %-10s %-5s %9s %10s %8s %10s" % ("layer", "op", "algo", "ms(avg)", "TF/s(dir)", "%peak", "TF/s(exec)"),
+              file=sys.stderr)
         for li, r in enumerate(recs):
             for op in ("fwd", "bwd_data", "bwd_weight"):
                 ts = per[(op, li)]
                 ms = sum(ts) / len(ts)
                 tf = r["flops"] / (ms * 1e-3) / 1e12
-                print("%-12s %-10s %9.3f %9.2f %8.1f" % (r["L"].name, op, ms, tf,
-                                                         100 * tf / PEAK_MFMA_FP32_TFLOPS), file=sys.stderr)
-        for op in fam_ms:
-            print("total %-10s %9.3f ms/step" % (op, fam_ms[op] / args.steps), file=sys.stderr)
-        print("wall %.3f ms/step, %.2f TFLOP/s (%.1f%% of fp32 MFMA peak)" % (
+                xtf = r["xflops"][op] / (ms * 1e-3) / 1e12
+                print("%-12s %-10s %-5s %9.3f %10.2f %8.1f %10.2f" % (
+                    r["L"].name, op, "wino" if r["algo"][op] == 2 else "igemm", ms, tf,
+                    100 * tf / PEAK_MFMA_FP32_TFLOPS, xtf), file=sys.stderr)
+        for op in op_ms:
+            print("total %-10s %9.3f ms/step" % (op, op_ms[op] / args.steps), file=sys.stderr)
+        for k, f in fam.items():
+            print("family %-55s %8.3f ms/step  exec %.1f TF/s" % (k, f["ms"] / args.steps,
+                                                                 f["xflops"] / f["ms"] / 1e9), file=sys.stderr)
+        print("wall %.3f ms/step, %.2f TFLOP/s direct-equivalent (%.1f%% of fp32 MFMA peak)" % (
             ms_per_step, tflops, 100 * tflops / PEAK_MFMA_FP32_TFLOPS), file=sys.stderr)
 
-    # dominant kernel family: the gather kernel serves fwd and bwd_data calls
-    gather_ms = fam_ms["fwd"] + fam_ms["bwd_data"]
-    if gather_ms >= fam_ms["bwd_weight"]:
-        kname, k_ms = "gemmconv_kernel (fwd + bwd_data calls)", gather_ms
-        k_flops = fam_flops["fwd"] + fam_flops["bwd_data"]
-        k_calls = fam_calls["fwd"] + fam_calls["bwd_data"]
-    else:
-        kname, k_ms, k_flops = "wgrad_kernel (bwd_weight calls)", fam_ms["bwd_weight"], fam_flops["bwd_weight"]
-        k_calls = fam_calls["bwd_weight"]
-    achieved = k_flops / (k_ms * 1e-3) / 1e12
+    # roofline of the dominant kernel family: MFMA flops the algorithm executes
+    # (not the direct-equivalent count) over the summed event durations of its calls
+    kname, kf = max(fam.items(), key=lambda kv: kv[1]["ms"])
+    achieved = kf["xflops"] / (kf["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 3),
                 "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_FP32_TFLOPS, 4), "traffic": None,
-                "avg_launch_ms": round(k_ms / k_calls, 4), "launches": k_calls}
+                "avg_launch_ms": round(kf["ms"] / kf["calls"], 4), "launches": kf["calls"],
+                "direct_equivalent_tflops": round(kf["dflops"] / (kf["ms"] * 1e-3) / 1e12, 3)}
+
+    # HBM traffic of that kernel family per launch, from the committed rocprofv3
+    # counter summary of this workload (null if none has been taken)
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    if os.path.exists(tpath):
+        try:
+            with open(tpath) as fh:
+                tr = json.load(fh)
+            key = kname.split(" ")[0]
+            if key in tr.get("bytes_per_launch", {}):
+                roofline["traffic"] = tr["bytes_per_launch"][key]
+        except (OSError, ValueError):
+            pass
 
     out = {
         "metric": "fp32 conv TFLOP/s fwd+bwd (%s conv stack)" % args.workload,

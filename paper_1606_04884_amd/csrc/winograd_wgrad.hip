@@ -38,19 +38,23 @@ __device__ __forceinline__ int xcd_remap_ww(int id, int nb)
     return xcd * per + (xcd < rem ? xcd : rem) + local;
 }
 
-constexpr int kWwKB = 64, kWwCB = 64, kWwTS = 8, kWwPitch = 72;
-constexpr int kWwLdsBytes = 2 * 2 * 16 * kWwTS * kWwPitch * (int)sizeof(float);
+// LDS rows of 64 values are padded to 68 floats (68 mod 32 = 4): the 8 tiles x 4
+// columns a half-wave writes then fall in 32 different banks.  Each position's
+// block of 8 rows is padded to 576 floats, a multiple of 64 dwords, so that two
+// positions can be written by one paired store.
+constexpr int kWwKB = 64, kWwCB = 64, kWwTS = 8, kWwPitch = 68, kWwPosStride = 576;
+constexpr int kWwLdsBytes = 2 * 2 * 16 * kWwPosStride * (int)sizeof(float);
 
 __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
 {
-    constexpr int KB = kWwKB, CB = kWwCB, TS = kWwTS, PITCH = kWwPitch;
+    constexpr int KB = kWwKB, CB = kWwCB, TS = kWwTS, PITCH = kWwPitch, PSTR = kWwPosStride;
     extern __shared__ float lds[];
-    // As[buf][pos][tile][filter], Bs[buf][pos][tile][channel]; row pitch 72 floats so
-    // the writes (8 tiles x 8 columns per wave) spread over all banks
+    // As[buf][pos][tile][filter], Bs[buf][pos][tile][channel]
     float *const As = lds;
-    float *const Bs = lds + 2 * 16 * TS * PITCH;
-    auto as_at = [&](int buf, int pos, int t, int k) -> float & { return As[((buf * 16 + pos) * TS + t) * PITCH + k]; };
-    auto bs_at = [&](int buf, int pos, int t, int c) -> float & { return Bs[((buf * 16 + pos) * TS + t) * PITCH + c]; };
+    float *const Bs = lds + 2 * 16 * PSTR;
+    static_assert(TS * PITCH <= PSTR, "position block");
+    auto as_at = [&](int buf, int pos, int t, int k) -> float & { return As[(buf * 16 + pos) * PSTR + t * PITCH + k]; };
+    auto bs_at = [&](int buf, int pos, int t, int c) -> float & { return Bs[(buf * 16 + pos) * PSTR + t * PITCH + c]; };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
