@@ -115,6 +115,9 @@ __device__ __forceinline__ int xcd_remap_wino(int id, int nb)
 constexpr int kWinoKB = 64, kWinoTB = 64, kWinoCB = 8;
 constexpr int kWinoLdsBytes = 2 * 16 * kWinoCB * (kWinoKB + kWinoTB) * (int)sizeof(float);
 
+// VEC: row-vector patch loads (needs pad_w <= 1); MASK_MID: patch column 2 can
+// fall outside the image (odd widths)
+template <bool VEC, bool MASK_MID>
 __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 {
     constexpr int KB = kWinoKB, TB = kWinoTB, CB = kWinoCB;
@@ -139,14 +142,18 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     // Patch elements are fetched with buffer loads: the per-thread byte offset of
     // each element (inside channel 0 of its image) never changes, the channel
     // advances through the scalar offset, and elements outside the image carry
-    // an offset beyond the buffer, for which the hardware range check returns 0:
-    // zero padding costs no instruction.
+    // an offset beyond the buffer, for which the hardware range check (done per
+    // dword) returns 0: that zero padding costs no instruction.
+    // VEC (pad_w <= 1): a patch row is one dword (column 0) plus one 12-byte load
+    // (columns 1..3, whose start offset is never negative); columns 2 and 3 can
+    // then alias the next row in memory and are cleared by a select instead.
     const int HW = a.Hin * a.Win;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t ursrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.U, 0, a.u_bytes, 0x00020000);
-    uint32_t eoff[16];
+    uint32_t eoff[16];      // byte offset of patch element 4*i+j inside channel 0 (or 2^31)
+    bool cok[4];            // patch column inside the image
     {
         const int tile = tt * TB + lane;
         const bool tv = tile < a.T;
@@ -155,11 +162,15 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
         const int th = rem / a.TW, tw = rem - th * a.TW;
         const int ih0 = 2 * th - a.pad_h, iw0 = 2 * tw - a.pad_w;
 #pragma unroll
+        for (int j = 0; j < 4; ++j) cok[j] = (unsigned)(iw0 + j) < (unsigned)a.Win;
+#pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool ok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin &&
-                                (unsigned)(iw0 + j) < (unsigned)a.Win;
+                const bool rok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin;
+                // VEC: columns 1..3 come from one 12-byte load at column 1, which
+                // only needs the row to be valid (its start is never negative)
+                const bool ok = rok && ((VEC && j == 1) ? true : cok[j]);
                 const int idx = n * a.Cin * HW + (ih0 + i) * a.Win + (iw0 + j);
                 eoff[4 * i + j] = ok ? (uint32_t)idx * 4u : 0x80000000u;
             }
@@ -180,10 +191,29 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     float xr[2][16];
     floatx4 ur[8];
 
-    auto load_x = [&](int it, int e, int chunk) {
-        xr[it][e] = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[e], chunk * x_chunk + (it ? xs1 : xs0), 0));
+    typedef float floatx3 __attribute__((ext_vector_type(3)));
+    // load number l of an item: VEC: 8 loads (row l/2: column 0, then columns 1..3);
+    // otherwise 16 single elements in column-major order
+    auto load_x = [&](int it, int l, int chunk) {
+        const int so = chunk * x_chunk + (it ? xs1 : xs0);
+        if (VEC) {
+            const int i = l >> 1;
+            if ((l & 1) == 0) {
+                xr[it][4 * i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[4 * i], so, 0));
+            } else {
+                // (cast the whole result vector, then index the cast value)
+                const floatx3 v = __builtin_bit_cast(
+                    floatx3, __builtin_amdgcn_raw_buffer_load_b96(xrsrc, eoff[4 * i + 1], so, 0));
+                xr[it][4 * i + 1] = v[0];
+                xr[it][4 * i + 2] = v[1];
+                xr[it][4 * i + 3] = v[2];
+            }
+        } else {
+            const int e = 4 * (l & 3) + (l >> 2);
+            xr[it][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[e], so, 0));
+        }
     };
+    constexpr int XLOADS = VEC ? 8 : 16;
     auto load_u = [&](int i, int chunk) {
         ur[i] = __builtin_bit_cast(floatx4,
                                    __builtin_amdgcn_raw_buffer_load_b128(ursrc, uoff[i], chunk * u_chunk, 0));
@@ -192,7 +222,13 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     // input transform of item `it`, in two stages of four pieces each
     float tr[2][16];
     auto xform_col = [&](int it, int j) {     // stage 1 on patch column j: t = B^T d
-        const float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
+        float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
+        if (VEC && (j == 3 || (MASK_MID && j == 2))) {   // columns past the right edge
+            d0 = cok[j] ? d0 : 0.f;
+            d1 = cok[j] ? d1 : 0.f;
+            d2 = cok[j] ? d2 : 0.f;
+            d3 = cok[j] ? d3 : 0.f;
+        }
         tr[it][0 + j] = d0 - d2;
         tr[it][4 + j] = d1 + d2;
         tr[it][8 + j] = d2 - d1;
@@ -234,7 +270,7 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 #pragma unroll
     for (int it = 0; it < 2; ++it)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) load_x(it, e, 0);
+        for (int l = 0; l < XLOADS; ++l) load_x(it, l, 0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) load_u(i, 0);
 #pragma unroll
@@ -251,7 +287,7 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 #pragma unroll
         for (int it = 0; it < 2; ++it)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) load_x(it, e, c1);
+            for (int l = 0; l < XLOADS; ++l) load_x(it, l, c1);
 #pragma unroll
         for (int i = 0; i < 8; ++i) load_u(i, c1);
     }
@@ -340,18 +376,26 @@ int wino_filter_tile() { return kWinoKB; }
 int wino_tile_block() { return kWinoTB; }
 int wino_chan_chunk() { return kWinoCB; }
 
-hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s)
+template <bool VEC, bool MASK_MID>
+static hipError_t launch_wino_variant(const WinoArgs &a, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel<VEC, MASK_MID>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWinoLdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(wino_fused_kernel, dim3((unsigned)(a.tiles_t * a.tiles_k)), dim3(256),
-                       kWinoLdsBytes, s, a);
+    hipLaunchKernelGGL((wino_fused_kernel<VEC, MASK_MID>), dim3((unsigned)(a.tiles_t * a.tiles_k)),
+                       dim3(256), kWinoLdsBytes, s, a);
     return hipGetLastError();
+}
+
+hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s)
+{
+    if (a.pad_w > 1) return launch_wino_variant<false, false>(a, s);
+    if (a.Win % 2 != 0) return launch_wino_variant<true, true>(a, s);
+    return launch_wino_variant<true, false>(a, s);
 }
 
 }  // namespace mi355conv
