@@ -57,8 +57,9 @@ int pick_gather_tile(int filters)
     return best;
 }
 
-int pick_wgrad_tile(int filters)
+int pick_wgrad_tile(int filters, int crs)
 {
+    if (crs <= 32) return 3;            // 64 filters x 32 lowered columns
     static const double handicap[3] = {1.0, 1.03, 1.10};
     int best = 0;
     double best_cost = 1e30;
@@ -138,7 +139,7 @@ WgradPlan plan_wgrad(const Geom &g)
     WgradPlan p;
     const int CRS = g.C * g.R * g.S;
     const int64_t M = (int64_t)g.N * g.P * g.Q;
-    p.tile = pick_wgrad_tile(g.K);
+    p.tile = pick_wgrad_tile(g.K, CRS);
     p.tiles_k = ceil_div(g.K, wgrad_filter_tile(p.tile));
     p.tiles_j = ceil_div(CRS, wgrad_col_tile(p.tile));
     const int tiles = p.tiles_k * p.tiles_j;
@@ -257,9 +258,7 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
     }
     p.tiles_per_split = round_up(ceil_div(p.T, best), step);
     p.splits = ceil_div(p.T, p.tiles_per_split);
-    p.bias_splits = 1024 / g.K;
-    if (p.bias_splits > g.N) p.bias_splits = g.N;
-    if (p.bias_splits < 1) p.bias_splits = 1;
+    p.bias_splits = p.splits;       // the main kernel also sums dy: one partial per split
     p.part_bytes = align_up((size_t)p.splits * g.K * g.C * 9 * sizeof(float), 256);
     p.bias_bytes = align_up((size_t)p.bias_splits * g.K * sizeof(float), 256);
     p.total_bytes = p.part_bytes + p.bias_bytes;
@@ -471,7 +470,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
         float *part = (float *)ws;
         float *bias_part = (float *)((char *)ws + p.part_bytes);
         WinoWgradArgs a = {};
-        a.x = x; a.dy = dy; a.part = part;
+        a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
         a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q;
         a.pad_h = g.ph; a.pad_w = g.pw;
         a.TH = p.TH; a.TW = p.TW; a.T = p.T;
@@ -487,8 +486,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
                                                accumulate, s));
         if (rc) return rc;
         if (dbias)
-            rc = launch_status(launch_bias_grad(dy, bias_part, dbias, g.N, g.K, g.P * g.Q,
-                                                p.bias_splits, scale, accumulate, s));
+            rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, accumulate, s));
         return rc;
     }
 

@@ -93,7 +93,7 @@ struct PrepArgs {
     PrepPhase ph[kMaxPhases];
 };
 
-// tile = 0: 128 filters x 128 pixels, 1: 64 x 256, 2: 32 x 256
+// gather tile = 0: 128 filters x 128 pixels, 1: 64 x 256, 2: 32 x 256
 int gemmconv_filter_tile(int tile);
 int gemmconv_pixel_tile(int tile);
 hipError_t launch_gemmconv_prep(const PrepArgs &a, hipStream_t s);
@@ -123,6 +123,9 @@ hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s);
 // dst[i] = scale * sum_s part[s][i] (+ dst[i] if accumulate)
 hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
                                float scale, int accumulate, hipStream_t s);
+// db[k] = scale * sum_i part[i][k] (+ db[k])
+hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
+                             int accumulate, hipStream_t s);
 // db[k] = scale * sum_{n,pq} dy[n,k,pq] (+ db[k]); part holds nsplit*K floats
 hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,
                             int nsplit, float scale, int accumulate, hipStream_t s);
@@ -157,6 +160,7 @@ struct WinoWgradArgs {
     const float *x;
     const float *dy;
     float *part;               // [splits][K][C][9]
+    float *bias_part;          // [splits][K] partial sums of dy per filter, or null
     int32_t N, C, H, W, K, P, Q, pad_h, pad_w;
     int32_t TH, TW, T;         // 2x2 output tiles per image (rows, cols), in total
     int32_t tiles_per_split;   // multiple of the 8-tile step

@@ -43,7 +43,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
 {
     constexpr int BK = 32;                   // pixels per main-loop step
     constexpr int WAVES_N = BN / WN;
-    static_assert((BM / WM) * WAVES_N == 4, "4 waves per workgroup");
+    constexpr int WAVES_MN = (BM / WM) * WAVES_N;     // waves tiling the output tile
+    constexpr int WAVES_K = 4 / WAVES_MN;             // waves sharing one output sub-tile: each
+    static_assert(WAVES_MN * WAVES_K == 4, "4 waves per workgroup");   // takes a slice of every step
     constexpr int MI = WM / 32, NI = WN / 32;
     constexpr int A_PER_THREAD = BM / 8;     // 8 thread rows x 32 pixels
     constexpr int B_PER_THREAD = BN / 8;
@@ -138,8 +140,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    const int wm0 = (wave / WAVES_N) * WM;
-    const int wn0 = (wave % WAVES_N) * WN;
+    const int wave_mn = wave % WAVES_MN, wave_k = wave / WAVES_MN;
+    const int wm0 = (wave_mn / WAVES_N) * WM;
+    const int wn0 = (wave_mn % WAVES_N) * WN;
     const int l32 = lane & 31, lhi = lane >> 5;
 
     float av[2][MI], bv[2][NI];
@@ -150,18 +153,24 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
         for (int ni = 0; ni < NI; ++ni) bv[slot][ni] = Bs[buf][kk + lhi][wn0 + ni * 32 + l32];
     };
 
-    // Software pipeline, same shape as the gather kernel's: per 32-pixel tile,
-    // 16 MFMA steps; between consecutive MFMAs one slot of other work.
-    //   steps 0..1  : registers holding tile t+1 go to the other LDS buffer
-    //   step  2     : pixel coordinates of tile t+2
-    //   steps 3..10 : global loads of tile t+2
-    //   last step   : LDS-only barrier, then the first operands of tile t+1
+    // Software pipeline, same shape as the gather kernel's: per 32-pixel tile a
+    // wave runs NSTEPW MFMA steps (its slice of the tile's 16 depth-2 steps) of
+    // NMF MFMAs; between consecutive MFMAs sits one slot of other work:
+    //   first eighth of the slots : registers holding tile t+1 go to the other LDS buffer
+    //   next slot                 : pixel coordinates of tile t+2
+    //   following half            : global loads of tile t+2
+    //   last step                 : LDS-only barrier, then the first operands of tile t+1
     constexpr int NSTEP = BK / 2;
+    constexpr int NSTEPW = NSTEP / WAVES_K;
     constexpr int NMF = MI * NI;
+    constexpr int NSLOT = NSTEPW * NMF;
     constexpr int NEL = A_PER_THREAD + B_PER_THREAD;
-    constexpr int SSLOTS = 2 * NMF, LSLOTS = 8 * NMF;
+    constexpr int SSLOTS = NSLOT / 8 > 0 ? NSLOT / 8 : 1;
+    constexpr int LSLOTS = NSLOT / 2;
+    static_assert(SSLOTS + 1 + LSLOTS <= NSLOT - NMF, "side work must end before the barrier step");
     auto load_el = [&](int e) { if (e < A_PER_THREAD) load_a(e); else load_b(e - A_PER_THREAD); };
     auto store_el = [&](int buf, int e) { if (e < A_PER_THREAD) store_a(buf, e); else store_b(buf, e - A_PER_THREAD); };
+    const int kk0 = wave_k * NSTEPW * 2;     // first depth index of this wave's slice
 
     if (nsteps > 0) {
         pixel_setup(0);
@@ -174,32 +183,32 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
         for (int e = 0; e < NEL; ++e) load_el(e);
     }
     lds_barrier_w();
-    if (nsteps > 0) read_ops(0, 0, 0);
+    if (nsteps > 0) read_ops(0, kk0, 0);
     for (int st = 0; st < nsteps; ++st) {
         const int buf = st & 1;
 #pragma unroll
-        for (int j = 0; j < NSTEP; ++j) {
+        for (int j = 0; j < NSTEPW; ++j) {
             const int cur = j & 1, nxt = cur ^ 1;
-            if (j + 1 < NSTEP) {
-                read_ops(buf, 2 * (j + 1), nxt);
+            if (j + 1 < NSTEPW) {
+                read_ops(buf, kk0 + 2 * (j + 1), nxt);
             } else {
                 lds_barrier_w();
-                read_ops(buf ^ 1, 0, nxt);
+                read_ops(buf ^ 1, kk0, nxt);
             }
 #pragma unroll
             for (int q = 0; q < NMF; ++q) {
-                if (j < 2) {
-                    const int sidx = j * NMF + q;
+                const int sidx = j * NMF + q;
+                if (sidx < SSLOTS) {
 #pragma unroll
                     for (int e = 0; e < NEL; ++e)
                         if (e * SSLOTS / NEL == sidx) store_el(buf ^ 1, e);
-                } else if (j == 2) {
-                    if (q == 0) pixel_setup(st + 2);
-                } else if (j <= 10) {
-                    const int sidx = (j - 3) * NMF + q;
+                } else if (sidx == SSLOTS) {
+                    pixel_setup(st + 2);
+                } else if (sidx <= SSLOTS + LSLOTS) {
+                    const int l = sidx - SSLOTS - 1;
 #pragma unroll
                     for (int e = 0; e < NEL; ++e)
-                        if (e * LSLOTS / NEL == sidx) load_el(e);
+                        if (e * LSLOTS / NEL == l) load_el(e);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x2f32(
@@ -207,6 +216,35 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+    }
+
+    // waves that shared an output sub-tile add their accumulators through LDS
+    if (WAVES_K > 1) {
+        float *scratch = &As[0][0][0];
+        static_assert((WAVES_K - 1) * WAVES_MN * MI * NI * 16 * 64 <= 2 * BK * (BM + 1), "scratch fits in As");
+        __syncthreads();
+        if (wave_k > 0) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        scratch[((((wave_k - 1) * WAVES_MN + wave_mn) * MI * NI + mi * NI + ni) * 16 + v) * 64 + lane] =
+                            acc[mi][ni][v];
+        }
+        __syncthreads();
+        if (wave_k > 0) return;
+#pragma unroll
+        for (int wk = 1; wk < WAVES_K; ++wk)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[mi][ni][v] +=
+                            scratch[((((wk - 1) * WAVES_MN + wave_mn) * MI * NI + mi * NI + ni) * 16 + v) * 64 + lane];
     }
 
     // partial tile -> part[split][k][j]
@@ -225,8 +263,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
     }
 }
 
-static const int kWFilterTile[3] = {128, 64, 32};
-static const int kWColTile[3] = {128, 128, 128};
+static const int kWFilterTile[4] = {128, 64, 32, 64};
+static const int kWColTile[4] = {128, 128, 128, 32};
 int wgrad_filter_tile(int tile) { return kWFilterTile[tile]; }
 int wgrad_col_tile(int tile) { return kWColTile[tile]; }
 
@@ -240,8 +278,11 @@ hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s)
     case 1:
         hipLaunchKernelGGL((wgrad_kernel<64, 128, 32, 64>), grid, dim3(256), 0, s, a);
         break;
-    default:
+    case 2:
         hipLaunchKernelGGL((wgrad_kernel<32, 128, 32, 32>), grid, dim3(256), 0, s, a);
+        break;
+    default:    // narrow lowered matrix (first layers with 3x3 filters): two waves per sub-tile
+        hipLaunchKernelGGL((wgrad_kernel<64, 32, 32, 32>), grid, dim3(256), 0, s, a);
         break;
     }
     return hipGetLastError();
@@ -304,6 +345,14 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float *__res
     for (int i = 0; i < nsplit; ++i) s += part[i * K + k];
     s *= scale;
     db[k] = accumulate ? db[k] + s : s;
+}
+
+hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
+                             int accumulate, hipStream_t s)
+{
+    hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s,
+                       part, db, K, nsplit, scale, accumulate);
+    return hipGetLastError();
 }
 
 hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,

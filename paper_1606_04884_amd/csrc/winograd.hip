@@ -115,9 +115,9 @@ __device__ __forceinline__ int xcd_remap_wino(int id, int nb)
 constexpr int kWinoKB = 64, kWinoTB = 64, kWinoCB = 8;
 constexpr int kWinoLdsBytes = 2 * 16 * kWinoCB * (kWinoKB + kWinoTB) * (int)sizeof(float);
 
-// VEC: row-vector patch loads (needs pad_w <= 1); MASK_MID: patch column 2 can
-// fall outside the image (odd widths)
-template <bool VEC, bool MASK_MID>
+// VEC: row-vector patch loads; needs pad_w <= 1 and an even width, so that of
+// the patch columns only the last one can fall outside the image
+template <bool VEC>
 __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 {
     constexpr int KB = kWinoKB, TB = kWinoTB, CB = kWinoCB;
@@ -144,9 +144,9 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     // advances through the scalar offset, and elements outside the image carry
     // an offset beyond the buffer, for which the hardware range check (done per
     // dword) returns 0: that zero padding costs no instruction.
-    // VEC (pad_w <= 1): a patch row is one dword (column 0) plus one 12-byte load
-    // (columns 1..3, whose start offset is never negative); columns 2 and 3 can
-    // then alias the next row in memory and are cleared by a select instead.
+    // VEC (pad_w <= 1, even width): a patch row is one dword (column 0) plus one
+    // 12-byte load (columns 1..3, whose start offset is never negative); column 3
+    // can then alias the next row in memory and is cleared by a select instead.
     const int HW = a.Hin * a.Win;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     float tr[2][16];
     auto xform_col = [&](int it, int j) {     // stage 1 on patch column j: t = B^T d
         float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
-        if (VEC && (j == 3 || (MASK_MID && j == 2))) {   // columns past the right edge
+        if (VEC && j == 3) {                     // column past the right edge
             d0 = cok[j] ? d0 : 0.f;
             d1 = cok[j] ? d1 : 0.f;
             d2 = cok[j] ? d2 : 0.f;
@@ -376,26 +376,25 @@ int wino_filter_tile() { return kWinoKB; }
 int wino_tile_block() { return kWinoTB; }
 int wino_chan_chunk() { return kWinoCB; }
 
-template <bool VEC, bool MASK_MID>
+template <bool VEC>
 static hipError_t launch_wino_variant(const WinoArgs &a, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel<VEC, MASK_MID>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel<VEC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWinoLdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((wino_fused_kernel<VEC, MASK_MID>), dim3((unsigned)(a.tiles_t * a.tiles_k)),
+    hipLaunchKernelGGL((wino_fused_kernel<VEC>), dim3((unsigned)(a.tiles_t * a.tiles_k)),
                        dim3(256), kWinoLdsBytes, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s)
 {
-    if (a.pad_w > 1) return launch_wino_variant<false, false>(a, s);
-    if (a.Win % 2 != 0) return launch_wino_variant<true, true>(a, s);
-    return launch_wino_variant<true, false>(a, s);
+    if (a.pad_w > 1 || a.Win % 2 != 0) return launch_wino_variant<false>(a, s);
+    return launch_wino_variant<true>(a, s);
 }
 
 }  // namespace mi355conv

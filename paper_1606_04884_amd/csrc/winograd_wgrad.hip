@@ -145,8 +145,10 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
         bs_at(buf, 4 * i + 3, tile_l, c) = t1 - t3;
     };
     // gradient-tile transform DY' = A dy A^T, A = [1 0; 1 1; 1 -1; 0 -1]; piece i = row i
+    float bsum[2] = {0.f, 0.f};      // running sum of this thread's gradient tiles (bias gradient)
     auto dyform_row_store = [&](int buf, int it, int i) {
         const float y00 = dr[it][0], y01 = dr[it][1], y10 = dr[it][2], y11 = dr[it][3];
+        if (i == 0) bsum[it] += (y00 + y01) + (y10 + y11);
         float t0, t1;       // row i of A dy
         if (i == 0) { t0 = y00; t1 = y01; }
         else if (i == 1) { t0 = y00 + y10; t1 = y01 + y11; }
@@ -251,6 +253,20 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
                                                                           acc[2 * pair + u], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    }
+
+    // ---- bias gradient: every tile of the range went through bsum exactly once.
+    // Only the workgroups of channel tile 0 write it: one partial per (split, k).
+    if (a.bias_part != nullptr && ct == 0) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            float v = bsum[it];
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 4);
+            const int k = k0 + 32 * it;
+            if (tile_l == 0 && k < a.K) a.bias_part[split * a.K + k] = v;
         }
     }
 
