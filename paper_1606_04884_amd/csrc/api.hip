@@ -180,7 +180,8 @@ WgradPlan plan_wgrad(const Geom &g)
 // ---- Winograd F(2x2,3x3) ---------------------------------------------------
 struct WinoPlan {
     int Cin, Kout, Cpad, Kpad, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, tiles_t, tiles_k;
-    size_t total_bytes;
+    int grid;                   // persistent workgroups
+    size_t u_bytes, total_bytes;
 };
 
 // The fused kernel handles 3x3 stride-1 layers whose reduction channels are a
@@ -222,7 +223,10 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
     p.T = g.N * p.TH * p.TW;
     p.tiles_t = ceil_div(p.T, wino_tile_block());
     p.tiles_k = p.Kpad / wino_filter_tile();
-    p.total_bytes = align_up((size_t)16 * p.Cpad * p.Kpad * sizeof(float), 256);
+    const int tiles = p.tiles_t * p.tiles_k;
+    p.grid = tiles < 256 ? tiles : 256;          // one resident workgroup per compute unit
+    p.u_bytes = align_up((size_t)16 * p.Cpad * p.Kpad * sizeof(float), 256);
+    p.total_bytes = p.u_bytes + align_up((size_t)p.grid * 2 * wino_partial_slot_floats() * sizeof(float), 256);
     return p;
 }
 
@@ -298,10 +302,13 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
     a.Kout = p.Kout; a.Kpad = p.Kpad; a.Hout = p.Hout; a.Wout = p.Wout;
     a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T;
     a.tiles_t = p.tiles_t; a.tiles_k = p.tiles_k;
+    a.nchunks = p.Cin / wino_chan_chunk();
+    a.units_total = p.tiles_t * p.tiles_k * a.nchunks;
+    a.partial = (float *)((char *)ws + p.u_bytes);
     a.in_bytes = (int32_t)((int64_t)g.N * p.Cin * p.Hin * p.Win * 4);
     a.u_bytes = (int32_t)((int64_t)16 * p.Cpad * p.Kpad * 4);
     a.vec2 = (p.Wout % 2 == 0) && (((uintptr_t)out & 7) == 0);
-    return launch_status(launch_wino_fused(a, s));
+    return launch_status(launch_wino_fused(a, p.grid, s));
 }
 
 }  // namespace

@@ -146,6 +146,8 @@ struct WinoArgs {
     int32_t tiles_t, tiles_k;
     int32_t vec2;            // output rows can be stored as aligned float2
     int32_t in_bytes, u_bytes;   // sizes of `in` and `U` (both below 2^31)
+    int32_t nchunks, units_total; // 8-channel chunks per tile; tiles_t*tiles_k*nchunks
+    float *partial;              // [grid][2] slots of 64*64*4 floats for tiles cut by a range boundary
 };
 
 int wino_filter_tile();
@@ -153,7 +155,9 @@ int wino_tile_block();
 int wino_chan_chunk();
 hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
                               int Kpad, int mode, hipStream_t s);
-hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s);
+int wino_partial_slot_floats();
+// G persistent workgroups (G <= tiles_t*tiles_k)
+hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s);
 
 // Winograd backward-weight F(3x3,2x2) (see winograd_wgrad.hip).
 struct WinoWgradArgs {

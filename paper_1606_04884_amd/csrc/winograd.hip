@@ -13,7 +13,7 @@
 // The sum over c at each of the 16 positions is a GEMM  M[pos] = U[pos]^T V[pos]
 // with U[pos] : [C x K] (filters), V[pos] : [C x tiles].
 //
-// One workgroup (4 waves) owns 64 filters x 64 tiles at all 16 positions: each
+// One workgroup (4 waves) computes 64 filters x 64 tiles at all 16 positions: each
 // wave keeps 16 accumulator tiles of 32x32 (256 accumulator registers), so the
 // output transform needs no exchange: the 16 values of one (filter, tile) sit in
 // the same lane and register index of the 16 accumulators.  Per 8-channel chunk
@@ -115,8 +115,21 @@ __device__ __forceinline__ int xcd_remap_wino(int id, int nb)
 constexpr int kWinoKB = 64, kWinoTB = 64, kWinoCB = 8;
 constexpr int kWinoLdsBytes = 2 * 16 * kWinoCB * (kWinoKB + kWinoTB) * (int)sizeof(float);
 
-// VEC: row-vector patch loads; needs pad_w <= 1 and an even width, so that of
-// the patch columns only the last one can fall outside the image
+// Work decomposition ("stream-K"): a unit is one 8-channel chunk of one output
+// tile (64 filters x 64 tiles); units are numbered chunk-fastest, then tile block,
+// then filter tile.  The grid is persistent: workgroup b processes the contiguous
+// unit range [b*U/G, (b+1)*U/G), so every compute unit gets the same amount of
+// MFMA work whatever the layer's tile count, and the software pipeline simply
+// runs on across tile boundaries (the loads of the next tile's first chunks are
+// in flight while the previous tile's epilogue runs).  An output tile that lies
+// entirely inside a range is finished there (output transform, bias, store); a
+// tile cut by a range boundary is written, output-transformed but without bias,
+// to the range's head or tail slot in the workspace, and wino_fixup_kernel adds
+// the two halves in a fixed order.  G <= number of tiles, so a tile is cut at
+// most once.
+//
+// VEC: patch rows are fetched as dword + 8-byte + dword; needs pad_w <= 1 and an
+// even width so that the middle two columns are always inside the image.
 template <bool VEC>
 __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 {
@@ -133,28 +146,28 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    // filter tile slowest: an XCD's contiguous run of blocks shares one slice of U
-    const int logical = xcd_remap_wino(blockIdx.x, gridDim.x);
-    const int tt = logical % a.tiles_t;
-    const int kt = logical / a.tiles_t;
+    // XCD-contiguous ranges: an XCD then works on few filter tiles at a time and
+    // keeps their slices of U in its L2
+    const int G = gridDim.x;
+    const int lb = xcd_remap_wino(blockIdx.x, G);
+    const int ub = (int)((int64_t)lb * a.units_total / G);
+    const int ue = (int)((int64_t)(lb + 1) * a.units_total / G);
+    const int nunits = ue - ub;
+    if (nunits <= 0) return;
+    const int nchunks = a.nchunks;
 
-    // ---- this thread's input tile (fixed for the whole kernel) ----
     // Patch elements are fetched with buffer loads: the per-thread byte offset of
-    // each element (inside channel 0 of its image) never changes, the channel
-    // advances through the scalar offset, and elements outside the image carry
-    // an offset beyond the buffer, for which the hardware range check (done per
-    // dword) returns 0: that zero padding costs no instruction.
-    // VEC (pad_w <= 1, even width): a patch row is one dword (column 0) plus one
-    // 12-byte load (columns 1..3, whose start offset is never negative); column 3
-    // can then alias the next row in memory and is cleared by a select instead.
+    // each element (inside channel 0 of its image) is fixed per tile block, the
+    // channel advances through the scalar offset, and elements outside the image
+    // carry an offset beyond the buffer, for which the hardware range check (done
+    // per dword) returns 0: zero padding costs no instruction.
     const int HW = a.Hin * a.Win;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t ursrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.U, 0, a.u_bytes, 0x00020000);
     uint32_t eoff[16];      // byte offset of patch element 4*i+j inside channel 0 (or 2^31)
-    bool cok[4];            // patch column inside the image
-    {
+    auto set_tile_block = [&](int tt) {
         const int tile = tt * TB + lane;
         const bool tv = tile < a.T;
         const int tl = tv ? tile : 0;
@@ -162,19 +175,16 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
         const int th = rem / a.TW, tw = rem - th * a.TW;
         const int ih0 = 2 * th - a.pad_h, iw0 = 2 * tw - a.pad_w;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) cok[j] = (unsigned)(iw0 + j) < (unsigned)a.Win;
-#pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool rok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin;
-                // VEC: columns 1..3 come from one 12-byte load at column 1, which
-                // only needs the row to be valid (its start is never negative)
-                const bool ok = rok && ((VEC && j == 1) ? true : cok[j]);
+                if (VEC && j == 2) continue;        // fetched together with column 1
+                const bool ok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin &&
+                                (unsigned)(iw0 + j) < (unsigned)a.Win;
                 const int idx = n * a.Cin * HW + (ih0 + i) * a.Win + (iw0 + j);
                 eoff[4 * i + j] = ok ? (uint32_t)idx * 4u : 0x80000000u;
             }
-    }
+    };
     // wave w transforms channels w and w+4 of every chunk
     const int x_chunk = CB * HW * 4;                  // bytes per chunk of channels
     const int xs0 = wave * HW * 4, xs1 = xs0 + 4 * HW * 4;
@@ -182,53 +192,46 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     // U tile copy: 8 float4 per thread per chunk; vector v = tid + 256*i ->
     // pos = 2*i + tid/128, row = (tid%128)/16, column quad = tid%16
     const int u_row = (tid & 127) >> 4, u_c4 = tid & 15, u_p0 = tid >> 7;
-    uint32_t uoff[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        uoff[i] = (uint32_t)((((int64_t)(2 * i + u_p0) * a.Cpad + u_row) * a.Kpad + kt * KB + u_c4 * 4) * 4);
+    // (vector i differs from vector 0 only by a uniform stride: it goes into the
+    // scalar offset, leaving a single per-thread offset register)
+    const uint32_t uoff0 = (uint32_t)((((int64_t)u_p0 * a.Cpad + u_row) * a.Kpad + u_c4 * 4) * 4);
+    const int u_vec_stride = 2 * a.Cpad * a.Kpad * 4;
     const int u_chunk = CB * a.Kpad * 4;
 
     float xr[2][16];
     floatx4 ur[8];
-
-    typedef float floatx3 __attribute__((ext_vector_type(3)));
-    // load number l of an item: VEC: 8 loads (row l/2: column 0, then columns 1..3);
-    // otherwise 16 single elements in column-major order
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    constexpr int XLOADS = VEC ? 12 : 16;
+    // load number l of an item.  VEC: row l/3: column 0, columns 1-2, column 3;
+    // otherwise the 16 elements in column-major order (the order of consumption)
     auto load_x = [&](int it, int l, int chunk) {
         const int so = chunk * x_chunk + (it ? xs1 : xs0);
         if (VEC) {
-            const int i = l >> 1;
-            if ((l & 1) == 0) {
-                xr[it][4 * i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[4 * i], so, 0));
-            } else {
+            const int i = l / 3, part = l - 3 * i;
+            if (part == 1) {
                 // (cast the whole result vector, then index the cast value)
-                const floatx3 v = __builtin_bit_cast(
-                    floatx3, __builtin_amdgcn_raw_buffer_load_b96(xrsrc, eoff[4 * i + 1], so, 0));
+                const floatx2 v = __builtin_bit_cast(
+                    floatx2, __builtin_amdgcn_raw_buffer_load_b64(xrsrc, eoff[4 * i + 1], so, 0));
                 xr[it][4 * i + 1] = v[0];
                 xr[it][4 * i + 2] = v[1];
-                xr[it][4 * i + 3] = v[2];
+            } else {
+                const int e = 4 * i + (part == 0 ? 0 : 3);
+                xr[it][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[e], so, 0));
             }
         } else {
             const int e = 4 * (l & 3) + (l >> 2);
             xr[it][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, eoff[e], so, 0));
         }
     };
-    constexpr int XLOADS = VEC ? 8 : 16;
-    auto load_u = [&](int i, int chunk) {
-        ur[i] = __builtin_bit_cast(floatx4,
-                                   __builtin_amdgcn_raw_buffer_load_b128(ursrc, uoff[i], chunk * u_chunk, 0));
+    auto load_u = [&](int i, int kt, int chunk) {
+        ur[i] = __builtin_bit_cast(
+            floatx4, __builtin_amdgcn_raw_buffer_load_b128(ursrc, uoff0, chunk * u_chunk + kt * (KB * 4) + i * u_vec_stride, 0));
     };
 
     // input transform of item `it`, in two stages of four pieces each
     float tr[2][16];
     auto xform_col = [&](int it, int j) {     // stage 1 on patch column j: t = B^T d
-        float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
-        if (VEC && j == 3) {                     // column past the right edge
-            d0 = cok[j] ? d0 : 0.f;
-            d1 = cok[j] ? d1 : 0.f;
-            d2 = cok[j] ? d2 : 0.f;
-            d3 = cok[j] ? d3 : 0.f;
-        }
+        const float d0 = xr[it][0 + j], d1 = xr[it][4 + j], d2 = xr[it][8 + j], d3 = xr[it][12 + j];
         tr[it][0 + j] = d0 - d2;
         tr[it][4 + j] = d1 + d2;
         tr[it][8 + j] = d2 - d1;
@@ -264,15 +267,112 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
             }
     };
 
-    const int nchunks = a.Cin / CB;
-    const int lastc = nchunks - 1;
-    // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 into registers ----
+    // output transform of the finished (or cut) tile in registers; accumulator
+    // element v of lane L: filter row 8*(v/4) + 4*(L/32) + v%4, tile column L%32
+    auto finish_tile = [&](int tile_id, int first_unit) {
+        const int kt = tile_id / a.tiles_t, tt = tile_id - kt * a.tiles_t;
+        const bool head = first_unit < ub, tail = first_unit + nchunks > ue;
+        float *slot = a.partial + ((int64_t)lb * 2 + (head ? 0 : 1)) * (KB * TB * 4);
+        const int tile = tt * TB + wn0 + l32;
+        const bool tv = tile < a.T;
+        const int tl = tv ? tile : 0;
+        const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
+        const int th = rem / a.TW, tw = rem - th * a.TW;
+        const int oh = 2 * th, ow = 2 * tw;
+        const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+        const int HWo = a.Hout * a.Wout;
+        float *obase = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow;
+        // 2x2 outputs of accumulator element v (without bias)
+        auto out_xform = [&](int v, float &y00, float &y01, float &y10, float &y11) {
+            float s0[4], s1[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+                s0[j] = m0 + m1 + m2;
+                s1[j] = m1 - m2 - m3;
+            }
+            y00 = s0[0] + s0[1] + s0[2]; y01 = s0[1] - s0[2] - s0[3];
+            y10 = s1[0] + s1[1] + s1[2]; y11 = s1[1] - s1[2] - s1[3];
+        };
+        // (the 16 rounds are kept apart by scheduling fences: scheduled together they
+        // would need all 256 accumulator values in ordinary registers at once)
+        if (head || tail) {
+            float *sp = slot + ((wm0 + 4 * lhi) * TB + wn0 + l32) * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                __builtin_amdgcn_sched_barrier(0);
+                float y00, y01, y10, y11;
+                out_xform(v, y00, y01, y10, y11);
+                const floatx4 o4 = {y00, y01, y10, y11};
+                *reinterpret_cast<floatx4 *>(sp + ((8 * (v >> 2) + (v & 3)) * TB) * 4) = o4;
+            }
+        } else if (tv) {
+            const int kbase = kt * KB + wm0 + 4 * lhi;
+            float *ob = obase + (int64_t)kbase * HWo;
+            const float *bp = a.bias ? a.bias + kbase : nullptr;
+            if (a.vec2) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int kr = 8 * (v >> 2) + (v & 3);
+                    if (kbase + kr < a.Kout) {
+                        float y00, y01, y10, y11;
+                        out_xform(v, y00, y01, y10, y11);
+                        const float bz = bp ? bp[kr] : 0.f;
+                        float *o = ob + (int64_t)kr * HWo;
+                        *reinterpret_cast<float2 *>(o) = make_float2(y00 + bz, y01 + bz);
+                        if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10 + bz, y11 + bz);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int kr = 8 * (v >> 2) + (v & 3);
+                    if (kbase + kr < a.Kout) {
+                        float y00, y01, y10, y11;
+                        out_xform(v, y00, y01, y10, y11);
+                        const float bz = bp ? bp[kr] : 0.f;
+                        float *o = ob + (int64_t)kr * HWo;
+                        o[0] = y00 + bz;
+                        if (col1) o[1] = y01 + bz;
+                        if (row1) {
+                            o[a.Wout] = y10 + bz;
+                            if (col1) o[a.Wout + 1] = y11 + bz;
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+    };
+
+    // cursors (unit -> tile, chunk) of the three pipeline stages; units past the
+    // end of the range are clamped to the last one (harmless reloads)
+    const int ulast = ue - 1;
+    auto tile_of = [&](int u) { return u / nchunks; };
+    int c_tile = tile_of(ub), c_chunk = ub - c_tile * nchunks;          // compute: unit i
+    int u_tile = c_tile, u_chunk_i = c_chunk;                            // filter loads: unit i+1
+    int x_tile = c_tile, x_chunk_i = c_chunk;                            // patch loads: unit i+2
+    auto advance = [&](int &tile, int &chunk, int &unit) {
+        if (unit < ulast) {
+            ++unit;
+            if (++chunk == nchunks) { chunk = 0; ++tile; }
+        }
+    };
+    int u_unit = ub, x_unit = ub;
+
+    // ---- prologue: unit 0 into LDS buffer 0, patch loads of unit 1 ----
+    set_tile_block(x_tile % a.tiles_t);
 #pragma unroll
     for (int it = 0; it < 2; ++it)
 #pragma unroll
-        for (int l = 0; l < XLOADS; ++l) load_x(it, l, 0);
+        for (int l = 0; l < XLOADS; ++l) load_x(it, l, x_chunk_i);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_u(i, 0);
+    for (int i = 0; i < 8; ++i) load_u(i, u_tile / a.tiles_t, u_chunk_i);
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
 #pragma unroll
@@ -283,91 +383,114 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 #pragma unroll
     for (int i = 0; i < 8; ++i) store_u(0, i);
     {
-        const int c1 = lastc < 1 ? lastc : 1;
+        const int before = x_tile;
+        advance(x_tile, x_chunk_i, x_unit);
+        if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
 #pragma unroll
         for (int it = 0; it < 2; ++it)
 #pragma unroll
-            for (int l = 0; l < XLOADS; ++l) load_x(it, l, c1);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) load_u(i, c1);
+            for (int l = 0; l < XLOADS; ++l) load_x(it, l, x_chunk_i);
+        advance(u_tile, u_chunk_i, u_unit);
     }
     lds_barrier_wg();
     read_pair(0, 0, 0);
 
-    for (int t = 0; t < nchunks; ++t) {
-        const int buf = t & 1;
-        const int t2 = (t + 2 < nchunks) ? t + 2 : lastc;
-#pragma unroll
-        for (int pair = 0; pair < 8; ++pair) {
-            const int cur = pair & 1, nxt = cur ^ 1;
-            if (pair + 1 < 8) {
-                read_pair(buf, pair + 1, nxt);
-            } else {
-                lds_barrier_wg();
-                read_pair(buf ^ 1, 0, nxt);
+    // 64 MFMA slots per unit i:
+    //   slots  0..15 : input transform + LDS writes of unit i+1 (registers loaded
+    //                  during unit i-1); slots 0..7 also issue the filter-tile
+    //                  loads of unit i+1
+    //   slots 16..47 : the patch loads of unit i+2
+    //   slots 48..55 : filter tile of unit i+1 to LDS
+    //   slot  56     : LDS-only barrier, then the first operands of unit i+1
+    // Outer loop: one segment per output tile touched by the range; the inner loop
+    // is the pipelined chunk loop, in which the accumulators are only ever used by
+    // MFMAs (they stay in the accumulator register file); the output transform
+    // runs between segments while the next tile's loads are already in flight.
+    int first_unit = ub - c_chunk;          // first unit of the compute tile
+    int i = 0;
+    while (i < nunits) {
+        int seg_end = i + (nchunks - c_chunk);
+        if (seg_end > nunits) seg_end = nunits;
+        for (; i < seg_end; ++i) {
+            const int buf = i & 1;
+            const int ukt = u_tile / a.tiles_t;
+            {
+                const int before = x_tile;
+                advance(x_tile, x_chunk_i, x_unit);
+                // the patch registers still hold unit i+1 (transformed in slots 0..15);
+                // the offsets are only used from slot 16 on
+                if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
             }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int s = pair * 8 + q;      // MFMA slot 0..63 of this chunk
-                // slots 0..15: transform + LDS write of the two items of chunk t+1
-                if (s < 16) {
-                    const int it = s >> 3, piece = s & 7;
-                    if (piece < 4) xform_col(it, piece); else xform_row_store(buf ^ 1, it, piece - 4);
-                } else if (s < 24) {
-                    store_u(buf ^ 1, s - 16);
-                } else if (s < 56) {
-                    // global loads of chunk t+2, in the order they are consumed
-                    // (item, patch column, row)
-                    const int l = s - 24, it = l >> 4, j = (l >> 2) & 3, i = l & 3;
-                    load_x(it, 4 * i + j, t2);
+    #pragma unroll
+            for (int pair = 0; pair < 8; ++pair) {
+                const int cur = pair & 1, nxt = cur ^ 1;
+                if (pair + 1 < 8) {
+                    read_pair(buf, pair + 1, nxt);
                 } else {
-                    load_u(s - 56, t2);
+                    lds_barrier_wg();
+                    read_pair(buf ^ 1, 0, nxt);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                const int u = q & 1, ks = q >> 1;
-                acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ao[cur][u][ks], bo[cur][u][ks],
-                                                                          acc[2 * pair + u], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int s = pair * 8 + q;      // MFMA slot 0..63 of this unit
+                    if (s < 16) {
+                        const int it = s >> 3, piece = s & 7;
+                        if (piece < 4) xform_col(it, piece); else xform_row_store(buf ^ 1, it, piece - 4);
+                        if (s < 8) load_u(s, ukt, u_chunk_i);
+                    } else if (s < 48) {
+                        const int l = s - 16;        // 32 slots for 2 * XLOADS loads
+    #pragma unroll
+                        for (int m = 0; m < 2 * XLOADS; ++m)
+                            if (m * 32 / (2 * XLOADS) == l) load_x(m / XLOADS, m % XLOADS, x_chunk_i);
+                    } else if (s < 56) {
+                        store_u(buf ^ 1, s - 48);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int u = q & 1, ks = q >> 1;
+                    acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ao[cur][u][ks], bo[cur][u][ks],
+                                                                              acc[2 * pair + u], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
+            advance(u_tile, u_chunk_i, u_unit);
         }
+        finish_tile(c_tile, first_unit);
+        first_unit += nchunks;
+        ++c_tile;
+        c_chunk = 0;
     }
+}
 
-    // ---- epilogue: output transform in registers, bias, store ----
-    // accumulator element v of lane L: filter row 8*(v/4) + 4*(L/32) + v%4,
-    // tile column L%32 of this wave's 32x32 sub-tile
-    const int tile = tt * TB + wn0 + l32;
-    if (tile >= a.T) return;
-    const int n = tile / (a.TH * a.TW), rem = tile - n * (a.TH * a.TW);
-    const int th = rem / a.TW, tw = rem - th * a.TW;
-    const int oh = 2 * th, ow = 2 * tw;
-    const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+// Adds the two halves of every tile that a range boundary cut: boundary b lies
+// between ranges b and b+1; tail slot of b + head slot of b+1 + bias -> y.
+__global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
+{
+    constexpr int KB = kWinoKB, TB = kWinoTB;
+    const int b = blockIdx.x;                 // boundary between logical ranges b and b+1
+    const int unit = (int)((int64_t)(b + 1) * a.units_total / G);
+    if (unit % a.nchunks == 0) return;        // boundary on a tile edge: nothing was cut
+    const int tile_id = unit / a.nchunks;
+    const int kt = tile_id / a.tiles_t, tt = tile_id - kt * a.tiles_t;
+    const float *tailp = a.partial + ((int64_t)b * 2 + 1) * (KB * TB * 4);
+    const float *headp = a.partial + ((int64_t)(b + 1) * 2 + 0) * (KB * TB * 4);
     const int HWo = a.Hout * a.Wout;
-    float *obase = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int k = kt * KB + wm0 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-        if (k >= a.Kout) continue;
-        float s0[4], s1[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
-            s0[j] = m0 + m1 + m2;
-            s1[j] = m1 - m2 - m3;
-        }
+    for (int e = threadIdx.x; e < KB * TB; e += 256) {
+        const int kl = e / TB, tloc = e - kl * TB;
+        const int k = kt * KB + kl, tile = tt * TB + tloc;
+        if (k >= a.Kout || tile >= a.T) continue;
+        const floatx4 p = *reinterpret_cast<const floatx4 *>(tailp + e * 4);
+        const floatx4 q = *reinterpret_cast<const floatx4 *>(headp + e * 4);
         const float bz = a.bias ? a.bias[k] : 0.f;
-        const float y00 = s0[0] + s0[1] + s0[2] + bz, y01 = s0[1] - s0[2] - s0[3] + bz;
-        const float y10 = s1[0] + s1[1] + s1[2] + bz, y11 = s1[1] - s1[2] - s1[3] + bz;
-        float *o = obase + (int64_t)k * HWo;
-        if (a.vec2) {
-            *reinterpret_cast<float2 *>(o) = make_float2(y00, y01);
-            if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10, y11);
-        } else {
-            o[0] = y00;
-            if (col1) o[1] = y01;
-            if (row1) {
-                o[a.Wout] = y10;
-                if (col1) o[a.Wout + 1] = y11;
-            }
+        const int n = tile / (a.TH * a.TW), rem = tile - n * (a.TH * a.TW);
+        const int th = rem / a.TW, tw = rem - th * a.TW;
+        const int oh = 2 * th, ow = 2 * tw;
+        float *o = a.out + ((int64_t)n * a.Kout + k) * HWo + (int64_t)oh * a.Wout + ow;
+        const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+        o[0] = p[0] + q[0] + bz;
+        if (col1) o[1] = p[1] + q[1] + bz;
+        if (row1) {
+            o[a.Wout] = p[2] + q[2] + bz;
+            if (col1) o[a.Wout + 1] = p[3] + q[3] + bz;
         }
     }
 }
@@ -375,9 +498,10 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 int wino_filter_tile() { return kWinoKB; }
 int wino_tile_block() { return kWinoTB; }
 int wino_chan_chunk() { return kWinoCB; }
+int wino_partial_slot_floats() { return kWinoKB * kWinoTB * 4; }
 
 template <bool VEC>
-static hipError_t launch_wino_variant(const WinoArgs &a, hipStream_t s)
+static hipError_t launch_wino_variant(const WinoArgs &a, int G, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
@@ -386,15 +510,18 @@ static hipError_t launch_wino_variant(const WinoArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((wino_fused_kernel<VEC>), dim3((unsigned)(a.tiles_t * a.tiles_k)),
-                       dim3(256), kWinoLdsBytes, s, a);
+    hipLaunchKernelGGL((wino_fused_kernel<VEC>), dim3((unsigned)G), dim3(256), kWinoLdsBytes, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_wino_fused(const WinoArgs &a, hipStream_t s)
+hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s)
 {
-    if (a.pad_w > 1 || a.Win % 2 != 0) return launch_wino_variant<false>(a, s);
-    return launch_wino_variant<true>(a, s);
+    hipError_t e;
+    if (a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
+    else e = launch_wino_variant<true>(a, G, s);
+    if (e != hipSuccess || G < 2) return e;
+    hipLaunchKernelGGL(wino_fixup_kernel, dim3((unsigned)(G - 1)), dim3(256), 0, s, a, G);
+    return hipGetLastError();
 }
 
 }  // namespace mi355conv

@@ -140,6 +140,10 @@ WINO_SHAPES = [
     G(2, 16, 10, 7, 16, 3, 3, 1, 2),         # full padding
     (2, 8, 11, 12, 24, 3, 3, 1, 1, 0, 2),    # pad_h != pad_w
     G(5, 40, 28, 28, 136, 3, 3, 1, 1),
+    # more output tiles than compute units: unit ranges cut tiles (fixup path), with
+    # ragged filter and tile counts; second shape cuts tiles in backward-data
+    G(40, 16, 28, 28, 136, 3, 3, 1, 1),
+    G(36, 136, 26, 26, 24, 3, 3, 1, 1),
 ]
 
 
