@@ -43,15 +43,22 @@ int check_desc(const conv2d_desc *d, Geom *g)
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 int round_up(int a, int b) { return ceil_div(a, b) * b; }
 
-// Filter-tile choice of the gather kernel: least padded filters, with a small
-// handicap for the narrower tiles (they re-gather the same pixels more often).
-int pick_gather_tile(int filters)
+// Tile choice of the gather kernel from a small cost model: a workgroup's depth
+// step costs 64 issue cycles per MFMA plus ~4.3 per other instruction (measured:
+// other instructions barely overlap MFMAs, not even those of another wave on the
+// same SIMD, so co-resident workgroups share a compute unit's time rather than
+// multiply its throughput), i.e. about 2600 / 3050 / 1950 / 2200 cycles for the
+// 128x128 / 64x256 / 32x256 / 96x128 tiles; the busiest of the 256 compute units
+// executes ceil(blocks / 256) workgroups.
+int pick_gather_tile(int filters, int64_t pixels)
 {
-    static const double handicap[3] = {1.0, 1.03, 1.10};
+    static const double step_cycles[4] = {2608.0, 3040.0, 1970.0, 2180.0};
     int best = 0;
-    double best_cost = 1e30;
-    for (int t = 0; t < 3; ++t) {
-        const double cost = round_up(filters, gemmconv_filter_tile(t)) * handicap[t];
+    double best_cost = 1e300;
+    for (int t = 0; t < 4; ++t) {
+        const int64_t blocks = (int64_t)ceil_div(filters, gemmconv_filter_tile(t)) *
+                               ((pixels + gemmconv_pixel_tile(t) - 1) / gemmconv_pixel_tile(t));
+        const double cost = (double)((blocks + 255) / 256) * step_cycles[t];
         if (cost < best_cost) { best_cost = cost; best = t; }
     }
     return best;
@@ -71,7 +78,11 @@ int pick_wgrad_tile(int filters, int crs)
 }
 
 // ---- workspace plans -------------------------------------------------------
+int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+
 struct GatherPlan {
+    int d2s;                    // backward-data as one gather with depth-to-space rows
+    int dr_min, nd_r, dt_min, nd_t;
     int tile, Kpad;             // Kpad: columns of the filter matrix
     int nphases;                // all phases (may exceed kMaxPhases: launched in groups)
     int64_t rows_total;         // padded rows over all phases
@@ -102,8 +113,8 @@ PhaseGeom bwd_phase(const Geom &g, int a, int b)
 
 GatherPlan plan_fwd(const Geom &g)
 {
-    GatherPlan p;
-    p.tile = pick_gather_tile(g.K);
+    GatherPlan p = {};
+    p.tile = pick_gather_tile(g.K, (int64_t)g.N * g.P * g.Q);
     p.Kpad = round_up(g.K, gemmconv_filter_tile(p.tile));
     p.nphases = 1;
     p.rows_total = round_up(g.C * g.R * g.S, kDepthTile);
@@ -115,8 +126,35 @@ GatherPlan plan_fwd(const Geom &g)
 
 GatherPlan plan_bwd_data(const Geom &g)
 {
-    GatherPlan p;
-    p.tile = pick_gather_tile(g.C);
+    GatherPlan p = {};
+    // Strided layers with few input channels (first layers): instead of one
+    // sub-convolution per phase with C (<< 32) GEMM rows each, compute the
+    // stride_h*stride_w*C values of every stride x stride block of dx as the rows of
+    // ONE stride-1 gather over the union of the phases' tap displacements.
+    if (g.sh * g.sw > 1) {
+        const int rows = g.sh * g.sw * g.C;
+        p.dr_min = floor_div(g.ph - g.R + 1 + g.sh - 1, g.sh);          // ceil((ph-R+1)/sh)
+        p.dt_min = floor_div(g.pw - g.S + 1 + g.sw - 1, g.sw);
+        p.nd_r = floor_div(g.sh - 1 + g.ph, g.sh) - p.dr_min + 1;
+        p.nd_t = floor_div(g.sw - 1 + g.pw, g.sw) - p.dt_min + 1;
+        const int64_t block_pixels = (int64_t)g.N * ceil_div(g.H, g.sh) * ceil_div(g.W, g.sw);
+        const int tile = pick_gather_tile(rows, block_pixels);
+        const double cost_d2s = (double)round_up(rows, gemmconv_filter_tile(tile)) * p.nd_r * p.nd_t;
+        const int ptile = pick_gather_tile(g.C, block_pixels);
+        const double cost_phase = (double)round_up(g.C, gemmconv_filter_tile(ptile)) * g.R * g.S;
+        if (rows <= 256 && cost_d2s < cost_phase) {
+            p.d2s = 1;
+            p.tile = tile;
+            p.Kpad = round_up(rows, gemmconv_filter_tile(tile));
+            p.nphases = 1;
+            p.rows_total = round_up(g.K * p.nd_r * p.nd_t, kDepthTile);
+            p.wt_bytes = align_up((size_t)p.rows_total * p.Kpad * sizeof(float), 256);
+            p.tab_bytes = align_up((size_t)p.rows_total * sizeof(DepthEntry), 256);
+            p.total_bytes = p.wt_bytes + p.tab_bytes;
+            return p;
+        }
+    }
+    p.tile = pick_gather_tile(g.C, (int64_t)g.N * ceil_div(g.H, g.sh) * ceil_div(g.W, g.sw));
     p.Kpad = round_up(g.C, gemmconv_filter_tile(p.tile));
     p.nphases = g.sh * g.sw;
     p.rows_total = 0;
@@ -419,6 +457,32 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
     a.out_chan_stride = g.H * g.W; a.out_img_stride = g.C * g.H * g.W;
     a.in_step_h = 1; a.in_step_w = 1; a.out_step_h = g.sh; a.out_step_w = g.sw;
     a.tiles_k = p.Kpad / gemmconv_filter_tile(p.tile);
+
+    if (p.d2s) {
+        PrepArgs pa = {};
+        pa.w = w; pa.wt = wt; pa.tab = tab; pa.mode = 2;
+        pa.K = g.K; pa.C = g.C; pa.R = g.R; pa.S = g.S; pa.Kpad = p.Kpad;
+        pa.gather_chan_stride = g.P * g.Q; pa.gather_W = g.Q;
+        pa.stride_h = g.sh; pa.stride_w = g.sw; pa.pad_h = g.ph; pa.pad_w = g.pw;
+        pa.dr_min = p.dr_min; pa.nd_r = p.nd_r; pa.dt_min = p.dt_min; pa.nd_t = p.nd_t;
+        pa.nphases = 1;
+        pa.rows_total = (int32_t)p.rows_total;
+        pa.ph[0].row0 = 0; pa.ph[0].rows = g.K * p.nd_r * p.nd_t; pa.ph[0].rows_pad = (int32_t)p.rows_total;
+        rc = launch_status(launch_gemmconv_prep(pa, s));
+        if (rc) return rc;
+        const int Hs = ceil_div(g.H, g.sh), Ws = ceil_div(g.W, g.sw);
+        a.Kout = g.sh * g.sw * g.C;
+        a.d2s_C = g.C; a.d2s_sh = g.sh; a.d2s_sw = g.sw;
+        a.div_d2s_C = make_fastdiv((uint32_t)g.C);
+        a.div_d2s_sw = make_fastdiv((uint32_t)g.sw);
+        a.tiles_pix = ceil_div(g.N * Hs * Ws, BN);
+        a.phase[0].row0 = 0;
+        a.phase[0].depth_tiles = (int32_t)(p.rows_total / kDepthTile);
+        a.phase[0].in_base_h = 0; a.phase[0].in_base_w = 0;
+        a.phase[0].out_base_h = 0; a.phase[0].out_base_w = 0;
+        a.phase[0].Hs = Hs; a.phase[0].Ws = Ws;
+        return launch_status(launch_gemmconv(a, p.tile, 1, s));
+    }
 
     // phases are prepared and launched in groups of at most kMaxPhases
     int64_t row_cursor = 0;

@@ -73,6 +73,11 @@ struct GemmConvArgs {
     int32_t Kout, Kpad, Hout, Wout, out_chan_stride, out_img_stride;
     int32_t in_step_h, in_step_w, out_step_h, out_step_w;
     int32_t tiles_k, tiles_pix;   // grid.x = tiles_k * tiles_pix (max over phases)
+    // depth-to-space epilogue (strided backward-data with few channels): GEMM row
+    // k' = (a*d2s_sw + b)*d2s_C + c is stored to out[n][c][oh*d2s_sh + a][ow*d2s_sw + b];
+    // d2s_C == 0 selects the ordinary epilogue
+    int32_t d2s_C, d2s_sh, d2s_sw;
+    FastDiv div_d2s_C, div_d2s_sw;
     Phase phase[kMaxPhases];
 };
 
@@ -85,15 +90,18 @@ struct PrepArgs {
     const float *w;
     float *wt;
     DepthEntry *tab;
-    int32_t mode;               // 0 forward, 1 backward-data
+    int32_t mode;               // 0 forward, 1 backward-data by phases, 2 backward-data
+                                //   as one stride-1 gather with depth-to-space rows
     int32_t K, C, R, S, Kpad;   // Kpad = row pitch of wt
     int32_t gather_chan_stride, gather_W;   // of the tensor the main kernel gathers from
     int32_t stride_h, stride_w;
     int32_t rows_total, nphases;
+    int32_t pad_h, pad_w;       // mode 2
+    int32_t dr_min, nd_r, dt_min, nd_t;   // mode 2: tap displacements dr_min .. dr_min+nd_r-1
     PrepPhase ph[kMaxPhases];
 };
 
-// gather tile = 0: 128 filters x 128 pixels, 1: 64 x 256, 2: 32 x 256
+// gather tile = 0: 128 filters x 128 pixels, 1: 64 x 256, 2: 32 x 256, 3: 96 x 128
 int gemmconv_filter_tile(int tile);
 int gemmconv_pixel_tile(int tile);
 hipError_t launch_gemmconv_prep(const PrepArgs &a, hipStream_t s);

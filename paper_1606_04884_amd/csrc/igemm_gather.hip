@@ -46,6 +46,24 @@ __global__ __launch_bounds__(256) void gemmconv_prep_kernel(PrepArgs a)
                 e.off = c * a.gather_chan_stride + r * a.gather_W + t;
                 e.drdt = (int32_t)(((uint32_t)r << 16) | ((uint32_t)t & 0xffffu));
                 if (col < a.K) v = a.w[(int64_t)col * a.C * RS + d];
+            } else if (a.mode == 2) {
+                // backward-data, all phases at once: row d = (k, dr, dt) over the union of
+                // the phases' tap displacements, column k' = (pa, pb, c): output pixel
+                // (oh*sh + pa, ow*sw + pb) of channel c receives dy[oh + dr][ow + dt] through
+                // the tap r = pa + pad_h - dr*sh, t = pb + pad_w - dt*sw (if that tap exists)
+                const int ndd = a.nd_r * a.nd_t;
+                const int k = d / ndd, rt = d - k * ndd, ir = rt / a.nd_t, it = rt - ir * a.nd_t;
+                const int dr = a.dr_min + ir, dt = a.dt_min + it;
+                e.off = k * a.gather_chan_stride + dr * a.gather_W + dt;
+                e.drdt = (int32_t)(((uint32_t)dr << 16) | ((uint32_t)dt & 0xffffu));
+                const int cols = a.stride_h * a.stride_w * a.C;
+                if (col < cols) {
+                    const int pab = col / a.C, c = col - pab * a.C;
+                    const int pa = pab / a.stride_w, pb = pab - pa * a.stride_w;
+                    const int r = pa + a.pad_h - dr * a.stride_h, t = pb + a.pad_w - dt * a.stride_w;
+                    if (r >= 0 && r < a.R && t >= 0 && t < a.S)
+                        v = a.w[(((int64_t)k * a.C + c) * a.R + r) * a.S + t];
+                }
             } else {
                 // backward-data: row d = (k, r', t') of this phase, column = channel c
                 const int nrt = ph.nr * ph.nt;
@@ -278,6 +296,30 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
             const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
             bz[mi][v] = (a.bias && k < a.Kout) ? a.bias[k] : 0.f;
         }
+    if (a.d2s_C > 0) {
+        // depth-to-space store: GEMM row k' -> (pa, pb, c)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int m = pt * BN + wn0 + ni * 32 + l32;
+            if (m >= Mpix) continue;
+            const int n = m / HWs, rem = m - n * HWs;
+            const int oh = rem / ph.Ws, ow = rem - oh * ph.Ws;
+            const int h0 = oh * a.d2s_sh, v0 = ow * a.d2s_sw;
+            float *op = a.out + (int64_t)n * a.out_img_stride + h0 * a.Wout + v0;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                    const int pab = (int)fast_div((uint32_t)k, a.div_d2s_C), c = k - pab * a.d2s_C;
+                    const int pa = (int)fast_div((uint32_t)pab, a.div_d2s_sw), pb = pab - pa * a.d2s_sw;
+                    if (k < a.Kout && h0 + pa < a.Hout && v0 + pb < a.Wout)
+                        op[(int64_t)c * a.out_chan_stride + pa * a.Wout + pb] = acc[mi][ni][v];
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
         const int m = pt * BN + wn0 + ni * 32 + l32;
@@ -298,8 +340,8 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
     }
 }
 
-static const int kFilterTile[3] = {128, 64, 32};
-static const int kPixelTile[3] = {128, 256, 256};
+static const int kFilterTile[4] = {128, 64, 32, 96};
+static const int kPixelTile[4] = {128, 256, 256, 128};
 int gemmconv_filter_tile(int tile) { return kFilterTile[tile]; }
 int gemmconv_pixel_tile(int tile) { return kPixelTile[tile]; }
 
@@ -313,8 +355,11 @@ hipError_t launch_gemmconv(const GemmConvArgs &a, int tile, int nphases, hipStre
     case 1:
         hipLaunchKernelGGL((gemmconv_kernel<64, 256, 64, 64>), grid, dim3(256), 0, s, a);
         break;
-    default:
+    case 2:
         hipLaunchKernelGGL((gemmconv_kernel<32, 256, 32, 64>), grid, dim3(256), 0, s, a);
+        break;
+    default:    // 96 filters: three 32-row MFMA tiles per wave (filter counts 96, 192, ...)
+        hipLaunchKernelGGL((gemmconv_kernel<96, 128, 96, 32>), grid, dim3(256), 0, s, a);
         break;
     }
     return hipGetLastError();

@@ -41,6 +41,8 @@ SHAPES = [
     G(2, 6, 15, 11, 10, 1, 1, 2, 0),         # 1x1 stride 2: phases without taps
     (2, 4, 17, 14, 9, 3, 5, 2, 3, 1, 2),     # stride_h != stride_w, pad_h != pad_w
     (1, 3, 30, 9, 5, 7, 1, 5, 1, 3, 0),      # stride 5 in h: 5 phases
+    G(2, 40, 15, 16, 24, 3, 3, 2, 1),        # strided with many channels: per-phase backward-data
+    G(2, 3, 23, 23, 16, 5, 5, 2, 2),         # strided with few channels: depth-to-space backward-data
 ]
 
 
