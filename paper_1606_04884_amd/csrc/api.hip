@@ -182,11 +182,10 @@ WgradPlan plan_wgrad(const Geom &g)
     p.tiles_j = ceil_div(CRS, wgrad_col_tile(p.tile));
     const int tiles = p.tiles_k * p.tiles_j;
     // Choose the number of ranges the reduction axis is cut into.  All workgroups
-    // take equally long, so the grid should fill the machine's resident slots
-    // (256 compute units x 2 workgroups) a whole number of times; more splits
-    // also mean more partial tiles to write and add up again.  Minimise an
-    // estimate of MFMA time / slot efficiency + partial-sum traffic time.
-    const double slots = 512.0;
+    // take equally long and co-resident ones share a compute unit's time, so the
+    // busiest of the 256 compute units runs ceil(blocks / 256) of them; more
+    // splits also mean more partial tiles to write and a longer chain of adds in
+    // the reduction kernel.  Minimise an estimate of the three.
     const double flops = 2.0 * (double)M * g.K * CRS;
     int64_t max_splits = (M + 255) / 256;            // at least 256 pixels of depth each
     if (max_splits > 4096) max_splits = 4096;
@@ -195,11 +194,12 @@ WgradPlan plan_wgrad(const Geom &g)
     double best_t = 1e300;
     for (int64_t sp = 1; sp <= max_splits; ++sp) {
         const double blocks = (double)tiles * sp;
-        const double rounds = (double)((int64_t)((blocks + slots - 1) / slots));
-        const double eff = blocks / (rounds * slots);
-        const double t_mfma = flops / (0.65 * 155e12) / eff;
+        const double rounds = (double)((int64_t)((blocks + 255) / 256));
+        const double eff = blocks / (rounds * 256.0);
+        const double t_mfma = flops / (0.6 * 155e12) / eff;
         const double t_part = 2.0 * sp * g.K * (double)CRS * 4.0 / 3.0e12;
-        const double t = t_mfma + t_part;
+        const double t_chain = 0.1e-6 * sp;
+        const double t = t_mfma + t_part + t_chain;
         if (t < best_t) { best_t = t; best = (int)sp; }
     }
     int64_t chunk = (M + best - 1) / best;
@@ -295,7 +295,7 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
         const double blocks = (double)tiles * sp;
         const double rounds = (double)((int64_t)((blocks + slots - 1) / slots));
         const double eff = blocks / (rounds * slots);
-        const double t = flops / (0.6 * 155e12) / eff + 2.0 * sp * g.K * (double)g.C * 36.0 / 3.0e12;
+        const double t = flops / (0.6 * 155e12) / eff + 2.0 * sp * g.K * (double)g.C * 36.0 / 3.0e12 + 0.1e-6 * sp;
         if (t < best_t) { best_t = t; best = sp; }
     }
     p.tiles_per_split = round_up(ceil_div(p.T, best), step);
@@ -321,6 +321,13 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
     case CONV2D_ALGO_WINOGRAD: return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ERR_ALGO;
     default: return CONV2D_ERR_ALGO;
     }
+}
+
+// 1x1 stride-1 unpadded layer whose pixel rows can be fetched as aligned 16-byte vectors
+bool pointwise_ok(const Geom &g, const float *in, int64_t in_elems)
+{
+    return g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0 &&
+           (g.H * g.W) % 4 == 0 && ((uintptr_t)in & 15) == 0 && in_elems * 4 < (int64_t(1) << 31);
 }
 
 int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
@@ -429,6 +436,10 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
     a.phase[0].in_base_h = -g.ph; a.phase[0].in_base_w = -g.pw;
     a.phase[0].out_base_h = 0; a.phase[0].out_base_w = 0;
     a.phase[0].Hs = g.P; a.phase[0].Ws = g.Q;
+    if (pointwise_ok(g, x, (int64_t)g.N * g.C * g.H * g.W)) {
+        a.pw_depth = g.C;
+        a.in_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+    }
     return launch_status(launch_gemmconv(a, p.tile, 1, s));
 }
 
@@ -516,6 +527,10 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
             if (rc) return rc;
         }
         a.tiles_pix = tiles_pix;
+        if (pointwise_ok(g, dy, (int64_t)g.N * g.K * g.P * g.Q)) {     // implies a single phase
+            a.pw_depth = g.K;
+            a.in_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+        }
         rc = launch_status(launch_gemmconv(a, p.tile, cnt, s));
         if (rc) return rc;
         row_cursor += group_rows;

@@ -78,6 +78,9 @@ struct GemmConvArgs {
     // d2s_C == 0 selects the ordinary epilogue
     int32_t d2s_C, d2s_sh, d2s_sw;
     FastDiv div_d2s_C, div_d2s_sw;
+    // pointwise fast path (1x1, stride 1, no padding, H*W % 4 == 0): pw_depth = number
+    // of channels of `in` (0 selects the gather path), in_bytes = its size (< 2^31)
+    int32_t pw_depth, in_bytes;
     Phase phase[kMaxPhases];
 };
 

@@ -16,6 +16,8 @@
 
 #include "conv_internal.h"
 
+#include <type_traits>
+
 namespace mi355conv {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -110,7 +112,12 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int BM, int BN, int WM, int WN>
+// PW ("pointwise"): 1x1 stride-1 unpadded layers whose H*W is a multiple of 4.
+// The lowered tile is then a plain [channels x pixels] block of the tensor: it is
+// fetched with 16-byte buffer loads (4 pixels of one channel per thread, fixed
+// per-thread offsets, the depth step in the scalar offset) instead of per-element
+// gathers, which is what lets these HBM-bound layers stream.
+template <int BM, int BN, int WM, int WN, bool PW>
 __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
 {
     constexpr int BK = kDepthTile;
@@ -118,7 +125,10 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
     static_assert((BM / WM) * WAVES_N == 4, "4 waves per workgroup");
     constexpr int MI = WM / 32, NI = WN / 32;
     constexpr int TPP = 256 / BN;            // threads per pixel column: 1 or 2
-    constexpr int B_ROWS = BK / TPP;         // gathered rows per thread
+    // elements fetched per thread and tile: gathered rows, or (PW) 4-pixel vectors
+    constexpr int B_ROWS = PW ? BK * BN / 1024 : BK / TPP;
+    constexpr int PW_VPR = BN / 4;           // PW: vectors per tile row
+    constexpr int PW_RPP = 256 / PW_VPR;     // PW: rows per pass of the 256 threads
     constexpr int A_VECS = BK * BM / 4;      // float4 per filter tile
     constexpr int A_PER_THREAD = (A_VECS + 255) / 256;
     static_assert(BN >= 64 && 256 % BN == 0, "pixel tile");
@@ -155,18 +165,45 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
     const DepthEntry *tab = a.tab + ph.row0;
     const float *wt = a.wt + (int64_t)ph.row0 * a.Kpad + kt * BM;
 
-    float breg[B_ROWS];
+    // PW set-up: this thread's 4 pixels and its rows of every depth tile
+    const __amdgpu_buffer_rsrc_t pw_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, PW ? a.in_bytes : 0, 0x00020000);
+    const int pw_row0 = tid / PW_VPR, pw_col = (tid % PW_VPR) * 4;
+    const int pw_chan_bytes = a.Hin * a.Win * 4;
+    uint32_t pw_off[B_ROWS];
+    if (PW) {
+        const int m = pt * BN + pw_col;
+        const int n = m / HWs, rem = m - n * HWs;          // the 4 pixels share an image (HW % 4 == 0)
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i)
+            pw_off[i] = m < Mpix ? (uint32_t)(n * a.in_img_stride + rem) * 4u + (uint32_t)(pw_row0 + i * PW_RPP) * (uint32_t)pw_chan_bytes
+                                 : 0x80000000u;
+    }
+
+    typename std::conditional<PW, floatx4, float>::type breg[B_ROWS];
     floatx4 areg[A_PER_THREAD];
     uint32_t bmask = 0;    // bit i: gathered element i is inside the image
     DepthEntry ent[B_ROWS];   // table rows of the tile being gathered (wave-uniform: SGPRs)
 
     // This thread gathers rows prow0*B_ROWS .. +B_ROWS-1 of a depth tile: one
     // contiguous run of table entries, fetched with wide scalar loads.
+    int pw_depth0 = 0;       // PW: first channel of the tile being fetched
     auto table_fetch = [&](int tile) {
+        if constexpr (PW) {
+            pw_depth0 = tile * BK;
+        } else {
 #pragma unroll
-        for (int i = 0; i < B_ROWS; ++i) ent[i] = tab[tile * BK + prow0 * B_ROWS + i];
+            for (int i = 0; i < B_ROWS; ++i) ent[i] = tab[tile * BK + prow0 * B_ROWS + i];
+        }
     };
     auto gather_issue = [&](int i) {
+        if constexpr (PW) {
+            // channels past the real depth (padding rows of the last tile) read as 0
+            const uint32_t off = (pw_depth0 + pw_row0 + i * PW_RPP < a.pw_depth) ? pw_off[i] : 0x80000000u;
+            breg[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                      pw_rsrc, off, pw_depth0 * pw_chan_bytes, 0));
+            return;
+        } else {
         const DepthEntry e = ent[i];
         const int dr = e.drdt >> 16;
         const int dt = (int)(short)(e.drdt & 0xffff);
@@ -175,6 +212,7 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
         const int idx = ok ? gbase + e.off : 0;
         breg[i] = a.in[idx];
         bmask = (bmask & ~(1u << i)) | (ok ? (1u << i) : 0u);
+        }
     };
     auto filter_issue = [&](int tile, int i) {
         const int vi = tid + i * 256;
@@ -184,7 +222,11 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
         }
     };
     auto store_b = [&](int buf, int i) {
-        Bs[buf][prow0 * B_ROWS + i][pcol] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
+        if constexpr (PW) {
+            *reinterpret_cast<floatx4 *>(&Bs[buf][pw_row0 + i * PW_RPP][pw_col]) = breg[i];
+        } else {
+            Bs[buf][prow0 * B_ROWS + i][pcol] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
+        }
     };
     auto store_a = [&](int buf, int i) {
         const int vi = tid + i * 256;
@@ -345,23 +387,30 @@ static const int kPixelTile[4] = {128, 256, 256, 128};
 int gemmconv_filter_tile(int tile) { return kFilterTile[tile]; }
 int gemmconv_pixel_tile(int tile) { return kPixelTile[tile]; }
 
+template <bool PW>
+static void launch_gemmconv_t(const GemmConvArgs &a, int tile, dim3 grid, hipStream_t s)
+{
+    switch (tile) {
+    case 0:
+        hipLaunchKernelGGL((gemmconv_kernel<128, 128, 64, 64, PW>), grid, dim3(256), 0, s, a);
+        break;
+    case 1:
+        hipLaunchKernelGGL((gemmconv_kernel<64, 256, 64, 64, PW>), grid, dim3(256), 0, s, a);
+        break;
+    case 2:
+        hipLaunchKernelGGL((gemmconv_kernel<32, 256, 32, 64, PW>), grid, dim3(256), 0, s, a);
+        break;
+    default:    // 96 filters: three 32-row MFMA tiles per wave (filter counts 96, 192, ...)
+        hipLaunchKernelGGL((gemmconv_kernel<96, 128, 96, 32, PW>), grid, dim3(256), 0, s, a);
+        break;
+    }
+}
+
 hipError_t launch_gemmconv(const GemmConvArgs &a, int tile, int nphases, hipStream_t s)
 {
     const dim3 grid((unsigned)(a.tiles_k * a.tiles_pix), (unsigned)nphases);
-    switch (tile) {
-    case 0:
-        hipLaunchKernelGGL((gemmconv_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, a);
-        break;
-    case 1:
-        hipLaunchKernelGGL((gemmconv_kernel<64, 256, 64, 64>), grid, dim3(256), 0, s, a);
-        break;
-    case 2:
-        hipLaunchKernelGGL((gemmconv_kernel<32, 256, 32, 64>), grid, dim3(256), 0, s, a);
-        break;
-    default:    // 96 filters: three 32-row MFMA tiles per wave (filter counts 96, 192, ...)
-        hipLaunchKernelGGL((gemmconv_kernel<96, 128, 96, 32>), grid, dim3(256), 0, s, a);
-        break;
-    }
+    if (a.pw_depth > 0) launch_gemmconv_t<true>(a, tile, grid, s);
+    else launch_gemmconv_t<false>(a, tile, grid, s);
     return hipGetLastError();
 }
 

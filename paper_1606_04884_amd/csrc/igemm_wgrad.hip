@@ -288,17 +288,28 @@ hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s)
     return hipGetLastError();
 }
 
-// dst[i] = scale * (part[0][i] + part[1][i] + ...) (+ dst[i])
+// dst[i] = scale * (sum over splits of part[s][i]) (+ dst[i]).  Eight interleaved
+// partial sums (split s goes to sum s % 8) combined pairwise: a fixed order, so the
+// result is reproducible, with eight loads in flight per thread.
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ part,
                                                            float *__restrict__ dst, int64_t count,
                                                            int splits, float scale, int accumulate)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
          i += (int64_t)gridDim.x * blockDim.x) {
-        float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += part[(int64_t)k * count + i];
-        s *= scale;
-        dst[i] = accumulate ? dst[i] + s : s;
+        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const float *p = part + i;
+        int k = 0;
+        for (; k + 8 <= splits; k += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s[u] += p[(int64_t)(k + u) * count];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k + u < splits) s[u] += p[(int64_t)(k + u) * count];
+        float t = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+        t *= scale;
+        dst[i] = accumulate ? dst[i] + t : t;
     }
 }
 

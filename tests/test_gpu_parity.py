@@ -31,7 +31,9 @@ SHAPES = [
     G(2, 16, 27, 27, 48, 5, 5, 1, 2),
     G(3, 24, 24, 24, 72, 5, 5, 1, 0),
     G(4, 48, 13, 13, 160, 1, 1, 1, 0),       # 1x1
-    G(2, 192, 28, 28, 16, 1, 1, 1, 0),       # inception 1x1 reduce
+    G(2, 192, 28, 28, 16, 1, 1, 1, 0),       # inception 1x1 reduce (vector-load 1x1 path)
+    G(3, 20, 12, 12, 96, 1, 1, 1, 0),        # 1x1 path, depth and pixel count ragged
+    G(5, 72, 8, 10, 200, 1, 1, 1, 0),        # 1x1 path, several filter tiles
     G(2, 8, 20, 21, 130, 3, 2, 2, 1),
     G(1, 5, 9, 9, 3, 3, 3, 3, 0),
     G(2, 20, 12, 12, 33, 5, 5, 1, 0),
