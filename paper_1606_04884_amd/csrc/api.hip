@@ -314,6 +314,9 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
     case CONV2D_ALGO_AUTO: {
         // Winograd pays once the 16 GEMMs are deep enough to amortise the transforms
         if (op == CONV2D_BWD_WEIGHT) return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
+        // backward-data into <= 4 channels: Winograd/GEMM rows would be almost empty;
+        // a direct kernel takes it when its alignment conditions hold, else the GEMM
+        if (op == CONV2D_BWD_DATA && g.C <= 4) return CONV2D_ALGO_IGEMM;
         const int cin = op == CONV2D_FWD ? g.C : g.K;
         return (wino_ok && cin >= 32) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
     }
@@ -328,6 +331,15 @@ bool pointwise_ok(const Geom &g, const float *in, int64_t in_elems)
 {
     return g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0 &&
            (g.H * g.W) % 4 == 0 && ((uintptr_t)in & 15) == 0 && in_elems * 4 < (int64_t(1) << 31);
+}
+
+// first-layer backward-data on the vector ALU: 3x3, stride 1, pad_w 1, C <= 4, rows of
+// 4-pixel groups with aligned 16-byte accesses
+bool smallc_bwd_ok(const Geom &g, const float *dy, const float *dx)
+{
+    return g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && g.pw == 1 && g.ph <= 2 && g.C <= 4 &&
+           g.W % 4 == 0 && ((uintptr_t)dy & 15) == 0 && ((uintptr_t)dx & 15) == 0 &&
+           (int64_t)g.N * g.K * g.P * g.Q * 4 < (int64_t(1) << 31);
 }
 
 int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
@@ -453,6 +465,13 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
     const int al = resolve_algo(g, CONV2D_BWD_DATA, (int)algo);
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (algo == CONV2D_ALGO_AUTO && smallc_bwd_ok(g, dy, dx)) {
+        SmallCArgs sa = {};
+        sa.dy = dy; sa.w = w; sa.dx = dx;
+        sa.N = g.N; sa.C = g.C; sa.H = g.H; sa.W = g.W; sa.K = g.K; sa.P = g.P; sa.Q = g.Q; sa.pad_h = g.ph;
+        sa.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+        return launch_status(launch_bwd_data_smallc(sa, s));
+    }
     if (al == CONV2D_ALGO_WINOGRAD) return run_wino(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
 
     const GatherPlan p = plan_bwd_data(g);

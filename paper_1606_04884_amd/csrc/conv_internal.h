@@ -188,6 +188,16 @@ int wino_wgrad_tile();
 int wino_wgrad_step();
 hipError_t launch_wino_wgrad(const WinoWgradArgs &a, hipStream_t s);
 
+// Direct backward-data for 3x3 stride-1 layers with C <= 4 (see direct_small.hip).
+struct SmallCArgs {
+    const float *dy;
+    const float *w;
+    float *dx;
+    int32_t N, C, H, W, K, P, Q, pad_h;
+    int32_t dy_bytes;
+};
+hipError_t launch_bwd_data_smallc(const SmallCArgs &a, hipStream_t s);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace mi355conv

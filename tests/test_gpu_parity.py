@@ -204,3 +204,15 @@ def test_winograd_wgrad_parity(geom):
     got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, scale=0.5, dw0=dw0.copy(), db0=db0.copy(),
                     passes=("bwd_weight",))
     assert max_err_ratio(got["dw"], 0.5 * dw + dw0) <= TOL_WINOGRAD
+
+
+@pytest.mark.parametrize("geom", [G(2, 3, 16, 16, 8, 3, 3, 1, 1), G(3, 3, 19, 24, 20, 3, 3, 1, 1),
+                                  G(2, 1, 9, 8, 5, 3, 3, 1, 1), G(2, 4, 12, 12, 7, 3, 3, 1, 1),
+                                  (2, 2, 10, 12, 6, 3, 3, 1, 1, 2, 1), (1, 3, 7, 4, 3, 3, 3, 1, 1, 0, 1)],
+                         ids=lambda g: "x".join(map(str, g)))
+def test_first_layer_backward_data_direct(geom):
+    """AUTO routes 3x3 stride-1 backward-data into <= 4 channels to the direct kernel."""
+    x, w, b, dy = random_layer(geom, 4000 + sum(geom))
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_AUTO, passes=("bwd_data",))
+    ref = oracle.bwd_data(geom, dy, w)
+    assert max_err_ratio(got["dx"], ref) <= TOL_IGEMM
