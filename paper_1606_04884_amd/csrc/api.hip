@@ -206,9 +206,7 @@ WgradPlan plan_wgrad(const Geom &g)
     chunk = (chunk + 31) / 32 * 32;
     p.chunk = (int)chunk;
     p.splits = (int)((M + chunk - 1) / chunk);
-    p.bias_splits = 1024 / g.K;
-    if (p.bias_splits > g.N) p.bias_splits = g.N;
-    if (p.bias_splits < 1) p.bias_splits = 1;
+    p.bias_splits = p.splits;       // the main kernel also sums dy: one partial per split
     p.part_bytes = align_up((size_t)p.splits * g.K * CRS * sizeof(float), 256);
     p.bias_bytes = align_up((size_t)p.bias_splits * g.K * sizeof(float), 256);
     p.total_bytes = p.part_bytes + p.bias_bytes;
@@ -601,7 +599,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     float *bias_part = (float *)((char *)ws + p.part_bytes);
 
     WgradArgs a = {};
-    a.x = x; a.dy = dy; a.part = part;
+    a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
     a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.R = g.R; a.S = g.S; a.P = g.P; a.Q = g.Q;
     a.stride_h = g.sh; a.stride_w = g.sw; a.pad_h = g.ph; a.pad_w = g.pw;
     a.PQ = g.P * g.Q; a.CRS = g.C * g.R * g.S; a.M = g.N * g.P * g.Q;
@@ -616,8 +614,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
                                            accumulate, s));
     if (rc) return rc;
     if (dbias) {
-        rc = launch_status(launch_bias_grad(dy, bias_part, dbias, g.N, g.K, a.PQ, p.bias_splits,
-                                            scale, accumulate, s));
+        rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, accumulate, s));
         if (rc) return rc;
     }
     return CONV2D_OK;

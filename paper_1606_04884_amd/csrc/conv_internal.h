@@ -120,6 +120,7 @@ struct WgradArgs {
     const float *x;
     const float *dy;
     float *part;               // [splits][K][CRS]
+    float *bias_part;          // [splits][K] partial sums of dy per filter, or null
     int32_t N, C, H, W, K, R, S, P, Q;
     int32_t stride_h, stride_w, pad_h, pad_w;
     int32_t PQ, CRS, M;        // M = N*P*Q
@@ -137,10 +138,6 @@ hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int
 // db[k] = scale * sum_i part[i][k] (+ db[k])
 hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
                              int accumulate, hipStream_t s);
-// db[k] = scale * sum_{n,pq} dy[n,k,pq] (+ db[k]); part holds nsplit*K floats
-hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,
-                            int nsplit, float scale, int accumulate, hipStream_t s);
-
 // ---------------------------------------------------------------------------
 // Winograd F(2x2,3x3), fused (see winograd.hip).  `in` is the tensor the 4x4
 // patches are read from (x for forward, dy for backward-data), U the

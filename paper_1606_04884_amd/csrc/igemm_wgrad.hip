@@ -125,8 +125,13 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
         breg[i] = a.x[ok ? x_base + e.x : 0];
         bmask = (bmask & ~(1u << i)) | (ok ? (1u << i) : 0u);
     };
+    float bsum[A_PER_THREAD];        // running sums of dy per filter (bias gradient)
+#pragma unroll
+    for (int i = 0; i < A_PER_THREAD; ++i) bsum[i] = 0.f;
     auto store_a = [&](int buf, int i) {
-        As[buf][pp][trow + i * 8] = ((amask >> i) & 1u) ? areg[i] : 0.f;
+        const float v = ((amask >> i) & 1u) ? areg[i] : 0.f;
+        As[buf][pp][trow + i * 8] = v;
+        bsum[i] += v;                // every pixel of the range passes here exactly once
     };
     auto store_b = [&](int buf, int i) {
         Bs[buf][pp][trow + i * 8] = ((bmask >> i) & 1u) ? breg[i] : 0.f;
@@ -215,6 +220,22 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
                     av[cur][q / NI], bv[cur][q % NI], acc[q / NI][q % NI], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    }
+
+    // bias gradient: the workgroups of column tile 0 reduce their sums over the 32
+    // pixel lanes and write one partial per (split, filter)
+    if (a.bias_part != nullptr && jt == 0) {
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) {
+            float v = bsum[i];
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 16);
+            const int k = kt * BM + trow + i * 8;
+            if (pp == 0 && k < a.K) a.bias_part[split * a.K + k] = v;
         }
     }
 
@@ -323,29 +344,7 @@ hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int
     return hipGetLastError();
 }
 
-// Bias gradient, stage 1: block (k, split) sums dy[n][k][:] over its images.
-__global__ __launch_bounds__(256) void bias_grad_partial_kernel(const float *__restrict__ dy,
-                                                                float *__restrict__ part, int N,
-                                                                int K, int PQ, int nsplit)
-{
-    __shared__ float red[256];
-    const int k = blockIdx.x, sp = blockIdx.y;
-    const int per = (N + nsplit - 1) / nsplit;
-    const int n0 = sp * per, n1 = min(N, n0 + per);
-    float s = 0.f;
-    for (int n = n0; n < n1; ++n) {
-        const float *p = dy + ((int64_t)n * K + k) * PQ;
-        for (int i = threadIdx.x; i < PQ; i += 256) s += p[i];
-    }
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) part[sp * K + k] = red[0];
-}
-
+// Bias gradient, final stage: db[k] = scale * sum of the per-split partial sums.
 __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float *__restrict__ part,
                                                               float *__restrict__ db, int K,
                                                               int nsplit, float scale, int accumulate)
@@ -361,18 +360,6 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float *__res
 hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
                              int accumulate, hipStream_t s)
 {
-    hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s,
-                       part, db, K, nsplit, scale, accumulate);
-    return hipGetLastError();
-}
-
-hipError_t launch_bias_grad(const float *dy, float *part, float *db, int N, int K, int PQ,
-                            int nsplit, float scale, int accumulate, hipStream_t s)
-{
-    hipLaunchKernelGGL(bias_grad_partial_kernel, dim3((unsigned)K, (unsigned)nsplit), dim3(256), 0,
-                       s, dy, part, N, K, PQ, nsplit);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s,
                        part, db, K, nsplit, scale, accumulate);
     return hipGetLastError();
