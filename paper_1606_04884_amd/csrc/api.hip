@@ -267,7 +267,7 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
 }
 
 struct WinoWgradPlan {
-    int TH, TW, T, tiles_k, tiles_c, splits, tiles_per_split, bias_splits;
+    int TH, TW, T, tiles_k, tiles_c, splits, tiles_per_split, bias_splits, mode;
     size_t part_bytes, bias_bytes, total_bytes;
 };
 
@@ -276,6 +276,13 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
     WinoWgradPlan p;
     p.TH = ceil_div(g.P, 2);
     p.TW = ceil_div(g.Q, 2);
+    // pad_w 1 and an even width: tile pairs fetched with vector loads, the tile grid
+    // taken with an even row width (one phantom tile per row when the true one is odd)
+    p.mode = 0;
+    if (g.pw == 1 && g.W % 2 == 0) {
+        p.mode = (p.TW & 1) ? 2 : 1;
+        p.TW = round_up(p.TW, 2);
+    }
     p.T = g.N * p.TH * p.TW;
     p.tiles_k = ceil_div(g.K, wino_wgrad_tile());
     p.tiles_c = ceil_div(g.C, wino_wgrad_tile());
@@ -576,7 +583,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
         a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
         a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q;
         a.pad_h = g.ph; a.pad_w = g.pw;
-        a.TH = p.TH; a.TW = p.TW; a.T = p.T;
+        a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
         a.tiles_per_split = p.tiles_per_split;
         a.tiles_k = p.tiles_k; a.tiles_c = p.tiles_c; a.splits = p.splits;
         a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);

@@ -174,7 +174,10 @@ struct WinoWgradArgs {
     float *part;               // [splits][K][C][9]
     float *bias_part;          // [splits][K] partial sums of dy per filter, or null
     int32_t N, C, H, W, K, P, Q, pad_h, pad_w;
-    int32_t TH, TW, T;         // 2x2 output tiles per image (rows, cols), in total
+    int32_t TH, TW, T;         // 2x2 output tiles per image (rows, cols), in total; in the
+                               // vector modes TW is rounded up to even (phantom last tile)
+    int32_t mode;              // 0 per-element loads, 1 vector loads, 2 vector loads with
+                               // an odd true tile-row width
     int32_t tiles_per_split;   // multiple of the 8-tile step
     int32_t tiles_k, tiles_c, splits;
     int32_t x_bytes, dy_bytes; // both below 2^31

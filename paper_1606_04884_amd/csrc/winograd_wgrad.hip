@@ -23,6 +23,8 @@
 namespace mi355conv {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void lds_barrier_ww()
 {
@@ -208,8 +210,10 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
     // Software pipeline, as in the forward kernel: 64 MFMA slots per step.
     //   slots  0..15 : input transform + LDS writes of step t+1 (two items)
     //   slots 16..23 : gradient-tile transform + LDS writes of step t+1
-    //   slots 24..25 : tile coordinates and buffer offsets of step t+2
-    //   slots 26..63 : the 40 buffer loads of step t+2
+    //   slot   1     : tile coordinates and buffer offsets of step t+2
+    //   slots  4..43 : the 40 buffer loads of step t+2, each register reloaded as
+    //                  soon as the transform has consumed it, so that every load
+    //                  has at least 36 slots until its value is needed
     for (int t = 0; t < nsteps; ++t) {
         const int buf = t & 1;
 #pragma unroll
@@ -230,21 +234,16 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
                 } else if (s < 24) {
                     const int it = (s - 16) >> 2, i = (s - 16) & 3;
                     dyform_row_store(buf ^ 1, it, i);
-                } else if (s == 24) {
-                    setup(t + 2);
-                } else if (s >= 26) {
-                    // 40 loads over 38 slots, in consumption order: x item 0 (column
-                    // major), x item 1, then the gradient tiles
-                    const int l0 = s - 26;
-#pragma unroll
-                    for (int l = 0; l < 40; ++l) {
-                        if (l * 38 / 40 != l0) continue;
-                        if (l < 32) {
-                            const int it = l >> 4, j = (l >> 2) & 3, i = l & 3;
-                            load_x(it, 4 * i + j);
-                        } else {
-                            load_d((l - 32) >> 2, (l - 32) & 3);
-                        }
+                }
+                if (s == 1) setup(t + 2);
+                if (s >= 4 && s < 44) {
+                    // in consumption order: x item 0 (column major), x item 1, gradient tiles
+                    const int l = s - 4;
+                    if (l < 32) {
+                        const int it = l >> 4, j = (l >> 2) & 3, i = l & 3;
+                        load_x(it, 4 * i + j);
+                    } else {
+                        load_d((l - 32) >> 2, (l - 32) & 3);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -298,6 +297,276 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Vector-load variant for pad_w = 1 and even image width (then Q = W).
+//
+// A thread owns one channel (and one filter) and a PAIR of horizontally adjacent
+// tiles per step: the two 4x4 patches overlap in two columns, so the pair is a
+// 4 x 6 block fetched per row as dword + 16 bytes + dword (the 16 bytes start at
+// an even column: always inside the row), the two gradient tiles are one
+// 16-byte load per row, the column half of B^T d B is shared by the two
+// patches, and both tiles' values of a position go out in one paired LDS store.
+// 14 loads per step instead of 40.  The tile grid is taken with its width
+// rounded up to even so that a pair never straddles two tile rows; when the true
+// width is odd (ODD) the last pair of a row has a phantom right tile: its
+// gradient tile and the image columns past the edge are fetched with 8-byte
+// loads of their own whose offset is out of range, so they read as zero and
+// the phantom contributes nothing.
+//
+// LDS operand planes are [buf][pos][half][64 columns][4]: the four reduction
+// steps (tiles 2*ks + half, ks = 0..3) of a column are 16 contiguous bytes, so
+// an MFMA operand for all four steps of a position is one 16-byte read at a
+// fixed per-lane address plus an immediate.  Signs: the rows/columns of
+// A dy A^T that carry a minus sign (index 3) are stored without it; the output
+// transform subtracts instead of adds there.
+
+template <int V> struct IntC { static constexpr int value = V; };
+
+constexpr int kWvPlane = 512;                          // floats per (buf, pos): 2 halves x 64 x 4
+constexpr int kWvOperand = 2 * 16 * kWvPlane;          // floats per operand (two buffers)
+constexpr int kWvLdsBytes = 2 * kWvOperand * (int)sizeof(float);
+
+template <bool ODD>
+__global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
+{
+    constexpr int KB = kWwKB, CB = kWwCB, TS = kWwTS;
+    constexpr int NXO = ODD ? 4 : 3, NDO = ODD ? 2 : 1;
+    extern __shared__ float lds[];
+    float *const As = lds;
+    float *const Bs = lds + kWvOperand;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    const int ntile = a.tiles_k * a.tiles_c;
+    const int logical = xcd_remap_ww(blockIdx.x, gridDim.x);
+    const int tile_id = logical % ntile;
+    const int split = logical / ntile;
+    const int kt = tile_id % a.tiles_k;
+    const int ct = tile_id / a.tiles_k;
+    const int t_begin = split * a.tiles_per_split;
+    const int t_end = min(a.T, t_begin + a.tiles_per_split);
+    const int nsteps = (t_end - t_begin + TS - 1) / TS;
+
+    const int pr = tid & 3, ch = tid >> 2;           // tile pair of the step, channel / filter
+    const int c = ct * CB + ch, k = kt * KB + ch;
+    const bool cok = c < a.C, kok = k < a.K;
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t drs = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.dy_bytes, 0x00020000);
+
+    uint32_t xo[4][NXO], dof[2][NDO];
+    float xr[4][6], dr[2][4];
+
+    auto setup = [&](int step) {
+        const int tb = t_begin + step * TS + 2 * pr;
+        const bool tv = tb < t_end;
+        const int tl = tv ? tb : 0;
+        const int n = (int)fast_div((uint32_t)tl, a.div_THW);
+        const int rem = tl - n * (a.TH * a.TW);
+        const int th = (int)fast_div((uint32_t)rem, a.div_TW);
+        const int tw = rem - th * a.TW;                 // even
+        const int ih0 = 2 * th - a.pad_h, col0 = 2 * tw;
+        const int xbase = ((n * a.C + c) * a.H + ih0) * a.W + col0;
+        const bool lok = tw > 0, hok = col0 + 3 < a.W, rgt = col0 + 4 < a.W;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool rok = tv && cok && (unsigned)(ih0 + i) < (unsigned)a.H;
+            const uint32_t m = (uint32_t)(xbase + i * a.W) * 4u;
+            xo[i][0] = (rok && lok) ? m - 4u : 0x80000000u;
+            xo[i][1] = rok ? m : 0x80000000u;
+            if (ODD) xo[i][2] = (rok && hok) ? m + 8u : 0x80000000u;
+            xo[i][NXO - 1] = (rok && rgt) ? m + 16u : 0x80000000u;
+        }
+        const int dbase = ((n * a.K + k) * a.P + 2 * th) * a.Q + col0;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const bool dok = tv && kok && 2 * th + r < a.P;
+            const uint32_t m = (uint32_t)(dbase + r * a.Q) * 4u;
+            dof[r][0] = dok ? m : 0x80000000u;
+            if (ODD) dof[r][1] = (dok && hok) ? m + 8u : 0x80000000u;
+        }
+    };
+    // one load instruction: row i of the patch pair, part 0 .. NXO-1
+    auto load_x = [&](int i, int part) {
+        if (part == 0) {
+            xr[i][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrs, xo[i][0], 0, 0));
+        } else if (part == NXO - 1) {
+            xr[i][5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrs, xo[i][NXO - 1], 0, 0));
+        } else if (!ODD) {
+            const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xrs, xo[i][1], 0, 0));
+            xr[i][1] = m[0]; xr[i][2] = m[1]; xr[i][3] = m[2]; xr[i][4] = m[3];
+        } else {
+            const floatx2 m = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(xrs, xo[i][part], 0, 0));
+            xr[i][2 * part - 1] = m[0]; xr[i][2 * part] = m[1];
+        }
+    };
+    auto load_d = [&](int r, int part) {
+        if (!ODD) {
+            const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(drs, dof[r][0], 0, 0));
+            dr[r][0] = m[0]; dr[r][1] = m[1]; dr[r][2] = m[2]; dr[r][3] = m[3];
+        } else {
+            const floatx2 m = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(drs, dof[r][part], 0, 0));
+            dr[r][2 * part] = m[0]; dr[r][2 * part + 1] = m[1];
+        }
+    };
+    constexpr int NLOAD = 4 * NXO + 2 * NDO;
+    auto load_nth = [&](int l) {
+        if (l < 4 * NXO) load_x(l / NXO, l % NXO); else load_d((l - 4 * NXO) / NDO, (l - 4 * NXO) % NDO);
+    };
+
+    // store addresses (floats): plane of (buf, pos) + half * 256 + column * 4 + ks, this
+    // thread's left tile is reduction step ks = pr of half 0, its right tile of half 1
+    const int wofs = ch * 4 + pr;
+    float tc[4][6];
+    auto xform_col = [&](int j) {
+        const float d0 = xr[0][j], d1 = xr[1][j], d2 = xr[2][j], d3 = xr[3][j];
+        tc[0][j] = d0 - d2;
+        tc[1][j] = d1 + d2;
+        tc[2][j] = d2 - d1;
+        tc[3][j] = d1 - d3;
+    };
+    auto xform_row_store = [&](int buf, int i) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float t0 = tc[i][2 * h + 0], t1 = tc[i][2 * h + 1], t2 = tc[i][2 * h + 2], t3 = tc[i][2 * h + 3];
+            float *o = Bs + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
+            o[0 * kWvPlane] = t0 - t2;
+            o[1 * kWvPlane] = t1 + t2;
+            o[2 * kWvPlane] = t2 - t1;
+            o[3 * kWvPlane] = t1 - t3;
+        }
+    };
+    float bsum = 0.f;
+    auto dyform_row_store = [&](int buf, int i) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float y00 = dr[0][2 * h], y01 = dr[0][2 * h + 1], y10 = dr[1][2 * h], y11 = dr[1][2 * h + 1];
+            float t0, t1;       // row i of |A| dy (row 3 without its sign)
+            if (i == 0) { t0 = y00; t1 = y01; }
+            else if (i == 1) { t0 = y00 + y10; t1 = y01 + y11; }
+            else if (i == 2) { t0 = y00 - y10; t1 = y01 - y11; }
+            else { t0 = y10; t1 = y11; }
+            const float sum = t0 + t1;
+            if (i == 1) bsum += sum;                       // all four values of the tile
+            float *o = As + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
+            o[0 * kWvPlane] = t0;
+            o[1 * kWvPlane] = sum;
+            o[2 * kWvPlane] = t0 - t1;
+            o[3 * kWvPlane] = t1;                          // column 3 without its sign
+        }
+    };
+
+    floatx16 acc[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+    const float *const rdA = As + lhi * 256 + (wm0 + l32) * 4;
+    const float *const rdB = Bs + lhi * 256 + (wn0 + l32) * 4;
+    floatx4 ao[2][2], bo[2][2];
+    auto read_pair = [&](int buf, int pair, int set) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            ao[set][u] = *reinterpret_cast<const floatx4 *>(rdA + (buf * 16 + 2 * pair + u) * kWvPlane);
+            bo[set][u] = *reinterpret_cast<const floatx4 *>(rdB + (buf * 16 + 2 * pair + u) * kWvPlane);
+        }
+    };
+
+    // ---- prologue: step 0 into LDS buffer 0, step 1 into registers ----
+    setup(0);
+#pragma unroll
+    for (int l = 0; l < NLOAD; ++l) load_nth(l);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) xform_col(j);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { xform_row_store(0, i); dyform_row_store(0, i); }
+    setup(1);            // steps past the end: every offset out of range, all zeros
+#pragma unroll
+    for (int l = 0; l < NLOAD; ++l) load_nth(l);
+    lds_barrier_ww();
+    read_pair(0, 0, 0);
+
+    // Software pipeline, 64 MFMA slots per step (buffer index a compile-time constant
+    // so every LDS address is a fixed register plus an immediate):
+    //   slots  0..5  : column half of the input transform of step t+1
+    //   slots  6..9  : row half + LDS stores, one patch row (both tiles) per slot
+    //   slots 10..13 : gradient-tile transform + LDS stores, one row per slot
+    //   slot  14     : tile coordinates and buffer offsets of step t+2
+    //   slots 15..   : the loads of step t+2, one per slot
+    auto step_body = [&](int t, auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+#pragma unroll
+        for (int pair = 0; pair < 8; ++pair) {
+            const int cur = pair & 1, nxt = cur ^ 1;
+            if (pair + 1 < 8) {
+                read_pair(buf, pair + 1, nxt);
+            } else {
+                lds_barrier_ww();
+                read_pair(buf ^ 1, 0, nxt);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int s = pair * 8 + q;
+                if (s < 6) xform_col(s);
+                else if (s < 10) xform_row_store(buf ^ 1, s - 6);
+                else if (s < 14) dyform_row_store(buf ^ 1, s - 10);
+                else if (s == 14) setup(t + 2);
+                else if (s < 15 + NLOAD) load_nth(s - 15);
+                __builtin_amdgcn_sched_barrier(0);
+                const int u = q & 1, ks = q >> 1;
+                acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ao[cur][u][ks], bo[cur][u][ks],
+                                                                          acc[2 * pair + u], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // an odd step count runs one extra all-zero step
+    for (int t = 0; t < nsteps; t += 2) {
+        step_body(t, IntC<0>());
+        step_body(t + 1, IntC<1>());
+    }
+
+    // ---- bias gradient: every tile of the range went through bsum exactly once ----
+    if (a.bias_part != nullptr && ct == 0) {
+        float v = bsum;
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        if (pr == 0 && kok) a.bias_part[split * a.K + k] = v;
+    }
+
+    // ---- epilogue: dg = G^T M G in registers (index-3 rows / columns enter with a
+    // minus sign, see above), partial 3x3 gradients out ----
+    const int co = ct * CB + wn0 + l32;
+    if (co >= a.C) return;
+    float *out = a.part + (int64_t)split * a.K * a.C * 9;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int ko = kt * KB + wm0 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+        if (ko >= a.K) continue;
+        float tt[3][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+            const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
+            tt[0][j] = m0 + hs;
+            tt[1][j] = hd;
+            tt[2][j] = hs - m3;
+        }
+        float *o = out + ((int64_t)ko * a.C + co) * 9;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const float hs = 0.5f * (tt[r][1] + tt[r][2]), hd = 0.5f * (tt[r][1] - tt[r][2]);
+            o[3 * r + 0] = tt[r][0] + hs;
+            o[3 * r + 1] = hd;
+            o[3 * r + 2] = hs - tt[r][3];
+        }
+    }
+}
+
 int wino_wgrad_tile() { return kWwKB; }
 int wino_wgrad_step() { return kWwTS; }
 
@@ -308,10 +577,21 @@ hipError_t launch_wino_wgrad(const WinoWgradArgs &a, hipStream_t s)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWwLdsBytes);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_vec_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kWvLdsBytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_vec_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kWvLdsBytes);
+        if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(wino_wgrad_kernel, dim3((unsigned)(a.tiles_k * a.tiles_c * a.splits)), dim3(256),
-                       kWwLdsBytes, s, a);
+    const dim3 grid((unsigned)(a.tiles_k * a.tiles_c * a.splits));
+    if (a.mode == 0)
+        hipLaunchKernelGGL(wino_wgrad_kernel, grid, dim3(256), kWwLdsBytes, s, a);
+    else if (a.mode == 1)
+        hipLaunchKernelGGL(wino_wgrad_vec_kernel<false>, grid, dim3(256), kWvLdsBytes, s, a);
+    else
+        hipLaunchKernelGGL(wino_wgrad_vec_kernel<true>, grid, dim3(256), kWvLdsBytes, s, a);
     return hipGetLastError();
 }
 

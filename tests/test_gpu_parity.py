@@ -184,6 +184,13 @@ WINO_WGRAD_SHAPES = [
     G(2, 32, 10, 7, 32, 3, 3, 1, 2),
     (2, 32, 11, 12, 32, 3, 3, 1, 1, 0, 2),
     G(7, 64, 28, 28, 128, 3, 3, 1, 1),
+    # vector-load variants (pad_w 1, even width): even and odd tile-row widths,
+    # rows that end inside a step, other pad_h
+    G(3, 64, 12, 12, 64, 3, 3, 1, 1),
+    G(5, 96, 20, 36, 160, 3, 3, 1, 1),
+    (2, 32, 7, 10, 32, 3, 3, 1, 1, 0, 1),
+    (2, 64, 9, 6, 32, 3, 3, 1, 1, 2, 1),
+    G(3, 32, 15, 22, 96, 3, 3, 1, 1),
 ]
 
 
