@@ -427,35 +427,29 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
         tc[2][j] = d2 - d1;
         tc[3][j] = d1 - d3;
     };
-    auto xform_row_store = [&](int buf, int i) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float t0 = tc[i][2 * h + 0], t1 = tc[i][2 * h + 1], t2 = tc[i][2 * h + 2], t3 = tc[i][2 * h + 3];
-            float *o = Bs + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
-            o[0 * kWvPlane] = t0 - t2;
-            o[1 * kWvPlane] = t1 + t2;
-            o[2 * kWvPlane] = t2 - t1;
-            o[3 * kWvPlane] = t1 - t3;
-        }
+    auto xform_row_store = [&](int buf, int i, int h) {
+        const float t0 = tc[i][2 * h + 0], t1 = tc[i][2 * h + 1], t2 = tc[i][2 * h + 2], t3 = tc[i][2 * h + 3];
+        float *o = Bs + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
+        o[0 * kWvPlane] = t0 - t2;
+        o[1 * kWvPlane] = t1 + t2;
+        o[2 * kWvPlane] = t2 - t1;
+        o[3 * kWvPlane] = t1 - t3;
     };
     float bsum = 0.f;
-    auto dyform_row_store = [&](int buf, int i) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float y00 = dr[0][2 * h], y01 = dr[0][2 * h + 1], y10 = dr[1][2 * h], y11 = dr[1][2 * h + 1];
-            float t0, t1;       // row i of |A| dy (row 3 without its sign)
-            if (i == 0) { t0 = y00; t1 = y01; }
-            else if (i == 1) { t0 = y00 + y10; t1 = y01 + y11; }
-            else if (i == 2) { t0 = y00 - y10; t1 = y01 - y11; }
-            else { t0 = y10; t1 = y11; }
-            const float sum = t0 + t1;
-            if (i == 1) bsum += sum;                       // all four values of the tile
-            float *o = As + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
-            o[0 * kWvPlane] = t0;
-            o[1 * kWvPlane] = sum;
-            o[2 * kWvPlane] = t0 - t1;
-            o[3 * kWvPlane] = t1;                          // column 3 without its sign
-        }
+    auto dyform_row_store = [&](int buf, int i, int h) {
+        const float y00 = dr[0][2 * h], y01 = dr[0][2 * h + 1], y10 = dr[1][2 * h], y11 = dr[1][2 * h + 1];
+        float t0, t1;       // row i of |A| dy (row 3 without its sign)
+        if (i == 0) { t0 = y00; t1 = y01; }
+        else if (i == 1) { t0 = y00 + y10; t1 = y01 + y11; }
+        else if (i == 2) { t0 = y00 - y10; t1 = y01 - y11; }
+        else { t0 = y10; t1 = y11; }
+        const float sum = t0 + t1;
+        if (i == 1) bsum += sum;                       // all four values of the tile
+        float *o = As + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
+        o[0 * kWvPlane] = t0;
+        o[1 * kWvPlane] = sum;
+        o[2 * kWvPlane] = t0 - t1;
+        o[3 * kWvPlane] = t1;                          // column 3 without its sign
     };
 
     floatx16 acc[16];
@@ -483,22 +477,33 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
 #pragma unroll
     for (int j = 0; j < 6; ++j) xform_col(j);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { xform_row_store(0, i); dyform_row_store(0, i); }
+    for (int q = 0; q < 8; ++q) { xform_row_store(0, q >> 1, q & 1); dyform_row_store(0, q >> 1, q & 1); }
     setup(1);            // steps past the end: every offset out of range, all zeros
 #pragma unroll
     for (int l = 0; l < NLOAD; ++l) load_nth(l);
+    setup(2);
     lds_barrier_ww();
     read_pair(0, 0, 0);
 
-    // Software pipeline, 64 MFMA slots per step (buffer index a compile-time constant
-    // so every LDS address is a fixed register plus an immediate):
-    //   slots  0..5  : column half of the input transform of step t+1
-    //   slots  6..9  : row half + LDS stores, one patch row (both tiles) per slot
-    //   slots 10..13 : gradient-tile transform + LDS stores, one row per slot
-    //   slot  14     : tile coordinates and buffer offsets of step t+2
-    //   slots 15..   : the loads of step t+2, one per slot
+    // Software pipeline.  A step is 8 groups of 8 back-to-back MFMAs (two positions x
+    // four reduction steps); all other work sits in the gaps between groups, because
+    // every switch from the matrix pipe to other instructions and back costs a
+    // pipeline drain (measured: ~11 cycles per gap on top of ~4-5 per instruction),
+    // so few large gaps beat one small gap per MFMA.  Inside a gap the loads are
+    // spread between the transform pieces: back-to-back vector loads hold the wave
+    // ~55 cycles each, loads a few instructions apart ~25.  Buffer index is a
+    // compile-time constant so every LDS address is a fixed register plus an immediate.
+    //   gap 0   : column half of the input transform of step t+1
+    //   gap 1-2 : row half + LDS stores of step t+1 (one patch row of one tile per
+    //             piece), an image load of step t+2 after every piece
+    //   gap 3-4 : gradient-tile transform + LDS stores, remaining image loads, first
+    //             gradient load
+    //   gap 5   : remaining gradient loads; coordinates and buffer offsets of step t+3
+    //   gap 7   : barrier, first operands of the next step
+    // every gap also reads the LDS operands of the following group
     auto step_body = [&](int t, auto bufc) {
         constexpr int buf = decltype(bufc)::value;
+        constexpr int NXL = 4 * NXO;
 #pragma unroll
         for (int pair = 0; pair < 8; ++pair) {
             const int cur = pair & 1, nxt = cur ^ 1;
@@ -508,20 +513,42 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
                 lds_barrier_ww();
                 read_pair(buf ^ 1, 0, nxt);
             }
+            if (pair == 0) {
+#pragma unroll
+                for (int j = 0; j < 6; ++j) xform_col(j);
+            } else if (pair == 1 || pair == 2) {
+#pragma unroll
+                for (int q = 4 * (pair - 1); q < 4 * pair; ++q) {
+                    xform_row_store(buf ^ 1, q >> 1, q & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_nth(q);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else if (pair == 3 || pair == 4) {
+#pragma unroll
+                for (int q = 4 * (pair - 3); q < 4 * (pair - 2); ++q) {
+                    dyform_row_store(buf ^ 1, q >> 1, q & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (8 + q < NXL) load_nth(8 + q);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (pair == 4) load_nth(NXL);
+            } else if (pair == 5) {
+#pragma unroll
+                for (int l = NXL + 1; l < NLOAD; ++l) {
+                    load_nth(l);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                setup(t + 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const int s = pair * 8 + q;
-                if (s < 6) xform_col(s);
-                else if (s < 10) xform_row_store(buf ^ 1, s - 6);
-                else if (s < 14) dyform_row_store(buf ^ 1, s - 10);
-                else if (s == 14) setup(t + 2);
-                else if (s < 15 + NLOAD) load_nth(s - 15);
-                __builtin_amdgcn_sched_barrier(0);
                 const int u = q & 1, ks = q >> 1;
                 acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ao[cur][u][ks], bo[cur][u][ks],
                                                                           acc[2 * pair + u], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     // an odd step count runs one extra all-zero step
