@@ -215,7 +215,7 @@ WgradPlan plan_wgrad(const Geom &g)
 
 // ---- Winograd F(2x2,3x3) ---------------------------------------------------
 struct WinoPlan {
-    int Cin, Kout, Cpad, Kpad, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, tiles_t, tiles_k;
+    int Cin, Kout, Cpad, Kpad, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, tiles_t, tiles_k, mode;
     int grid;                   // persistent workgroups
     size_t u_bytes, total_bytes;
 };
@@ -256,6 +256,8 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
     p.Kpad = round_up(p.Kout, wino_filter_tile());
     p.TH = ceil_div(p.Hout, 2);
     p.TW = ceil_div(p.Wout, 2);
+    // pad_w 1, even width and an even number of tiles per row: tile-pair kernel
+    p.mode = (p.pad_w == 1 && p.Win % 2 == 0 && p.TW % 2 == 0) ? 1 : 0;
     p.T = g.N * p.TH * p.TW;
     p.tiles_t = ceil_div(p.T, wino_tile_block());
     p.tiles_k = p.Kpad / wino_filter_tile();
@@ -356,13 +358,13 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
     float *U = (float *)ws;
     int rc = launch_status(launch_wino_filter(w, U, g.K, g.C, p.Cin, p.Kout, p.Cpad, p.Kpad,
-                                              op == CONV2D_FWD ? 0 : 1, s));
+                                              op == CONV2D_FWD ? 0 : 1, p.mode != 0, s));
     if (rc) return rc;
     WinoArgs a = {};
     a.in = in; a.U = U; a.bias = bias; a.out = out;
     a.N = g.N; a.Cin = p.Cin; a.Cpad = p.Cpad; a.Hin = p.Hin; a.Win = p.Win;
     a.Kout = p.Kout; a.Kpad = p.Kpad; a.Hout = p.Hout; a.Wout = p.Wout;
-    a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T;
+    a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
     a.tiles_t = p.tiles_t; a.tiles_k = p.tiles_k;
     a.nchunks = p.Cin / wino_chan_chunk();
     a.units_total = p.tiles_t * p.tiles_k * a.nchunks;

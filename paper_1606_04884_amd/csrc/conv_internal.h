@@ -151,6 +151,8 @@ struct WinoArgs {
     int32_t N, Cin, Cpad, Hin, Win, Kout, Kpad, Hout, Wout;
     int32_t pad_h, pad_w;    // patch origin = 2*tile - pad
     int32_t TH, TW, T;       // tiles per image (rows, cols), tiles in total
+    int32_t mode;            // 0 one tile per lane; 1 tile pairs (TW even, pad_w 1, even
+                             // width), needs the paired U layout
     int32_t tiles_t, tiles_k;
     int32_t vec2;            // output rows can be stored as aligned float2
     int32_t in_bytes, u_bytes;   // sizes of `in` and `U` (both below 2^31)
@@ -162,7 +164,7 @@ int wino_filter_tile();
 int wino_tile_block();
 int wino_chan_chunk();
 hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
-                              int Kpad, int mode, hipStream_t s);
+                              int Kpad, int mode, int paired, hipStream_t s);
 int wino_partial_slot_floats();
 // G persistent workgroups (G <= tiles_t*tiles_k)
 hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s);

@@ -33,13 +33,15 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // --------------------------------------------------------- filter transform
-// U[pos][c][k] (k contiguous, zero padded to Cpad x Kpad).
+// U[pos][c][k] (k contiguous, zero padded to Cpad x Kpad); with `paired` set the
+// layout is U[pos][c/8][c%2][k][(c%8)/2] instead: the four channels that one MFMA
+// lane needs for the four reduction steps of a chunk are 16 contiguous bytes.
 // mode 0: forward, filters g = w[k][c].  mode 1: backward-data, the layer that
 // maps dy to dx has filters g'[c][k][r][s] = w[k][c][2-r][2-s]; its "k" is c.
 __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w,
                                                           float *__restrict__ U, int K, int C,
                                                           int Cin, int Kout, int Cpad, int Kpad,
-                                                          int mode)
+                                                          int mode, int paired)
 {
     const int64_t total = (int64_t)Cpad * Kpad;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
@@ -79,21 +81,22 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restric
             const float u1 = 0.5f * (t[r][0] + t[r][1] + t[r][2]);
             const float u2 = 0.5f * (t[r][0] - t[r][1] + t[r][2]);
             const float u3 = t[r][2];
-            U[(int64_t)(4 * r + 0) * total + i] = u0;
-            U[(int64_t)(4 * r + 1) * total + i] = u1;
-            U[(int64_t)(4 * r + 2) * total + i] = u2;
-            U[(int64_t)(4 * r + 3) * total + i] = u3;
+            const int64_t at = paired ? ((int64_t)((ci >> 3) * 2 + (ci & 1)) * Kpad + ko) * 4 + ((ci & 7) >> 1) : i;
+            U[(int64_t)(4 * r + 0) * total + at] = u0;
+            U[(int64_t)(4 * r + 1) * total + at] = u1;
+            U[(int64_t)(4 * r + 2) * total + at] = u2;
+            U[(int64_t)(4 * r + 3) * total + at] = u3;
         }
     }
 }
 
 hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
-                              int Kpad, int mode, hipStream_t s)
+                              int Kpad, int mode, int paired, hipStream_t s)
 {
     int64_t blocks = ((int64_t)Cpad * Kpad + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, K, C, Cin,
-                       Kout, Cpad, Kpad, mode);
+                       Kout, Cpad, Kpad, mode, paired);
     return hipGetLastError();
 }
 
@@ -112,8 +115,111 @@ __device__ __forceinline__ int xcd_remap_wino(int id, int nb)
     return xcd * per + (xcd < rem ? xcd : rem) + local;
 }
 
+
 constexpr int kWinoKB = 64, kWinoTB = 64, kWinoCB = 8;
 constexpr int kWinoLdsBytes = 2 * 16 * kWinoCB * (kWinoKB + kWinoTB) * (int)sizeof(float);
+constexpr int kWinoPairLdsBytes = 2 * 16 * kWinoCB * kWinoTB * (int)sizeof(float);   // V planes only
+
+// Range of units of one persistent workgroup and the lane's place in the
+// accumulator layout, for the tile epilogue shared by the fused kernels.
+struct WinoTileCtx {
+    int ub, ue, lb, nchunks;
+    int wm0, wn0, l32, lhi;
+};
+
+// Output transform of the finished (or cut) tile in registers; accumulator
+// element v of lane L: filter row 8*(v/4) + 4*(L/32) + v%4, tile column L%32.
+// Tiles whose first output column lies outside the map (phantom tiles of a tile
+// grid taken wider than the map) are computed but not stored.
+template <bool ZERO>
+__device__ __forceinline__ void wino_finish_tile(const WinoArgs &a, floatx16 (&acc)[16], int tile_id,
+                                                 int first_unit, const WinoTileCtx &cx)
+{
+    constexpr int KB = kWinoKB, TB = kWinoTB;
+    const int ub = cx.ub, ue = cx.ue, lb = cx.lb, nchunks = cx.nchunks;
+    const int wm0 = cx.wm0, wn0 = cx.wn0, l32 = cx.l32, lhi = cx.lhi;
+
+    const int kt = tile_id / a.tiles_t, tt = tile_id - kt * a.tiles_t;
+    const bool head = first_unit < ub, tail = first_unit + nchunks > ue;
+    float *slot = a.partial + ((int64_t)lb * 2 + (head ? 0 : 1)) * (KB * TB * 4);
+    const int tile = tt * TB + wn0 + l32;
+    const int tl = tile < a.T ? tile : 0;
+    const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
+    const int th = rem / a.TW, tw = rem - th * a.TW;
+    const int oh = 2 * th, ow = 2 * tw;
+    const bool tv = tile < a.T && ow < a.Wout;
+    const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+    const int HWo = a.Hout * a.Wout;
+    float *obase = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow;
+    // 2x2 outputs of accumulator element v (without bias)
+    auto out_xform = [&](int v, float &y00, float &y01, float &y10, float &y11) {
+        float s0[4], s1[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+            s0[j] = m0 + m1 + m2;
+            s1[j] = m1 - m2 - m3;
+        }
+        y00 = s0[0] + s0[1] + s0[2]; y01 = s0[1] - s0[2] - s0[3];
+        y10 = s1[0] + s1[1] + s1[2]; y11 = s1[1] - s1[2] - s1[3];
+    };
+    // (the 16 rounds are kept apart by scheduling fences: scheduled together they
+    // would need all 256 accumulator values in ordinary registers at once)
+    if (head || tail) {
+        float *sp = slot + ((wm0 + 4 * lhi) * TB + wn0 + l32) * 4;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            __builtin_amdgcn_sched_barrier(0);
+            float y00, y01, y10, y11;
+            out_xform(v, y00, y01, y10, y11);
+            const floatx4 o4 = {y00, y01, y10, y11};
+            *reinterpret_cast<floatx4 *>(sp + ((8 * (v >> 2) + (v & 3)) * TB) * 4) = o4;
+        }
+    } else if (tv) {
+        const int kbase = kt * KB + wm0 + 4 * lhi;
+        float *ob = obase + (int64_t)kbase * HWo;
+        const float *bp = a.bias ? a.bias + kbase : nullptr;
+        if (a.vec2) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                __builtin_amdgcn_sched_barrier(0);
+                const int kr = 8 * (v >> 2) + (v & 3);
+                if (kbase + kr < a.Kout) {
+                    float y00, y01, y10, y11;
+                    out_xform(v, y00, y01, y10, y11);
+                    const float bz = bp ? bp[kr] : 0.f;
+                    float *o = ob + (int64_t)kr * HWo;
+                    *reinterpret_cast<float2 *>(o) = make_float2(y00 + bz, y01 + bz);
+                    if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10 + bz, y11 + bz);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                __builtin_amdgcn_sched_barrier(0);
+                const int kr = 8 * (v >> 2) + (v & 3);
+                if (kbase + kr < a.Kout) {
+                    float y00, y01, y10, y11;
+                    out_xform(v, y00, y01, y10, y11);
+                    const float bz = bp ? bp[kr] : 0.f;
+                    float *o = ob + (int64_t)kr * HWo;
+                    o[0] = y00 + bz;
+                    if (col1) o[1] = y01 + bz;
+                    if (row1) {
+                        o[a.Wout] = y10 + bz;
+                        if (col1) o[a.Wout + 1] = y11 + bz;
+                    }
+                }
+            }
+        }
+    }
+    if (ZERO) {
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+    }
+}
 
 // Work decomposition ("stream-K"): a unit is one 8-channel chunk of one output
 // tile (64 filters x 64 tiles); units are numbered chunk-fastest, then tile block,
@@ -267,88 +373,8 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
             }
     };
 
-    // output transform of the finished (or cut) tile in registers; accumulator
-    // element v of lane L: filter row 8*(v/4) + 4*(L/32) + v%4, tile column L%32
-    auto finish_tile = [&](int tile_id, int first_unit) {
-        const int kt = tile_id / a.tiles_t, tt = tile_id - kt * a.tiles_t;
-        const bool head = first_unit < ub, tail = first_unit + nchunks > ue;
-        float *slot = a.partial + ((int64_t)lb * 2 + (head ? 0 : 1)) * (KB * TB * 4);
-        const int tile = tt * TB + wn0 + l32;
-        const bool tv = tile < a.T;
-        const int tl = tv ? tile : 0;
-        const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
-        const int th = rem / a.TW, tw = rem - th * a.TW;
-        const int oh = 2 * th, ow = 2 * tw;
-        const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
-        const int HWo = a.Hout * a.Wout;
-        float *obase = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow;
-        // 2x2 outputs of accumulator element v (without bias)
-        auto out_xform = [&](int v, float &y00, float &y01, float &y10, float &y11) {
-            float s0[4], s1[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
-                s0[j] = m0 + m1 + m2;
-                s1[j] = m1 - m2 - m3;
-            }
-            y00 = s0[0] + s0[1] + s0[2]; y01 = s0[1] - s0[2] - s0[3];
-            y10 = s1[0] + s1[1] + s1[2]; y11 = s1[1] - s1[2] - s1[3];
-        };
-        // (the 16 rounds are kept apart by scheduling fences: scheduled together they
-        // would need all 256 accumulator values in ordinary registers at once)
-        if (head || tail) {
-            float *sp = slot + ((wm0 + 4 * lhi) * TB + wn0 + l32) * 4;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                __builtin_amdgcn_sched_barrier(0);
-                float y00, y01, y10, y11;
-                out_xform(v, y00, y01, y10, y11);
-                const floatx4 o4 = {y00, y01, y10, y11};
-                *reinterpret_cast<floatx4 *>(sp + ((8 * (v >> 2) + (v & 3)) * TB) * 4) = o4;
-            }
-        } else if (tv) {
-            const int kbase = kt * KB + wm0 + 4 * lhi;
-            float *ob = obase + (int64_t)kbase * HWo;
-            const float *bp = a.bias ? a.bias + kbase : nullptr;
-            if (a.vec2) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    const int kr = 8 * (v >> 2) + (v & 3);
-                    if (kbase + kr < a.Kout) {
-                        float y00, y01, y10, y11;
-                        out_xform(v, y00, y01, y10, y11);
-                        const float bz = bp ? bp[kr] : 0.f;
-                        float *o = ob + (int64_t)kr * HWo;
-                        *reinterpret_cast<float2 *>(o) = make_float2(y00 + bz, y01 + bz);
-                        if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10 + bz, y11 + bz);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    const int kr = 8 * (v >> 2) + (v & 3);
-                    if (kbase + kr < a.Kout) {
-                        float y00, y01, y10, y11;
-                        out_xform(v, y00, y01, y10, y11);
-                        const float bz = bp ? bp[kr] : 0.f;
-                        float *o = ob + (int64_t)kr * HWo;
-                        o[0] = y00 + bz;
-                        if (col1) o[1] = y01 + bz;
-                        if (row1) {
-                            o[a.Wout] = y10 + bz;
-                            if (col1) o[a.Wout + 1] = y11 + bz;
-                        }
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < 16; ++p)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
-    };
+    const WinoTileCtx cx = {ub, ue, lb, nchunks, wm0, wn0, l32, lhi};
+    auto finish_tile = [&](int tile_id, int first_unit) { wino_finish_tile<true>(a, acc, tile_id, first_unit, cx); };
 
     // cursors (unit -> tile, chunk) of the three pipeline stages; units past the
     // end of the range are clamped to the last one (harmless reloads)
@@ -461,6 +487,269 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Tile-pair variant of the fused kernel, for pad_w = 1 and an even input width.
+//
+// Same decomposition, accumulators and epilogue as wino_fused_kernel; what
+// differs is how a chunk is staged, built on three measurements on this chip:
+// (1) fp32 MFMAs and other vector instructions do not overlap, and every
+// switch between a run of MFMAs and other instructions costs a pipeline drain
+// (~11 cycles), so the MFMAs are issued in runs of 8 with all side work in the
+// 8 gaps of a chunk; (2) a vector-memory instruction holds its wave for ~25
+// cycles when a few other instructions separate it from the next one and ~55
+// when loads are back to back, so the loads are spread between the other
+// pieces; (3) LDS traffic costs the wave time in proportion to its bytes.
+//   * A thread owns one channel of the chunk and a PAIR of horizontally adjacent
+//     tiles: the two 4x4 patches are a 4 x 6 block, fetched per row as dword +
+//     16 bytes + dword (12 loads per chunk instead of 24); the column half of
+//     B^T d B is shared by the two patches.  The tile grid is taken with its
+//     row width even (the host picks this kernel only then), so a pair never
+//     straddles two tile rows and the 16 bytes never leave the image row.
+//   * The V planes in LDS are [buf][pos][half][64 tiles][4]: the four channels a
+//     lane needs for the four reduction steps of a chunk are 16 contiguous
+//     bytes, one read per position.  The two buffers are 32 KB apart: switching
+//     is one XOR per base register.
+//   * The transformed filters do not go through LDS at all: the filter transform
+//     writes U as [pos][chunk][half][filter][4], so the MFMA A operand of a lane
+//     for one position of a chunk is 16 contiguous bytes of U, loaded straight
+//     into the registers the MFMAs read (from L2; the two waves sharing a filter
+//     half hit the same lines).  The registers of a position pair are reloaded
+//     for the next unit in the gap after their last MFMA.
+__global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
+{
+    constexpr int KB = kWinoKB, CB = kWinoCB;
+    constexpr int NXO = 3;                    // loads per row of a patch pair
+    constexpr int NX = 4 * NXO;
+    constexpr int PLANE = 512;                // floats per (buf, pos): 2 halves x 64 x 4
+    constexpr int BUFSZ = 16 * PLANE;         // floats per buffer (32 KB)
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    floatx4 *const lds4 = reinterpret_cast<floatx4 *>(lds);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    const int G = gridDim.x;
+    const int lb = xcd_remap_wino(blockIdx.x, G);
+    const int ub = (int)((int64_t)lb * a.units_total / G);
+    const int ue = (int)((int64_t)(lb + 1) * a.units_total / G);
+    const int nunits = ue - ub;
+    if (nunits <= 0) return;
+    const int nchunks = a.nchunks;
+
+    // a half-wave holds 4 tile pairs x 8 channels: its LDS stores of one value then
+    // fall in 32 different banks (see the V plane layout below)
+    const int pr = wave * 8 + (lhi << 2) + (lane & 3);     // tile pair of the block: tiles 2*pr, 2*pr + 1
+    const int ch = (lane >> 2) & 7;                         // channel of the chunk
+    const int HW = a.Hin * a.Win;
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ursrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.U, 0, a.u_bytes, 0x00020000);
+    // byte offsets of the row pieces inside chunk 0 (channel ch), or 2^31 for "outside"
+    uint32_t xo[4][NXO];
+    auto set_tile_block = [&](int tt) {
+        const int tile = tt * kWinoTB + 2 * pr;
+        const bool tv = tile < a.T;
+        const int tl = tv ? tile : 0;
+        const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
+        const int th = rem / a.TW, tw = rem - th * a.TW;       // tw even
+        const int ih0 = 2 * th - a.pad_h, col0 = 2 * tw;         // patch pair: columns col0-1 .. col0+4
+        const int base = (n * a.Cin + ch) * HW + ih0 * a.Win + col0;
+        const bool lok = tw > 0, rgt = col0 + 4 < a.Win;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool rok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin;
+            const uint32_t m = (uint32_t)(base + i * a.Win) * 4u;
+            xo[i][0] = (rok && lok) ? m - 4u : 0x80000000u;
+            xo[i][1] = rok ? m : 0x80000000u;
+            xo[i][NXO - 1] = (rok && rgt) ? m + 16u : 0x80000000u;
+        }
+    };
+    const int x_chunk = CB * HW * 4;                  // bytes per chunk of channels
+
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+    // A operand of this lane: U[pos][chunk][half = lhi][filter wm0 + l32][0..3]
+    const int u_plane = a.Kpad * 16;                  // bytes per (pos, chunk, half)
+    const uint32_t aoff0 = (uint32_t)lhi * (uint32_t)u_plane + (uint32_t)(wm0 + l32) * 16u;
+    const int u_pos_stride = nchunks * 2 * u_plane;
+    const int u_chunk = 2 * u_plane;
+
+    float xr[4][6];
+    floatx4 ar[16];
+    // x load number l, in the order in which the column transform frees the
+    // registers: the left dwords of the four rows, the middle pieces, the right dwords
+    auto load_x = [&](int l, int chunk) {
+        const int part = l >> 2, i = l & 3;
+        const int so = chunk * x_chunk;
+        if (part == 0) {
+            xr[i][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][0], so, 0));
+        } else if (part == NXO - 1) {
+            xr[i][5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][NXO - 1], so, 0));
+        } else {
+            // (cast the whole result vector, then index the cast value)
+            const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xo[i][1], so, 0));
+            xr[i][1] = m[0]; xr[i][2] = m[1]; xr[i][3] = m[2]; xr[i][4] = m[3];
+        }
+    };
+    auto load_a = [&](int pos, int kt, int chunk) {
+        ar[pos] = __builtin_bit_cast(
+            floatx4, __builtin_amdgcn_raw_buffer_load_b128(ursrc, aoff0, chunk * u_chunk + kt * (KB * 16) + pos * u_pos_stride, 0));
+    };
+
+    // LDS float offsets; `wrV` points into the buffer being filled, `rdB` into the
+    // buffer being multiplied; one XOR switches each.
+    // V plane: column of tile t in half-plane `half` is t ^ half (adjacent columns swap
+    // in the second half-plane), which spreads the stores of a half-wave over all banks
+    uint32_t wrV = (ch & 1) * 256 + (2 * pr + (ch & 1)) * 4 + (ch >> 1);   // tile 2*pr; tile 2*pr+1 is at wrV ^ 4
+    uint32_t rdB = lhi * 256 + ((wn0 + l32) ^ lhi) * 4;                    // a multiple of 4
+    auto flip = [&]() { wrV ^= BUFSZ; rdB ^= BUFSZ; };
+
+    float tc[4][6];
+    auto xform_col = [&](int j) {               // stage 1 on column j of the pair: t = B^T d
+        const float d0 = xr[0][j], d1 = xr[1][j], d2 = xr[2][j], d3 = xr[3][j];
+        tc[0][j] = d0 - d2;
+        tc[1][j] = d1 + d2;
+        tc[2][j] = d2 - d1;
+        tc[3][j] = d1 - d3;
+    };
+    auto xform_row_store = [&](int i, int h) {  // stage 2 on row i of tile h: V = t B, to LDS
+        const float t0 = tc[i][2 * h + 0], t1 = tc[i][2 * h + 1], t2 = tc[i][2 * h + 2], t3 = tc[i][2 * h + 3];
+        float *o = lds + (h ? wrV ^ 4u : wrV) + 4 * i * PLANE;
+        o[0 * PLANE] = t0 - t2;
+        o[1 * PLANE] = t1 + t2;
+        o[2 * PLANE] = t2 - t1;
+        o[3 * PLANE] = t1 - t3;
+    };
+
+    floatx16 acc[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+
+    floatx4 bo[2][2];     // [register set][position of the pair]
+    auto read_b = [&](int pos, int set, int u) { bo[set][u] = lds4[(rdB >> 2) + pos * (PLANE / 4)]; };
+
+    const WinoTileCtx cx = {ub, ue, lb, nchunks, wm0, wn0, l32, lhi};
+
+    // cursors (unit -> tile, chunk) of the pipeline stages; units past the end of
+    // the range are clamped to the last one (harmless reloads)
+    const int ulast = ue - 1;
+    int c_tile = ub / nchunks, c_chunk = ub - c_tile * nchunks;          // compute: unit i
+    int u_tile = c_tile, u_chunk_i = c_chunk;                            // filter loads: unit i+1
+    int x_tile = c_tile, x_chunk_i = c_chunk;                            // patch loads: unit i+2
+    auto advance = [&](int &tile, int &chunk, int &unit) {
+        if (unit < ulast) {
+            ++unit;
+            if (++chunk == nchunks) { chunk = 0; ++tile; }
+        }
+    };
+    int u_unit = ub, x_unit = ub;
+
+    // ---- prologue: unit 0 into the first LDS buffer and the A registers, patch loads of unit 1 ----
+    set_tile_block(x_tile % a.tiles_t);
+#pragma unroll
+    for (int l = 0; l < NX; ++l) load_x(l, x_chunk_i);
+#pragma unroll
+    for (int p = 0; p < 16; ++p) load_a(p, u_tile / a.tiles_t, u_chunk_i);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) xform_col(j);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) xform_row_store(q >> 1, q & 1);
+    {
+        const int before = x_tile;
+        advance(x_tile, x_chunk_i, x_unit);
+        if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
+#pragma unroll
+        for (int l = 0; l < NX; ++l) load_x(l, x_chunk_i);
+        advance(u_tile, u_chunk_i, u_unit);
+    }
+    lds_barrier_wg();
+    wrV ^= BUFSZ;          // fill the other buffer from now on
+    read_b(0, 0, 0); read_b(1, 0, 1);
+
+    // One unit = 8 runs of 8 MFMAs (two positions x four reduction steps).  Gap g
+    // (before run g) reads the V operands of run g+1 and reloads the A registers of
+    // run g-1 for unit i+1 (gap 0: those of run 7, for unit i itself), one load after
+    // each read.  On top of that:
+    //   gap 0    : column half of the input transform of unit i+1, a patch load of
+    //              unit i+2 after each piece
+    //   gap 1, 2 : row half + LDS stores (one patch row of one tile per piece), the
+    //              remaining patch loads between the pieces
+    //   gap 7    : LDS-only barrier and buffer switch before the reads
+    int cc = c_chunk;                       // chunk of the compute unit
+    auto unit_body = [&]() {
+        const int ukt = u_tile / a.tiles_t, ckt = c_tile / a.tiles_t;
+        {
+            const int before = x_tile;
+            advance(x_tile, x_chunk_i, x_unit);
+            // the patch registers still hold unit i+1; its loads were issued during unit i-1
+            if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
+        }
+#pragma unroll
+        for (int pair = 0; pair < 8; ++pair) {
+            const int cur = pair & 1, nxt = cur ^ 1;
+            const int p0 = (2 * pair + 2) & 15, p1 = (2 * pair + 3) & 15;    // V positions read in this gap
+            const int q0 = (2 * pair + 14) & 15, q1 = (2 * pair + 15) & 15;  // A positions reloaded
+            if (pair == 7) {
+                lds_barrier_wg();
+                flip();
+            }
+            read_b(p0, nxt, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (pair == 0) load_a(q0, ckt, cc); else load_a(q0, ukt, u_chunk_i);
+            __builtin_amdgcn_sched_barrier(0);
+            read_b(p1, nxt, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (pair == 0) load_a(q1, ckt, cc); else load_a(q1, ukt, u_chunk_i);
+            __builtin_amdgcn_sched_barrier(0);
+            if (pair == 0) {
+#pragma unroll
+                for (int j = 0; j < 6; ++j) {
+                    xform_col(j);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_x(j, x_chunk_i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else if (pair == 1 || pair == 2) {
+#pragma unroll
+                for (int q = 4 * (pair - 1); q < 4 * pair; ++q) {
+                    xform_row_store(q >> 1, q & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (6 + q < NX) load_x(6 + q, x_chunk_i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int u = q & 1, ks = q >> 1;
+                acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[2 * pair + u][ks], bo[cur][u][ks],
+                                                                          acc[2 * pair + u], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        advance(u_tile, u_chunk_i, u_unit);
+        ++cc;
+    };
+    int first_unit = ub - c_chunk;          // first unit of the compute tile
+    int i = 0;
+    while (i < nunits) {
+        int seg_end = i + (nchunks - c_chunk);
+        if (seg_end > nunits) seg_end = nunits;
+        // the first chunk of a segment starts from C = 0 (also right for the head tile
+        // of the range: its earlier chunks belong to another workgroup)
+        for (; i < seg_end; ++i) unit_body();
+        wino_finish_tile<true>(a, acc, c_tile, first_unit, cx);
+        first_unit += nchunks;
+        ++c_tile;
+        c_chunk = 0;
+        cc = 0;
+    }
+}
+
 // Adds the two halves of every tile that a range boundary cut: boundary b lies
 // between ranges b and b+1; tail slot of b + head slot of b+1 + bias -> y.
 __global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
@@ -484,6 +773,7 @@ __global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
         const int n = tile / (a.TH * a.TW), rem = tile - n * (a.TH * a.TW);
         const int th = rem / a.TW, tw = rem - th * a.TW;
         const int oh = 2 * th, ow = 2 * tw;
+        if (ow >= a.Wout) continue;           // phantom tile of a widened tile grid
         float *o = a.out + ((int64_t)n * a.Kout + k) * HWo + (int64_t)oh * a.Wout + ow;
         const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
         o[0] = p[0] + q[0] + bz;
@@ -514,10 +804,24 @@ static hipError_t launch_wino_variant(const WinoArgs &a, int G, hipStream_t s)
     return hipGetLastError();
 }
 
+static hipError_t launch_wino_pair(const WinoArgs &a, int G, hipStream_t s)
+{
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(wino_pair_kernel, dim3((unsigned)G), dim3(256), kWinoPairLdsBytes, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s)
 {
     hipError_t e;
-    if (a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
+    if (a.mode == 1) e = launch_wino_pair(a, G, s);
+    else if (a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
     else e = launch_wino_variant<true>(a, G, s);
     if (e != hipSuccess || G < 2) return e;
     hipLaunchKernelGGL(wino_fixup_kernel, dim3((unsigned)(G - 1)), dim3(256), 0, s, a, G);

@@ -148,6 +148,11 @@ WINO_SHAPES = [
     # ragged filter and tile counts; second shape cuts tiles in backward-data
     G(40, 16, 28, 28, 136, 3, 3, 1, 1),
     G(36, 136, 26, 26, 24, 3, 3, 1, 1),
+    # tile-pair kernel (pad_w 1, even width) with other pad_h, narrow maps, rows ending
+    # inside a tile block
+    (2, 16, 7, 10, 24, 3, 3, 1, 1, 0, 1),
+    (3, 8, 9, 6, 16, 3, 3, 1, 1, 2, 1),
+    G(3, 24, 20, 36, 40, 3, 3, 1, 1),
 ]
 
 
