@@ -305,6 +305,9 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
                 lds_barrier();
                 read_ops(buf ^ 1, 0, nxt);
             }
+            // all side work of the step first, then its MFMAs back to back: every
+            // switch between the matrix pipe and other instructions costs a
+            // pipeline drain, so one gap per step beats one per MFMA
 #pragma unroll
             for (int q = 0; q < NMF; ++q) {
                 if (j == 0) {
@@ -320,11 +323,13 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
                         if (i * GSLOTS / B_ROWS == sidx) gather_issue(i);
                     if (sidx < A_PER_THREAD) filter_issue(t2, sidx);
                 }
-                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < NMF; ++q)
                 acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x2f32(
                     av[cur][q / NI], bv[cur][q % NI], acc[q / NI][q % NI], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 

@@ -215,11 +215,15 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs a)
                     for (int e = 0; e < NEL; ++e)
                         if (e * LSLOTS / NEL == l) load_el(e);
                 }
-                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the step's MFMAs back to back (one switch between the matrix pipe and
+            // other instructions per step instead of one per MFMA)
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < NMF; ++q)
                 acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x2f32(
                     av[cur][q / NI], bv[cur][q % NI], acc[q / NI][q % NI], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
