@@ -191,6 +191,14 @@ def main() -> int:
                                                                  f["xflops"] / f["ms"] / 1e9), file=sys.stderr)
         print("wall %.3f ms/step, %.2f TFLOP/s direct-equivalent (%.1f%% of fp32 MFMA peak)" % (
             ms_per_step, tflops, 100 * tflops / PEAK_MFMA_FP32_TFLOPS), file=sys.stderr)
+        # training skips the input gradient of the first layer: the same totals without it
+        first_bd = sum(per[("bwd_data", 0)]) / args.steps
+        ev_ms = sum(op_ms.values()) / args.steps
+        fl_wo = total_flops - recs[0]["flops"]
+        print("without first-layer bwd_data: %.3f ms/step (event sum), %.2f TFLOP/s direct-equivalent" % (
+            ev_ms - first_bd, fl_wo / ((ev_ms - first_bd) * 1e-3) / 1e12), file=sys.stderr)
+        if args.workload == "vgg16":
+            chained_forward(recs, ws, stream, args.algo)
 
     # roofline of the dominant kernel family: MFMA flops the algorithm executes
     # (not the direct-equivalent count) over the summed event durations of its calls
@@ -231,6 +239,33 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(cfg, layers)
     print(json.dumps(out))
     return 0
+
+
+def chained_forward(recs, ws, stream, algo):
+    """VGG-16 forward as a chain (outside the timed region): each layer's output,
+    max-pooled 2x2/stride 2 after every block (support code, a plain tensor
+    reduction), is the next layer's input.  Shows that the per-layer calls compose;
+    parity of the chain is covered by tests/test_gpu_chain.py."""
+    import torch
+    from paper_1606_04884_amd import binding as B
+    pool_after = {"conv1_2", "conv2_2", "conv3_3", "conv4_3"}
+    outs = [torch.empty_like(r["dy"]) for r in recs]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ms = []
+    for _ in range(3):
+        x = recs[0]["x"]
+        e0.record(stream)
+        for r, y in zip(recs, outs):
+            B.conv2d_fwd(r["geom"], x, r["w"], r["b"], y, ws=ws, algo=algo, stream=stream)
+            x = y
+            if r["L"].name in pool_after:
+                L = r["L"]
+                x = y.view(L.N, L.K, r["P"] // 2, 2, r["Q"] // 2, 2).amax(dim=(3, 5))
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    print("chained forward (13 conv calls + 4 max-pool reductions): %.3f ms (best of 3)" % min(ms),
+          file=sys.stderr)
 
 
 def cpu_baseline(cfg, layers):
