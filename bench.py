@@ -160,8 +160,10 @@ def main() -> int:
     def family(op, li):
         wino = recs[li]["algo"][op] == 2
         if op == "bwd_weight":
-            return "wino_wgrad_kernel (Winograd bwd_weight calls)" if wino else "wgrad_kernel (implicit-GEMM bwd_weight calls)"
-        return "wino_fused_kernel (Winograd fwd + bwd_data calls)" if wino else "gemmconv_kernel (implicit-GEMM fwd + bwd_data calls)"
+            return ("wino_wgrad (wino_wgrad_vec_kernel / wino_wgrad_kernel: Winograd bwd_weight calls)" if wino
+                    else "wgrad (wgrad_kernel: implicit-GEMM bwd_weight calls)")
+        return ("wino_fwd_bwd (wino_pair_kernel / wino_fused_kernel: Winograd fwd + bwd_data calls)" if wino
+                else "gemmconv (gemmconv_kernel / bwd_data_smallc_kernel: implicit-GEMM and direct fwd + bwd_data calls)")
 
     fam = {}
     op_ms = {"fwd": 0.0, "bwd_data": 0.0, "bwd_weight": 0.0}
@@ -187,7 +189,7 @@ def main() -> int:
         for op in op_ms:
             print("total %-10s %9.3f ms/step" % (op, op_ms[op] / args.steps), file=sys.stderr)
         for k, f in fam.items():
-            print("family %-55s %8.3f ms/step  exec %.1f TF/s" % (k, f["ms"] / args.steps,
+            print("family %-100s %8.3f ms/step  exec %.1f TF/s" % (k, f["ms"] / args.steps,
                                                                  f["xflops"] / f["ms"] / 1e9), file=sys.stderr)
         print("wall %.3f ms/step, %.2f TFLOP/s direct-equivalent (%.1f%% of fp32 MFMA peak)" % (
             ms_per_step, tflops, 100 * tflops / PEAK_MFMA_FP32_TFLOPS), file=sys.stderr)

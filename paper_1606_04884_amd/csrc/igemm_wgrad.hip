@@ -349,22 +349,27 @@ hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int
 }
 
 // Bias gradient, final stage: db[k] = scale * sum of the per-split partial sums.
+// One wave per filter: lane l adds the partials l, l+64, ... in order, then the 64
+// lane sums are combined in a fixed butterfly order (deterministic).
 __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float *__restrict__ part,
                                                               float *__restrict__ db, int K,
                                                               int nsplit, float scale, int accumulate)
 {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (k >= K) return;
     float s = 0.f;
-    for (int i = 0; i < nsplit; ++i) s += part[i * K + k];
+    for (int i = lane; i < nsplit; i += 64) s += part[i * K + k];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
     s *= scale;
-    db[k] = accumulate ? db[k] + s : s;
+    if (lane == 0) db[k] = accumulate ? db[k] + s : s;
 }
 
 hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
                              int accumulate, hipStream_t s)
 {
-    hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 3) / 4)), dim3(256), 0, s,
                        part, db, K, nsplit, scale, accumulate);
     return hipGetLastError();
 }

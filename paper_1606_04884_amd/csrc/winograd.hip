@@ -33,15 +33,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // --------------------------------------------------------- filter transform
-// U[pos][c][k] (k contiguous, zero padded to Cpad x Kpad); with `paired` set the
-// layout is U[pos][c/8][c%2][k][(c%8)/2] instead: the four channels that one MFMA
-// lane needs for the four reduction steps of a chunk are 16 contiguous bytes.
+// U[pos][c][k] (k contiguous, zero padded to Cpad x Kpad).
 // mode 0: forward, filters g = w[k][c].  mode 1: backward-data, the layer that
 // maps dy to dx has filters g'[c][k][r][s] = w[k][c][2-r][2-s]; its "k" is c.
 __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w,
                                                           float *__restrict__ U, int K, int C,
                                                           int Cin, int Kout, int Cpad, int Kpad,
-                                                          int mode, int paired)
+                                                          int mode)
 {
     const int64_t total = (int64_t)Cpad * Kpad;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
@@ -81,22 +79,88 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restric
             const float u1 = 0.5f * (t[r][0] + t[r][1] + t[r][2]);
             const float u2 = 0.5f * (t[r][0] - t[r][1] + t[r][2]);
             const float u3 = t[r][2];
-            const int64_t at = paired ? ((int64_t)((ci >> 3) * 2 + (ci & 1)) * Kpad + ko) * 4 + ((ci & 7) >> 1) : i;
-            U[(int64_t)(4 * r + 0) * total + at] = u0;
-            U[(int64_t)(4 * r + 1) * total + at] = u1;
-            U[(int64_t)(4 * r + 2) * total + at] = u2;
-            U[(int64_t)(4 * r + 3) * total + at] = u3;
+            U[(int64_t)(4 * r + 0) * total + i] = u0;
+            U[(int64_t)(4 * r + 1) * total + i] = u1;
+            U[(int64_t)(4 * r + 2) * total + i] = u2;
+            U[(int64_t)(4 * r + 3) * total + i] = u3;
         }
+    }
+}
+
+// The same transform writing the paired layout U[pos][c/8][c%2][k][(c%8)/2]: a
+// thread owns the four channels c = 8*chunk + half + 2*ks (ks = 0..3) of one filter
+// and stores each position as one 16-byte vector.
+__global__ __launch_bounds__(256) void wino_filter_paired_kernel(const float *__restrict__ w,
+                                                                 float *__restrict__ U, int C,
+                                                                 int Cin, int Kout, int Cpad, int Kpad,
+                                                                 int mode)
+{
+    const int64_t total = (int64_t)Cpad * Kpad;           // floats per position
+    const int64_t nvec = total / 4;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec;
+         v += (int64_t)gridDim.x * blockDim.x) {
+        const int ko = (int)(v % Kpad);
+        const int ch = (int)(v / Kpad);                   // chunk * 2 + half
+        floatx4 u[16];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int ci = (ch >> 1) * 8 + (ch & 1) + 2 * ks;
+            float g[3][3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s2 = 0; s2 < 3; ++s2) g[r][s2] = 0.f;
+            if (ci < Cin && ko < Kout) {
+                if (mode == 0) {
+                    const float *p = w + ((int64_t)ko * C + ci) * 9;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+#pragma unroll
+                        for (int s2 = 0; s2 < 3; ++s2) g[r][s2] = p[r * 3 + s2];
+                } else {
+                    const float *p = w + ((int64_t)ci * C + ko) * 9;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+#pragma unroll
+                        for (int s2 = 0; s2 < 3; ++s2) g[r][s2] = p[(2 - r) * 3 + (2 - s2)];
+                }
+            }
+            float t[4][3];
+#pragma unroll
+            for (int s2 = 0; s2 < 3; ++s2) {
+                t[0][s2] = g[0][s2];
+                t[1][s2] = 0.5f * (g[0][s2] + g[1][s2] + g[2][s2]);
+                t[2][s2] = 0.5f * (g[0][s2] - g[1][s2] + g[2][s2]);
+                t[3][s2] = g[2][s2];
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u[4 * r + 0][ks] = t[r][0];
+                u[4 * r + 1][ks] = 0.5f * (t[r][0] + t[r][1] + t[r][2]);
+                u[4 * r + 2][ks] = 0.5f * (t[r][0] - t[r][1] + t[r][2]);
+                u[4 * r + 3][ks] = t[r][2];
+            }
+        }
+#pragma unroll
+        for (int pos = 0; pos < 16; ++pos)
+            *reinterpret_cast<floatx4 *>(U + (int64_t)pos * total + v * 4) = u[pos];
     }
 }
 
 hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
                               int Kpad, int mode, int paired, hipStream_t s)
 {
+    if (paired) {
+        int64_t blocks = ((int64_t)Cpad * Kpad / 4 + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(wino_filter_paired_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, C,
+                           Cin, Kout, Cpad, Kpad, mode);
+        return hipGetLastError();
+    }
     int64_t blocks = ((int64_t)Cpad * Kpad + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, K, C, Cin,
-                       Kout, Cpad, Kpad, mode, paired);
+                       Kout, Cpad, Kpad, mode);
     return hipGetLastError();
 }
 
@@ -752,6 +816,9 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
 
 // Adds the two halves of every tile that a range boundary cut: boundary b lies
 // between ranges b and b+1; tail slot of b + head slot of b+1 + bias -> y.
+// Grid (G-1, 4): block (b, part) handles filters 16*part .. 16*part+15 of the cut
+// tile; a thread keeps one tile column (its image coordinates are computed once)
+// and walks over 4 filters.
 __global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
 {
     constexpr int KB = kWinoKB, TB = kWinoTB;
@@ -763,19 +830,25 @@ __global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
     const float *tailp = a.partial + ((int64_t)b * 2 + 1) * (KB * TB * 4);
     const float *headp = a.partial + ((int64_t)(b + 1) * 2 + 0) * (KB * TB * 4);
     const int HWo = a.Hout * a.Wout;
-    for (int e = threadIdx.x; e < KB * TB; e += 256) {
-        const int kl = e / TB, tloc = e - kl * TB;
-        const int k = kt * KB + kl, tile = tt * TB + tloc;
-        if (k >= a.Kout || tile >= a.T) continue;
+    const int tloc = threadIdx.x & 63;
+    const int tile = tt * TB + tloc;
+    if (tile >= a.T) return;
+    const int n = tile / (a.TH * a.TW), rem = tile - n * (a.TH * a.TW);
+    const int th = rem / a.TW, tw = rem - th * a.TW;
+    const int oh = 2 * th, ow = 2 * tw;
+    if (ow >= a.Wout) return;                 // phantom tile of a widened tile grid
+    const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+    float *obase = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int kl = blockIdx.y * 16 + (threadIdx.x >> 6) + 4 * i;
+        const int k = kt * KB + kl;
+        if (k >= a.Kout) continue;
+        const int e = kl * TB + tloc;
         const floatx4 p = *reinterpret_cast<const floatx4 *>(tailp + e * 4);
         const floatx4 q = *reinterpret_cast<const floatx4 *>(headp + e * 4);
         const float bz = a.bias ? a.bias[k] : 0.f;
-        const int n = tile / (a.TH * a.TW), rem = tile - n * (a.TH * a.TW);
-        const int th = rem / a.TW, tw = rem - th * a.TW;
-        const int oh = 2 * th, ow = 2 * tw;
-        if (ow >= a.Wout) continue;           // phantom tile of a widened tile grid
-        float *o = a.out + ((int64_t)n * a.Kout + k) * HWo + (int64_t)oh * a.Wout + ow;
-        const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+        float *o = obase + (int64_t)k * HWo;
         o[0] = p[0] + q[0] + bz;
         if (col1) o[1] = p[1] + q[1] + bz;
         if (row1) {
@@ -824,7 +897,7 @@ hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s)
     else if (a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
     else e = launch_wino_variant<true>(a, G, s);
     if (e != hipSuccess || G < 2) return e;
-    hipLaunchKernelGGL(wino_fixup_kernel, dim3((unsigned)(G - 1)), dim3(256), 0, s, a, G);
+    hipLaunchKernelGGL(wino_fixup_kernel, dim3((unsigned)(G - 1), 4), dim3(256), 0, s, a, G);
     return hipGetLastError();
 }
 
