@@ -738,11 +738,13 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
     // (before run g) reads the V operands of run g+1 and reloads the A registers of
     // run g-1 for unit i+1 (gap 0: those of run 7, for unit i itself), one load after
     // each read.  On top of that:
-    //   gap 0    : column half of the input transform of unit i+1, a patch load of
-    //              unit i+2 after each piece
-    //   gap 1, 2 : row half + LDS stores (one patch row of one tile per piece), the
-    //              remaining patch loads between the pieces
+    //   gap 0, 1 : column half of the input transform of unit i+1 (three columns per
+    //              gap), a patch load of unit i+2 after each piece
+    //   gap 2-5  : row half + LDS stores (one patch row of one tile per piece, two
+    //              pieces per gap), the remaining patch loads between the pieces
     //   gap 7    : LDS-only barrier and buffer switch before the reads
+    // (stores and loads spread over the gaps: bunched together, the four waves of the
+    // workgroup saturate the LDS and the texture-address path at the same moments)
     int cc = c_chunk;                       // chunk of the compute unit
     auto unit_body = [&]() {
         const int ukt = u_tile / a.tiles_t, ckt = c_tile / a.tiles_t;
@@ -769,17 +771,20 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
             __builtin_amdgcn_sched_barrier(0);
             if (pair == 0) load_a(q1, ckt, cc); else load_a(q1, ukt, u_chunk_i);
             __builtin_amdgcn_sched_barrier(0);
-            if (pair == 0) {
+            if (pair < 2) {
+                // three column pieces; patch loads 0-2 / 3-5 (the left dwords are free
+                // after column 0, the first two 16-byte pieces after column 4)
 #pragma unroll
-                for (int j = 0; j < 6; ++j) {
+                for (int j = 3 * pair; j < 3 * pair + 3; ++j) {
                     xform_col(j);
                     __builtin_amdgcn_sched_barrier(0);
                     load_x(j, x_chunk_i);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-            } else if (pair == 1 || pair == 2) {
+            } else if (pair < 6) {
+                // two row pieces (4 LDS stores) and, while there are any, two patch loads
 #pragma unroll
-                for (int q = 4 * (pair - 1); q < 4 * pair; ++q) {
+                for (int q = 2 * (pair - 2); q < 2 * (pair - 2) + 2; ++q) {
                     xform_row_store(q >> 1, q & 1);
                     __builtin_amdgcn_sched_barrier(0);
                     if (6 + q < NX) load_x(6 + q, x_chunk_i);
