@@ -98,6 +98,21 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
 int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias,
                float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
 
+/* Several 1x1, stride-1, unpadded convolutions of the SAME input in one pass over it
+ * (Sec. 4.2 singles out GoogLeNet's 1x1 layers; its inception module applies three of
+ * them to one input, and they are bound by reading that input).  Group g has K[g]
+ * filters w[g] (K[g] x C, device), an optional bias[g] (K[g], device; bias or bias[g]
+ * may be NULL) and its own output y[g] (N x K[g] x H x W, device), overwritten.
+ * d describes the stacked layer: R = S = 1, stride 1, pad 0 and d->K = sum of K[g];
+ * 1 <= ngroup <= 4.  K, w, bias and y are HOST arrays (of counts / device pointers)
+ * read before the call returns.  Workspace: conv2d_workspace_bytes(d, CONV2D_FWD,
+ * CONV2D_ALGO_IGEMM).  Every output element equals what conv2d_fwd computes for its
+ * group alone (same summation order).  Errors: CONV2D_ERR_ALGO if d is not a 1x1
+ * stride-1 unpadded layer, CONV2D_ERR_GEOMETRY for a bad group list. */
+int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, const int32_t *K,
+                         const float *const *w, const float *const *bias, float *const *y,
+                         void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Backward w.r.t. the input (Torch's updateGradInput; the benchmarks of Sec. 3.4
  * time forward plus backward).  Overwrites all of dx, including pixels no
  * output window covers (they get 0). */

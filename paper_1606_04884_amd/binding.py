@@ -17,7 +17,7 @@ ALGO_AUTO, ALGO_IGEMM, ALGO_WINOGRAD = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd",
-           "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version")
+           "conv2d_fwd_1x1_group", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version")
 
 
 class conv2d_desc(C.Structure):
@@ -53,6 +53,9 @@ def load() -> C.CDLL:
     lib.conv2d_workspace_bytes.restype = C.c_size_t
     lib.conv2d_fwd.argtypes = [dp, vp, vp, vp, vp, vp, C.c_size_t, C.c_int, vp]
     lib.conv2d_fwd.restype = C.c_int
+    lib.conv2d_fwd_1x1_group.argtypes = [dp, vp, C.c_int32, i32p, C.POINTER(vp), C.POINTER(vp),
+                                         C.POINTER(vp), vp, C.c_size_t, vp]
+    lib.conv2d_fwd_1x1_group.restype = C.c_int
     lib.conv2d_bwd_data.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, C.c_int, vp]
     lib.conv2d_bwd_data.restype = C.c_int
     lib.conv2d_bwd_weight.argtypes = [dp, vp, vp, vp, vp, C.c_float, C.c_int, vp, C.c_size_t,
@@ -154,6 +157,27 @@ def conv2d_fwd(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=None) ->
                            _stream(stream))
     if rc:
         raise Conv2dError(rc, "conv2d_fwd")
+
+
+def conv2d_fwd_1x1_group(d, x, ws_list, bias_list, ys, ws=None, stream=None) -> None:
+    """d describes the stacked layer (K = sum of the groups' filter counts); ws_list,
+    bias_list (entries or the whole list may be None) and ys are per-group tensors."""
+    dd = _desc(d)
+    n = len(ws_list)
+    if len(ys) != n or (bias_list is not None and len(bias_list) != n):
+        raise ValueError("group lists differ in length")
+    Ks = [int(w.shape[0]) for w in ws_list]
+    karr = (C.c_int32 * n)(*Ks)
+    warr = (C.c_void_p * n)(*[_ptr(w, (k, dd.C, 1, 1), "w[%d]" % i) for i, (w, k) in enumerate(zip(ws_list, Ks))])
+    yarr = (C.c_void_p * n)(*[_ptr(y, (dd.N, k, dd.H, dd.W), "y[%d]" % i) for i, (y, k) in enumerate(zip(ys, Ks))])
+    barr = None
+    if bias_list is not None:
+        barr = (C.c_void_p * n)(*[_ptr(b, (k,), "bias[%d]" % i) or None for i, (b, k) in enumerate(zip(bias_list, Ks))])
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, ALGO_IGEMM))
+    rc = load().conv2d_fwd_1x1_group(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"), n, karr, warr,
+                                     barr, yarr, wptr, wbytes, _stream(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_fwd_1x1_group")
 
 
 def conv2d_bwd_data(d, dy, w, dx, ws=None, algo: int = ALGO_AUTO, stream=None) -> None:

@@ -462,6 +462,73 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
     return launch_status(launch_gemmconv(a, p.tile, 1, s));
 }
 
+int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, const int32_t *K,
+                         const float *const *w, const float *const *bias, float *const *y, void *ws,
+                         size_t ws_bytes, void *hip_stream)
+{
+    Geom g;
+    int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (!x || !K || !w || !y) return CONV2D_ERR_NULL;
+    if (ngroup < 1 || ngroup > kMaxGroups) return CONV2D_ERR_GEOMETRY;
+    if (g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return CONV2D_ERR_ALGO;
+    int ksum = 0;
+    for (int i = 0; i < ngroup; ++i) {
+        if (K[i] < 1) return CONV2D_ERR_GEOMETRY;
+        if (!w[i] || !y[i]) return CONV2D_ERR_NULL;
+        ksum += K[i];
+    }
+    if (ksum != g.K) return CONV2D_ERR_GEOMETRY;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    const GatherPlan p = plan_fwd(g);
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *wt = (float *)ws;
+    DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);
+
+    PrepArgs pa = {};
+    pa.w = nullptr; pa.wt = wt; pa.tab = tab; pa.mode = 3;
+    pa.K = g.K; pa.C = g.C; pa.R = 1; pa.S = 1; pa.Kpad = p.Kpad;
+    pa.gather_chan_stride = g.H * g.W; pa.gather_W = g.W;
+    pa.stride_h = 1; pa.stride_w = 1;
+    pa.rows_total = (int32_t)p.rows_total; pa.nphases = 1;
+    pa.ph[0].row0 = 0; pa.ph[0].rows = g.C; pa.ph[0].rows_pad = (int32_t)p.rows_total;
+
+    GemmConvArgs a = {};
+    a.in = x; a.wt = wt; a.tab = tab; a.bias = nullptr; a.out = y[0];
+    a.N = g.N; a.Hin = g.H; a.Win = g.W; a.in_img_stride = g.C * g.H * g.W;
+    a.Kout = g.K; a.Kpad = p.Kpad; a.Hout = g.P; a.Wout = g.Q;
+    a.out_chan_stride = g.P * g.Q; a.out_img_stride = g.K * g.P * g.Q;
+    a.in_step_h = 1; a.in_step_w = 1; a.out_step_h = 1; a.out_step_w = 1;
+    a.tiles_k = p.Kpad / gemmconv_filter_tile(p.tile);
+    a.tiles_pix = ceil_div(g.N * g.P * g.Q, gemmconv_pixel_tile(p.tile));
+    a.phase[0].row0 = 0;
+    a.phase[0].depth_tiles = (int32_t)(p.rows_total / kDepthTile);
+    a.phase[0].in_base_h = 0; a.phase[0].in_base_w = 0;
+    a.phase[0].out_base_h = 0; a.phase[0].out_base_w = 0;
+    a.phase[0].Hs = g.P; a.phase[0].Ws = g.Q;
+    a.ngroup = ngroup;
+    int k0 = 0;
+    for (int i = 0; i <= kMaxGroups; ++i) {
+        pa.gk0[i] = k0;
+        a.grp_k0[i] = k0;
+        if (i < kMaxGroups) {
+            const bool used = i < ngroup;
+            pa.gw[i] = used ? w[i] : w[0];
+            a.grp_out[i] = used ? y[i] : y[0];
+            a.grp_bias[i] = (used && bias) ? bias[i] : nullptr;
+            if (used) k0 += K[i];
+        }
+    }
+    rc = launch_status(launch_gemmconv_prep(pa, s));
+    if (rc) return rc;
+    if (pointwise_ok(g, x, (int64_t)g.N * g.C * g.H * g.W)) {
+        a.pw_depth = g.C;
+        a.in_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+    }
+    return launch_status(launch_gemmconv(a, p.tile, 1, s));
+}
+
 int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float *dx, void *ws,
                     size_t ws_bytes, conv2d_algo algo, void *hip_stream)
 {

@@ -63,6 +63,8 @@ struct Phase {
     int32_t Hs, Ws;        // sub-grid size
 };
 
+constexpr int kMaxGroups = 4;
+
 struct GemmConvArgs {
     const float *in;
     const float *wt;           // [rows_total][Kpad]
@@ -81,6 +83,13 @@ struct GemmConvArgs {
     // pointwise fast path (1x1, stride 1, no padding, H*W % 4 == 0): pw_depth = number
     // of channels of `in` (0 selects the gather path), in_bytes = its size (< 2^31)
     int32_t pw_depth, in_bytes;
+    // grouped outputs (several convolutions of the same input in one pass): GEMM rows
+    // grp_k0[g] .. grp_k0[g+1]-1 are the filters of group g and go to grp_out[g]
+    // (N x K_g x Hout x Wout) with grp_bias[g] (nullable); ngroup == 0: single output
+    int32_t ngroup;
+    int32_t grp_k0[kMaxGroups + 1];
+    float *grp_out[kMaxGroups];
+    const float *grp_bias[kMaxGroups];
     Phase phase[kMaxPhases];
 };
 
@@ -94,7 +103,10 @@ struct PrepArgs {
     float *wt;
     DepthEntry *tab;
     int32_t mode;               // 0 forward, 1 backward-data by phases, 2 backward-data
-                                //   as one stride-1 gather with depth-to-space rows
+                                //   as one stride-1 gather with depth-to-space rows,
+                                //   3 forward with the filters of several groups stacked
+    const float *gw[kMaxGroups];        // mode 3: filters of group g, columns gk0[g] .. gk0[g+1]-1
+    int32_t gk0[kMaxGroups + 1];
     int32_t K, C, R, S, Kpad;   // Kpad = row pitch of wt
     int32_t gather_chan_stride, gather_W;   // of the tensor the main kernel gathers from
     int32_t stride_h, stride_w;

@@ -42,12 +42,23 @@ __global__ __launch_bounds__(256) void gemmconv_prep_kernel(PrepArgs a)
         e.off = 0;
         e.drdt = kInvalidDr << 16;
         if (d < ph.rows) {
-            if (a.mode == 0) {
+            if (a.mode == 0 || a.mode == 3) {
                 // forward: row d = (c, r, t), column = filter k
                 const int c = d / RS, rt = d - c * RS, r = rt / a.S, t = rt - r * a.S;
                 e.off = c * a.gather_chan_stride + r * a.gather_W + t;
                 e.drdt = (int32_t)(((uint32_t)r << 16) | ((uint32_t)t & 0xffffu));
-                if (col < a.K) v = a.w[(int64_t)col * a.C * RS + d];
+                if (col < a.K) {
+                    if (a.mode == 0) {
+                        v = a.w[(int64_t)col * a.C * RS + d];
+                    } else {
+                        // stacked groups: column col is filter col - gk0[g] of group g
+                        int g = 0;
+                        while (g + 1 < kMaxGroups && col >= a.gk0[g + 1]) ++g;
+                        const float *gw = g == 0 ? a.gw[0] : g == 1 ? a.gw[1] : g == 2 ? a.gw[2] : a.gw[3];
+                        const int k0 = g == 0 ? a.gk0[0] : g == 1 ? a.gk0[1] : g == 2 ? a.gk0[2] : a.gk0[3];
+                        v = gw[(int64_t)(col - k0) * a.C * RS + d];
+                    }
+                }
             } else if (a.mode == 2) {
                 // backward-data, all phases at once: row d = (k, dr, dt) over the union of
                 // the phases' tap displacements, column k' = (pa, pb, c): output pixel
@@ -362,6 +373,33 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
                     const int pa = (int)fast_div((uint32_t)pab, a.div_d2s_sw), pb = pab - pa * a.d2s_sw;
                     if (k < a.Kout && h0 + pa < a.Hout && v0 + pb < a.Wout)
                         op[(int64_t)c * a.out_chan_stride + pa * a.Wout + pb] = acc[mi][ni][v];
+                }
+            }
+        }
+        return;
+    }
+    if (a.ngroup > 0) {
+        // grouped outputs: GEMM row k is filter k - k0[g] of group g, stored to that
+        // group's own tensor (forward only: stride-1 output walk, one phase)
+        const int k1 = a.grp_k0[1], k2 = a.grp_k0[2], k3 = a.grp_k0[3];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int m = pt * BN + wn0 + ni * 32 + l32;
+            if (m >= Mpix) continue;
+            const int n = m / HWs, rem = m - n * HWs;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                    if (k >= a.Kout) continue;
+                    const int g = (k >= k1) + (k >= k2) + (k >= k3);
+                    float *o = g == 0 ? a.grp_out[0] : g == 1 ? a.grp_out[1] : g == 2 ? a.grp_out[2] : a.grp_out[3];
+                    const float *bp = g == 0 ? a.grp_bias[0] : g == 1 ? a.grp_bias[1] : g == 2 ? a.grp_bias[2] : a.grp_bias[3];
+                    const int k0 = g == 0 ? a.grp_k0[0] : g == 1 ? k1 : g == 2 ? k2 : k3;
+                    const int kend = g == 0 ? k1 : g == 1 ? k2 : g == 2 ? k3 : a.grp_k0[4];
+                    const int kl = k - k0, Kg = kend - k0;
+                    o[((int64_t)n * Kg + kl) * a.out_chan_stride + rem] = acc[mi][ni][v] + (bp ? bp[kl] : 0.f);
                 }
             }
         }

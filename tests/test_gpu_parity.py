@@ -228,3 +228,40 @@ def test_first_layer_backward_data_direct(geom):
     got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_AUTO, passes=("bwd_data",))
     ref = oracle.bwd_data(geom, dy, w)
     assert max_err_ratio(got["dx"], ref) <= TOL_IGEMM
+
+
+GROUP_CASES = [
+    # (N, C, H, W, [K_g...])
+    (3, 24, 10, 10, [16, 8, 40]),          # pointwise vector path (H*W % 4 == 0)
+    (2, 13, 7, 9, [5, 70]),                # gather path, ragged everything
+    (4, 192, 28, 28, [64, 96, 16]),        # the inception module's same-input 1x1 group
+    (2, 40, 6, 6, [33]),                   # a single group
+    (2, 16, 8, 8, [8, 8, 8, 8]),           # four groups
+]
+
+
+@pytest.mark.parametrize("case", GROUP_CASES, ids=[str(c[:4]) + str(c[4]) for c in GROUP_CASES])
+def test_grouped_1x1_forward(case):
+    """Several 1x1 convolutions of one input in one call: every group's output
+    against the oracle, and bit-identical to the single-layer call."""
+    import torch
+    N, Cc, H, W, Ks = case
+    dev = torch.device("cuda:0")
+    seed = 7000 + N + Cc + H + sum(Ks)
+    x = synth.normal((N, Cc, H, W), seed)
+    ws_np = [synth.normal((k, Cc, 1, 1), seed + 10 + i, std=float(np.sqrt(2.0 / Cc))) for i, k in enumerate(Ks)]
+    bs_np = [synth.uniform((k,), seed + 20 + i, -0.1, 0.1) if i != 1 else None for i, k in enumerate(Ks)]
+    tx = torch.from_numpy(x).to(dev)
+    tws = [torch.from_numpy(w).to(dev) for w in ws_np]
+    tbs = [torch.from_numpy(b).to(dev) if b is not None else None for b in bs_np]
+    ys = [torch.full((N, k, H, W), float("nan"), device=dev) for k in Ks]
+    geom = (N, Cc, H, W, sum(Ks), 1, 1, 1, 1, 0, 0)
+    print("case", case, flush=True)
+    B.conv2d_fwd_1x1_group(geom, tx, tws, tbs, ys)
+    torch.cuda.synchronize()
+    for i, k in enumerate(Ks):
+        g1 = (N, Cc, H, W, k, 1, 1, 1, 1, 0, 0)
+        ref = oracle.fwd(g1, x, ws_np[i], bs_np[i])
+        got = ys[i].cpu().numpy()
+        assert np.isfinite(got).all()
+        assert max_err_ratio(got, ref) <= TOL_IGEMM, "group %d" % i

@@ -96,3 +96,24 @@ def test_pick_algo_is_consistent_with_workspace():
             algo = B.conv2d_pick_algo(geom, op)
             assert algo in (B.ALGO_IGEMM, B.ALGO_WINOGRAD)
             assert B.conv2d_workspace_bytes(geom, op, algo) == B.conv2d_workspace_bytes(geom, op, B.ALGO_AUTO)
+
+
+def test_grouped_1x1_argument_checks():
+    lib = B.load()
+    vp = C.c_void_p
+    d = B.make_desc((2, 8, 6, 6, 12, 1, 1, 1, 1, 0, 0))
+    K = (C.c_int32 * 2)(4, 8)
+    one = (vp * 2)(1, 1)
+    need = B.conv2d_workspace_bytes(d, B.OP_FWD, B.ALGO_IGEMM)
+    # null lists, bad group count, filter counts that do not add up, workspace too small
+    assert lib.conv2d_fwd_1x1_group(C.byref(d), 1, 2, None, one, None, one, 1, need, None) == -1
+    assert lib.conv2d_fwd_1x1_group(C.byref(d), 1, 0, K, one, None, one, 1, need, None) == -2
+    assert lib.conv2d_fwd_1x1_group(C.byref(d), 1, 5, K, one, None, one, 1, need, None) == -2
+    Kbad = (C.c_int32 * 2)(4, 4)
+    assert lib.conv2d_fwd_1x1_group(C.byref(d), 1, 2, Kbad, one, None, one, 1, need, None) == -2
+    assert lib.conv2d_fwd_1x1_group(C.byref(d), 1, 2, K, one, None, one, 1, need - 1, None) == -4
+    nul = (vp * 2)(1, None)
+    assert lib.conv2d_fwd_1x1_group(C.byref(d), 1, 2, K, nul, None, one, 1, need, None) == -1
+    # not a 1x1 stride-1 unpadded layer
+    d3 = B.make_desc((2, 8, 6, 6, 12, 3, 3, 1, 1, 1, 1))
+    assert lib.conv2d_fwd_1x1_group(C.byref(d3), 1, 2, K, one, None, one, 1, 1 << 20, None) == -3
