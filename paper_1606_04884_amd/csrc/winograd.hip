@@ -182,7 +182,6 @@ __device__ __forceinline__ int xcd_remap_wino(int id, int nb)
 
 constexpr int kWinoKB = 64, kWinoTB = 64, kWinoCB = 8;
 constexpr int kWinoLdsBytes = 2 * 16 * kWinoCB * (kWinoKB + kWinoTB) * (int)sizeof(float);
-constexpr int kWinoPairLdsBytes = 2 * 16 * kWinoCB * kWinoTB * (int)sizeof(float);   // V planes only
 
 // Range of units of one persistent workgroup and the lane's place in the
 // accumulator layout, for the tile epilogue shared by the fused kernels.
@@ -552,46 +551,68 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// Tile-pair variant of the fused kernel, for pad_w = 1 and an even input width.
+// Tile-pair kernel, for pad_w = 1, an even input width and an even number of tiles
+// per row.
 //
-// Same decomposition, accumulators and epilogue as wino_fused_kernel; what
-// differs is how a chunk is staged, built on three measurements on this chip:
-// (1) fp32 MFMAs and other vector instructions do not overlap, and every
-// switch between a run of MFMAs and other instructions costs a pipeline drain
-// (~11 cycles), so the MFMAs are issued in runs of 8 with all side work in the
-// 8 gaps of a chunk; (2) a vector-memory instruction holds its wave for ~25
-// cycles when a few other instructions separate it from the next one and ~55
-// when loads are back to back, so the loads are spread between the other
-// pieces; (3) LDS traffic costs the wave time in proportion to its bytes.
+// Same decomposition (stream-K over 64 filters x 64 tiles x 16 positions) and the
+// same result as wino_fused_kernel; what differs is how a chunk is staged, built
+// on measurements on this chip: (1) fp32 MFMAs and other vector instructions do
+// not overlap, a wave issues in order, and every switch between a run of MFMAs and
+// other instructions costs a pipeline drain (~11 cycles): the MFMAs are issued in
+// runs of 8 with all side work in the gaps; (2) a vector-memory instruction holds
+// its wave for ~25 cycles when a few other instructions separate it from the next
+// one and ~55 when loads are back to back: few, wide loads, spread between the
+// other pieces; (3) LDS traffic costs the wave time in proportion to its bytes;
+// (4) the side work of a wave can overlap the MFMAs of ANOTHER wave on its SIMD.
 //   * A thread owns one channel of the chunk and a PAIR of horizontally adjacent
 //     tiles: the two 4x4 patches are a 4 x 6 block, fetched per row as dword +
-//     16 bytes + dword (12 loads per chunk instead of 24); the column half of
-//     B^T d B is shared by the two patches.  The tile grid is taken with its
-//     row width even (the host picks this kernel only then), so a pair never
-//     straddles two tile rows and the 16 bytes never leave the image row.
+//     16 bytes + dword; the column half of B^T d B is shared by the two patches.
+//     The tile grid has an even row width (the host picks this kernel only then),
+//     so a pair never straddles two tile rows and the 16 bytes never leave the
+//     image row.
 //   * The V planes in LDS are [buf][pos][half][64 tiles][4]: the four channels a
 //     lane needs for the four reduction steps of a chunk are 16 contiguous
-//     bytes, one read per position.  The two buffers are 32 KB apart: switching
-//     is one XOR per base register.
+//     bytes, one read per position; adjacent columns swap in the second
+//     half-plane so that the stores of a half-wave (4 pairs x 8 channels) fall in
+//     32 different banks.  The two buffers are 32 KB apart: switching is one XOR
+//     per base register.
 //   * The transformed filters do not go through LDS at all: the filter transform
 //     writes U as [pos][chunk][half][filter][4], so the MFMA A operand of a lane
 //     for one position of a chunk is 16 contiguous bytes of U, loaded straight
-//     into the registers the MFMAs read (from L2; the two waves sharing a filter
-//     half hit the same lines).  The registers of a position pair are reloaded
-//     for the next unit in the gap after their last MFMA.
-__global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
+//     into the registers the MFMAs read (from L2).  The registers of a position
+//     pair are reloaded for the next unit in the gap after their last MFMA.
+//   * Eight waves, two per SIMD (point 4).  The 512 registers of a lane are split
+//     between the two: a wave keeps 8 of the 16 positions of one 32x32 sub-tile
+//     (128 accumulator registers).  Wave w: sub-tile sub = w % 4, position half
+//     PH = w / 4; waves w and w + 4 share a SIMD.  Everything is split by PH:
+//       - transform: a thread handles (tile pair, channel, PH): the 8 positions of
+//         half PH are rows 2*PH, 2*PH+1 of B^T d B, which need only three of the
+//         four patch rows (PH..PH+2): 9 loads, 12 + 16 adds, 8 paired LDS stores
+//         per chunk;
+//       - MFMA: positions 8*PH .. 8*PH+7 of the sub-tile, 4 runs of 8; B operands
+//         from the V planes of half PH, which only the four waves of the same PH
+//         write and read;
+//       - epilogue: Y = A^T M A is a sum over the rows of M, so each wave reduces
+//         its two rows to a partial 2x2 output per accumulator element; the
+//         partials of the elements the partner finishes go through LDS (one
+//         16-byte vector per element), a barrier, and each wave adds, applies the
+//         bias and stores half of the elements.
+// V planes (two buffers) + the exchange area of the epilogue
+constexpr int kWinoPairLdsBytes = 2 * 16 * kWinoCB * kWinoTB * (int)sizeof(float) + 4 * 2 * 8 * 64 * 16;
+
+template <int PH>
+__device__ __forceinline__ void wino_pair_body(const WinoArgs &a, float *lds)
 {
-    constexpr int KB = kWinoKB, CB = kWinoCB;
-    constexpr int NXO = 3;                    // loads per row of a patch pair
-    constexpr int NX = 4 * NXO;
+    constexpr int KB = kWinoKB, TB = kWinoTB, CB = kWinoCB;
+    constexpr int NX = 9;
     constexpr int PLANE = 512;                // floats per (buf, pos): 2 halves x 64 x 4
     constexpr int BUFSZ = 16 * PLANE;         // floats per buffer (32 KB)
-    extern __shared__ __attribute__((aligned(16))) float lds[];
     floatx4 *const lds4 = reinterpret_cast<floatx4 *>(lds);
+    floatx4 *const xchg = lds4 + 2 * BUFSZ / 4;          // [sub][writer PH][8 elements][64 lanes]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
     const int l32 = lane & 31, lhi = lane >> 5;
 
     const int G = gridDim.x;
@@ -602,83 +623,74 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
     if (nunits <= 0) return;
     const int nchunks = a.nchunks;
 
-    // a half-wave holds 4 tile pairs x 8 channels: its LDS stores of one value then
-    // fall in 32 different banks (see the V plane layout below)
-    const int pr = wave * 8 + (lhi << 2) + (lane & 3);     // tile pair of the block: tiles 2*pr, 2*pr + 1
-    const int ch = (lane >> 2) & 7;                         // channel of the chunk
+    const int pr = sub * 8 + (lhi << 2) + (lane & 3);     // tile pair of the block
+    const int ch = (lane >> 2) & 7;                        // channel of the chunk
     const int HW = a.Hin * a.Win;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t ursrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.U, 0, a.u_bytes, 0x00020000);
-    // byte offsets of the row pieces inside chunk 0 (channel ch), or 2^31 for "outside"
-    uint32_t xo[4][NXO];
+    // patch rows PH .. PH+2: byte offsets of the row pieces inside chunk 0, or 2^31
+    uint32_t xo[3][3];
     auto set_tile_block = [&](int tt) {
-        const int tile = tt * kWinoTB + 2 * pr;
+        const int tile = tt * TB + 2 * pr;
         const bool tv = tile < a.T;
         const int tl = tv ? tile : 0;
         const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
         const int th = rem / a.TW, tw = rem - th * a.TW;       // tw even
-        const int ih0 = 2 * th - a.pad_h, col0 = 2 * tw;         // patch pair: columns col0-1 .. col0+4
+        const int ih0 = 2 * th - a.pad_h + PH, col0 = 2 * tw;
         const int base = (n * a.Cin + ch) * HW + ih0 * a.Win + col0;
         const bool lok = tw > 0, rgt = col0 + 4 < a.Win;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 3; ++i) {
             const bool rok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin;
             const uint32_t m = (uint32_t)(base + i * a.Win) * 4u;
             xo[i][0] = (rok && lok) ? m - 4u : 0x80000000u;
             xo[i][1] = rok ? m : 0x80000000u;
-            xo[i][NXO - 1] = (rok && rgt) ? m + 16u : 0x80000000u;
+            xo[i][2] = (rok && rgt) ? m + 16u : 0x80000000u;
         }
     };
-    const int x_chunk = CB * HW * 4;                  // bytes per chunk of channels
+    const int x_chunk = CB * HW * 4;
 
-    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
-    // A operand of this lane: U[pos][chunk][half = lhi][filter wm0 + l32][0..3]
-    const int u_plane = a.Kpad * 16;                  // bytes per (pos, chunk, half)
-    const uint32_t aoff0 = (uint32_t)lhi * (uint32_t)u_plane + (uint32_t)(wm0 + l32) * 16u;
+    const int wm0 = (sub >> 1) * 32, wn0 = (sub & 1) * 32;
+    const int u_plane = a.Kpad * 16;
     const int u_pos_stride = nchunks * 2 * u_plane;
     const int u_chunk = 2 * u_plane;
+    const uint32_t aoff0 = (uint32_t)lhi * (uint32_t)u_plane + (uint32_t)(wm0 + l32) * 16u;
+    const int a_pos0 = 8 * PH * u_pos_stride;
 
-    float xr[4][6];
-    floatx4 ar[16];
-    // x load number l, in the order in which the column transform frees the
-    // registers: the left dwords of the four rows, the middle pieces, the right dwords
+    float xr[3][6];
+    floatx4 ar[8];
+    // x load l: part = l / 3 (left dword, 16 bytes, right dword), row = l % 3
     auto load_x = [&](int l, int chunk) {
-        const int part = l >> 2, i = l & 3;
+        const int part = l / 3, i = l - 3 * part;
         const int so = chunk * x_chunk;
         if (part == 0) {
             xr[i][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][0], so, 0));
-        } else if (part == NXO - 1) {
-            xr[i][5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][NXO - 1], so, 0));
+        } else if (part == 2) {
+            xr[i][5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][2], so, 0));
         } else {
-            // (cast the whole result vector, then index the cast value)
             const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xo[i][1], so, 0));
             xr[i][1] = m[0]; xr[i][2] = m[1]; xr[i][3] = m[2]; xr[i][4] = m[3];
         }
     };
-    auto load_a = [&](int pos, int kt, int chunk) {
-        ar[pos] = __builtin_bit_cast(
-            floatx4, __builtin_amdgcn_raw_buffer_load_b128(ursrc, aoff0, chunk * u_chunk + kt * (KB * 16) + pos * u_pos_stride, 0));
+    auto load_a = [&](int p, int kt, int chunk) {
+        ar[p] = __builtin_bit_cast(
+            floatx4, __builtin_amdgcn_raw_buffer_load_b128(ursrc, aoff0, a_pos0 + chunk * u_chunk + kt * (KB * 16) + p * u_pos_stride, 0));
     };
 
-    // LDS float offsets; `wrV` points into the buffer being filled, `rdB` into the
-    // buffer being multiplied; one XOR switches each.
-    // V plane: column of tile t in half-plane `half` is t ^ half (adjacent columns swap
-    // in the second half-plane), which spreads the stores of a half-wave over all banks
-    uint32_t wrV = (ch & 1) * 256 + (2 * pr + (ch & 1)) * 4 + (ch >> 1);   // tile 2*pr; tile 2*pr+1 is at wrV ^ 4
-    uint32_t rdB = lhi * 256 + ((wn0 + l32) ^ lhi) * 4;                    // a multiple of 4
+    uint32_t wrV = 8 * PH * PLANE + (ch & 1) * 256 + (2 * pr + (ch & 1)) * 4 + (ch >> 1);
+    uint32_t rdB = 8 * PH * PLANE + lhi * 256 + ((wn0 + l32) ^ lhi) * 4;
     auto flip = [&]() { wrV ^= BUFSZ; rdB ^= BUFSZ; };
 
-    float tc[4][6];
-    auto xform_col = [&](int j) {               // stage 1 on column j of the pair: t = B^T d
-        const float d0 = xr[0][j], d1 = xr[1][j], d2 = xr[2][j], d3 = xr[3][j];
-        tc[0][j] = d0 - d2;
-        tc[1][j] = d1 + d2;
-        tc[2][j] = d2 - d1;
-        tc[3][j] = d1 - d3;
+    // rows 2*PH, 2*PH+1 of t = B^T d on column j of the pair (xr rows are patch rows PH..PH+2)
+    float tc[2][6];
+    auto xform_col = [&](int j) {
+        const float e0 = xr[0][j], e1 = xr[1][j], e2 = xr[2][j];
+        if (PH == 0) { tc[0][j] = e0 - e2; tc[1][j] = e1 + e2; }       // d0-d2, d1+d2
+        else         { tc[0][j] = e1 - e0; tc[1][j] = e0 - e2; }       // d2-d1, d1-d3
     };
-    auto xform_row_store = [&](int i, int h) {  // stage 2 on row i of tile h: V = t B, to LDS
+    auto xform_row_store = [&](int i, int h) {
         const float t0 = tc[i][2 * h + 0], t1 = tc[i][2 * h + 1], t2 = tc[i][2 * h + 2], t3 = tc[i][2 * h + 3];
         float *o = lds + (h ? wrV ^ 4u : wrV) + 4 * i * PLANE;
         o[0 * PLANE] = t0 - t2;
@@ -687,23 +699,19 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
         o[3 * PLANE] = t1 - t3;
     };
 
-    floatx16 acc[16];
+    floatx16 acc[8];
 #pragma unroll
-    for (int p = 0; p < 16; ++p)
+    for (int p = 0; p < 8; ++p)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
 
-    floatx4 bo[2][2];     // [register set][position of the pair]
+    floatx4 bo[2][2];
     auto read_b = [&](int pos, int set, int u) { bo[set][u] = lds4[(rdB >> 2) + pos * (PLANE / 4)]; };
 
-    const WinoTileCtx cx = {ub, ue, lb, nchunks, wm0, wn0, l32, lhi};
-
-    // cursors (unit -> tile, chunk) of the pipeline stages; units past the end of
-    // the range are clamped to the last one (harmless reloads)
     const int ulast = ue - 1;
-    int c_tile = ub / nchunks, c_chunk = ub - c_tile * nchunks;          // compute: unit i
-    int u_tile = c_tile, u_chunk_i = c_chunk;                            // filter loads: unit i+1
-    int x_tile = c_tile, x_chunk_i = c_chunk;                            // patch loads: unit i+2
+    int c_tile = ub / nchunks, c_chunk = ub - c_tile * nchunks;
+    int u_tile = c_tile, u_chunk_i = c_chunk;
+    int x_tile = c_tile, x_chunk_i = c_chunk;
     auto advance = [&](int &tile, int &chunk, int &unit) {
         if (unit < ulast) {
             ++unit;
@@ -712,16 +720,16 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
     };
     int u_unit = ub, x_unit = ub;
 
-    // ---- prologue: unit 0 into the first LDS buffer and the A registers, patch loads of unit 1 ----
+    // ---- prologue ----
     set_tile_block(x_tile % a.tiles_t);
 #pragma unroll
     for (int l = 0; l < NX; ++l) load_x(l, x_chunk_i);
 #pragma unroll
-    for (int p = 0; p < 16; ++p) load_a(p, u_tile / a.tiles_t, u_chunk_i);
+    for (int p = 0; p < 8; ++p) load_a(p, u_tile / a.tiles_t, u_chunk_i);
 #pragma unroll
     for (int j = 0; j < 6; ++j) xform_col(j);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) xform_row_store(q >> 1, q & 1);
+    for (int q = 0; q < 4; ++q) xform_row_store(q >> 1, q & 1);
     {
         const int before = x_tile;
         advance(x_tile, x_chunk_i, x_unit);
@@ -731,63 +739,56 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
         advance(u_tile, u_chunk_i, u_unit);
     }
     lds_barrier_wg();
-    wrV ^= BUFSZ;          // fill the other buffer from now on
+    wrV ^= BUFSZ;
     read_b(0, 0, 0); read_b(1, 0, 1);
 
-    // One unit = 8 runs of 8 MFMAs (two positions x four reduction steps).  Gap g
-    // (before run g) reads the V operands of run g+1 and reloads the A registers of
-    // run g-1 for unit i+1 (gap 0: those of run 7, for unit i itself), one load after
-    // each read.  On top of that:
-    //   gap 0, 1 : column half of the input transform of unit i+1 (three columns per
-    //              gap), a patch load of unit i+2 after each piece
-    //   gap 2-5  : row half + LDS stores (one patch row of one tile per piece, two
-    //              pieces per gap), the remaining patch loads between the pieces
-    //   gap 7    : LDS-only barrier and buffer switch before the reads
-    // (stores and loads spread over the gaps: bunched together, the four waves of the
-    // workgroup saturate the LDS and the texture-address path at the same moments)
-    int cc = c_chunk;                       // chunk of the compute unit
+    // One unit = 4 runs of 8 MFMAs.  Gap r (before run r) reads the V operands of run
+    // r+1 and reloads the A registers of run r-1 for unit i+1 (gap 0: those of run 3,
+    // for unit i itself).  Gap 0 also holds the column half of the transform of unit
+    // i+1 with six patch loads of unit i+2 between the pieces, gaps 1 and 2 the row
+    // half (two pieces each) with the remaining loads, gap 3 the barrier.
+    int cc = c_chunk;
     auto unit_body = [&]() {
         const int ukt = u_tile / a.tiles_t, ckt = c_tile / a.tiles_t;
         {
             const int before = x_tile;
             advance(x_tile, x_chunk_i, x_unit);
-            // the patch registers still hold unit i+1; its loads were issued during unit i-1
             if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
         }
 #pragma unroll
-        for (int pair = 0; pair < 8; ++pair) {
-            const int cur = pair & 1, nxt = cur ^ 1;
-            const int p0 = (2 * pair + 2) & 15, p1 = (2 * pair + 3) & 15;    // V positions read in this gap
-            const int q0 = (2 * pair + 14) & 15, q1 = (2 * pair + 15) & 15;  // A positions reloaded
-            if (pair == 7) {
+        for (int run = 0; run < 4; ++run) {
+            const int cur = run & 1, nxt = cur ^ 1;
+            const int p0 = (2 * run + 2) & 7, p1 = (2 * run + 3) & 7;
+            const int q0 = (2 * run + 6) & 7, q1 = (2 * run + 7) & 7;
+            if (run == 3) {
                 lds_barrier_wg();
                 flip();
             }
             read_b(p0, nxt, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (pair == 0) load_a(q0, ckt, cc); else load_a(q0, ukt, u_chunk_i);
+            if (run == 0) load_a(q0, ckt, cc); else load_a(q0, ukt, u_chunk_i);
             __builtin_amdgcn_sched_barrier(0);
             read_b(p1, nxt, 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (pair == 0) load_a(q1, ckt, cc); else load_a(q1, ukt, u_chunk_i);
+            if (run == 0) load_a(q1, ckt, cc); else load_a(q1, ukt, u_chunk_i);
             __builtin_amdgcn_sched_barrier(0);
-            if (pair < 2) {
-                // three column pieces; patch loads 0-2 / 3-5 (the left dwords are free
-                // after column 0, the first two 16-byte pieces after column 4)
+            if (run == 0) {
+                // columns 0..5; the left dwords are free after column 0, the 16-byte
+                // pieces after column 4
 #pragma unroll
-                for (int j = 3 * pair; j < 3 * pair + 3; ++j) {
+                for (int j = 0; j < 6; ++j) {
                     xform_col(j);
                     __builtin_amdgcn_sched_barrier(0);
-                    load_x(j, x_chunk_i);
+                    if (j < 3) load_x(j, x_chunk_i);
+                    else if (j >= 4) load_x(j - 1, x_chunk_i);       // loads 3, 4
                     __builtin_amdgcn_sched_barrier(0);
                 }
-            } else if (pair < 6) {
-                // two row pieces (4 LDS stores) and, while there are any, two patch loads
+            } else if (run < 3) {
 #pragma unroll
-                for (int q = 2 * (pair - 2); q < 2 * (pair - 2) + 2; ++q) {
+                for (int q = 2 * (run - 1); q < 2 * run; ++q) {
                     xform_row_store(q >> 1, q & 1);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (6 + q < NX) load_x(6 + q, x_chunk_i);
+                    load_x(5 + q, x_chunk_i);                         // loads 5 .. 8
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -795,28 +796,107 @@ __global__ __launch_bounds__(256, 1) void wino_pair_kernel(WinoArgs a)
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const int u = q & 1, ks = q >> 1;
-                acc[2 * pair + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[2 * pair + u][ks], bo[cur][u][ks],
-                                                                          acc[2 * pair + u], 0, 0, 0);
+                acc[2 * run + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[2 * run + u][ks], bo[cur][u][ks],
+                                                                         acc[2 * run + u], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
         advance(u_tile, u_chunk_i, u_unit);
         ++cc;
     };
-    int first_unit = ub - c_chunk;          // first unit of the compute tile
+
+    // tile epilogue: partial output transform of this wave's two rows of M
+    auto partial = [&](int v) -> floatx4 {
+        float s0[4], s1[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float ma = acc[j][v], mb = acc[4 + j][v];      // rows 2*PH, 2*PH+1
+            if (PH == 0) { s0[j] = ma + mb; s1[j] = mb; }
+            else         { s0[j] = ma; s1[j] = -ma - mb; }
+        }
+        floatx4 y;
+        y[0] = s0[0] + s0[1] + s0[2]; y[1] = s0[1] - s0[2] - s0[3];
+        y[2] = s1[0] + s1[1] + s1[2]; y[3] = s1[1] - s1[2] - s1[3];
+        return y;
+    };
+    auto finish_tile = [&](int tile_id, int first_unit) {
+        const int kt = tile_id / a.tiles_t, tt = tile_id - kt * a.tiles_t;
+        const bool head = first_unit < ub, tail = first_unit + nchunks > ue;
+        // this wave finishes elements 8*PH .. 8*PH+7; the partner's partials for them
+        // arrive through LDS, ours for the partner's elements go out the same way
+        floatx4 *const xw = xchg + ((sub * 2 + PH) * 8) * 64 + lane;
+        const floatx4 *const xrd = xchg + ((sub * 2 + (1 - PH)) * 8) * 64 + lane;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            __builtin_amdgcn_sched_barrier(0);
+            xw[e * 64] = partial(8 * (1 - PH) + e);
+        }
+        lds_barrier_wg();
+        const int tile = tt * TB + wn0 + l32;
+        const int tl = tile < a.T ? tile : 0;
+        const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
+        const int th = rem / a.TW, tw = rem - th * a.TW;
+        const int oh = 2 * th, ow = 2 * tw;
+        const bool tv = tile < a.T && ow < a.Wout;
+        const bool row1 = oh + 1 < a.Hout, col1 = ow + 1 < a.Wout;
+        const int HWo = a.Hout * a.Wout;
+        const int kbase = kt * KB + wm0 + 4 * lhi;
+        float *ob = a.out + (int64_t)n * a.Kout * HWo + (int64_t)oh * a.Wout + ow + (int64_t)kbase * HWo;
+        const float *bp = a.bias ? a.bias + kbase : nullptr;
+        float *sp = a.partial + ((int64_t)lb * 2 + (head ? 0 : 1)) * (KB * TB * 4) +
+                    ((wm0 + 4 * lhi) * TB + wn0 + l32) * 4;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            __builtin_amdgcn_sched_barrier(0);
+            const int v = 8 * PH + e;
+            const int kr = 8 * (v >> 2) + (v & 3);
+            floatx4 y = partial(v);
+            const floatx4 o4 = xrd[e * 64];
+            y[0] += o4[0]; y[1] += o4[1]; y[2] += o4[2]; y[3] += o4[3];
+            if (head || tail) {
+                *reinterpret_cast<floatx4 *>(sp + (kr * TB) * 4) = y;
+            } else if (tv && kbase + kr < a.Kout) {
+                const float bz = bp ? bp[kr] : 0.f;
+                float *o = ob + (int64_t)kr * HWo;
+                if (a.vec2) {
+                    *reinterpret_cast<float2 *>(o) = make_float2(y[0] + bz, y[1] + bz);
+                    if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y[2] + bz, y[3] + bz);
+                } else {
+                    o[0] = y[0] + bz;
+                    if (col1) o[1] = y[1] + bz;
+                    if (row1) {
+                        o[a.Wout] = y[2] + bz;
+                        if (col1) o[a.Wout + 1] = y[3] + bz;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
+    };
+
+    int first_unit = ub - c_chunk;
     int i = 0;
     while (i < nunits) {
         int seg_end = i + (nchunks - c_chunk);
         if (seg_end > nunits) seg_end = nunits;
-        // the first chunk of a segment starts from C = 0 (also right for the head tile
-        // of the range: its earlier chunks belong to another workgroup)
         for (; i < seg_end; ++i) unit_body();
-        wino_finish_tile<true>(a, acc, c_tile, first_unit, cx);
+        finish_tile(c_tile, first_unit);
         first_unit += nchunks;
         ++c_tile;
         c_chunk = 0;
         cc = 0;
     }
+}
+
+__global__ __launch_bounds__(512, 1) void wino_pair_kernel(WinoArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    // both halves run the same sequence of barriers
+    if (threadIdx.x < 256) wino_pair_body<0>(a, lds);
+    else wino_pair_body<1>(a, lds);
 }
 
 // Adds the two halves of every tile that a range boundary cut: boundary b lies
@@ -891,7 +971,7 @@ static hipError_t launch_wino_pair(const WinoArgs &a, int G, hipStream_t s)
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(wino_pair_kernel, dim3((unsigned)G), dim3(256), kWinoPairLdsBytes, s, a);
+    hipLaunchKernelGGL(wino_pair_kernel, dim3((unsigned)G), dim3(512), kWinoPairLdsBytes, s, a);
     return hipGetLastError();
 }
 
