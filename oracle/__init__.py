@@ -154,3 +154,15 @@ def bwd_weight_at(geom, x, dy, idx, scale: float = 1.0) -> np.ndarray:
     if rc:
         raise ValueError("oracle bwd_weight_at rc=%d" % rc)
     return out
+
+
+def apply_mul_add(x: np.ndarray, a: float, b: float) -> np.ndarray:
+    """Per-element operation of the paper's Sec. 3.3 experiment (bandwidth of
+    per-element kernels against tensor size; the paper does not say which
+    operation it timed): y[i] = fl(fl(a * x[i]) + b), both operations rounded to
+    fp32 separately (no fused multiply-add), as a Torch `mul` followed by `add`.
+    Plain numpy; fp32 in, fp32 out (the precision is part of the definition)."""
+    if x.dtype != np.float32:
+        raise ValueError("expected float32")
+    t = np.multiply(x, np.float32(a), dtype=np.float32)
+    return np.add(t, np.float32(b), dtype=np.float32)
