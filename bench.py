@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 PEAK_MFMA_FP32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
 
-WORKLOADS = {"tiny": 0, "alexnet": 1, "vgg16": 2, "inception": 3, "overfeat": 4}
+WORKLOADS = {"tiny": 0, "alexnet": 1, "vgg16": 2, "inception": 3, "overfeat": 4, "apply": -1}
 
 
 def layer_flops(L, P, Q):
@@ -77,6 +77,8 @@ def main() -> int:
     B.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "apply":
+        return bench_apply(args, dev)
     cfg = WORKLOADS[args.workload]
     layers = synth.config_layers(cfg, args.batch or None)
 
@@ -241,6 +243,66 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layers)
+    print(json.dumps(out))
+    return 0
+
+
+def bench_apply(args, dev):
+    """The per-element experiment of Sec. 3.3: bandwidth of one per-element kernel
+    launch (y = a*x + b, 8 bytes per element) against the number of floats per
+    launch.  The curve goes to stderr; the JSON line is the point at 1e7 floats,
+    the size the paper singles out.  Each size rotates over enough distinct buffers
+    (> 512 MB in total for the large sizes) that repeats are not served from cache."""
+    import numpy as np
+    import torch
+    from paper_1606_04884_amd import binding as B
+    import oracle
+    stream = torch.cuda.current_stream()
+    sizes = [10 ** 3, 10 ** 4, 10 ** 5, 10 ** 6, 10 ** 7, 10 ** 8]
+    pool = torch.randn(1 << 28, device=dev)              # 1 GiB of input
+    outp = torch.empty(1 << 28, device=dev)
+    curve = {}
+    for n in sizes:
+        nbuf = max(1, min(64, (1 << 28) // ((n + 1023) // 1024 * 1024)))
+        pitch = (1 << 28) // nbuf // 1024 * 1024
+        reps = max(args.steps * 4, min(2000, (1 << 27) // n + 1))
+        for i in range(args.warmup + 2):
+            o = (i % nbuf) * pitch
+            B.apply_mul_add(pool[o:o + n], outp[o:o + n], 1.5, 0.25, stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(reps):
+            o = (i % nbuf) * pitch
+            B.apply_mul_add(pool[o:o + n], outp[o:o + n], 1.5, 0.25, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        curve[n] = (us, 8.0 * n / (us * 1e-6) / 1e9)
+        print("apply n=%-10d %10.2f us/launch %10.1f GB/s" % (n, us, curve[n][1]), file=sys.stderr)
+    n0 = 10 ** 7
+    us, gbs = curve[n0]
+    out = {
+        "metric": "per-element kernel bandwidth at 1e7 floats per launch (y = a*x + b, 8 B/element)",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "per-element mul+add, 1e7 floats per launch, back-to-back launches on one stream",
+                   "curve_GBps": {str(k): round(v[1], 1) for k, v in curve.items()},
+                   "curve_us_per_launch": {str(k): round(v[0], 2) for k, v in curve.items()}},
+        "roofline": {"bound": "hbm", "kernel": "apply_mul_add_vec_kernel", "achieved": round(gbs, 1),
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        x = np.random.default_rng(1).standard_normal(n0).astype(np.float32)
+        t0 = time.perf_counter()
+        k = 0
+        while time.perf_counter() - t0 < 5.0:
+            oracle.apply_mul_add(x, 1.5, 0.25)
+            k += 1
+        sec = (time.perf_counter() - t0) / k
+        out["cpu_baseline"] = {"value": round(8.0 * n0 / sec / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "the numpy oracle on 1e7 floats, %d repetitions" % k}
     print(json.dumps(out))
     return 0
 

@@ -130,6 +130,15 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy,
                       float *dw, float *dbias, float scale, int accumulate,
                       void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
 
+/* Per-element operation of the experiment of Sec. 3.3 (bandwidth of per-element
+ * kernels against the number of floats per launch; the paper does not name the
+ * operation): y[i] = fl(fl(a * x[i]) + b) for i < n, the two operations rounded to
+ * fp32 separately (no fused multiply-add).  x and y are device pointers to n floats
+ * (4-byte aligned; 16-byte alignment of both selects the vector path); y may equal
+ * x.  n == 0 is a no-op; n < 0 returns CONV2D_ERR_GEOMETRY.  Enqueues on hip_stream
+ * and returns. */
+int apply_mul_add(const float *x, float *y, int64_t n, float a, float b, void *hip_stream);
+
 /* Static, never-NULL description of a status code. */
 const char *conv2d_status_string(int status);
 

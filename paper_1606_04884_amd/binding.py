@@ -17,7 +17,8 @@ ALGO_AUTO, ALGO_IGEMM, ALGO_WINOGRAD = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd",
-           "conv2d_fwd_1x1_group", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version")
+           "conv2d_fwd_1x1_group", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version",
+           "apply_mul_add")
 
 
 class conv2d_desc(C.Structure):
@@ -61,6 +62,8 @@ def load() -> C.CDLL:
     lib.conv2d_bwd_weight.argtypes = [dp, vp, vp, vp, vp, C.c_float, C.c_int, vp, C.c_size_t,
                                       C.c_int, vp]
     lib.conv2d_bwd_weight.restype = C.c_int
+    lib.apply_mul_add.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_float, vp]
+    lib.apply_mul_add.restype = C.c_int
     lib.conv2d_status_string.argtypes = [C.c_int]
     lib.conv2d_status_string.restype = C.c_char_p
     lib.conv2d_version.argtypes = []
@@ -204,3 +207,13 @@ def conv2d_bwd_weight(d, x, dy, dw, dbias=None, scale: float = 1.0, accumulate: 
                                   1 if accumulate else 0, wptr, wbytes, int(algo), _stream(stream))
     if rc:
         raise Conv2dError(rc, "conv2d_bwd_weight")
+
+
+def apply_mul_add(x, y, a: float, b: float, stream=None) -> None:
+    """y = fl(fl(a*x) + b) per element; x, y device float32 tensors of equal size."""
+    n = x.numel()
+    if y.numel() != n:
+        raise ValueError("x and y differ in size")
+    rc = load().apply_mul_add(_ptr(x, None, "x"), _ptr(y, None, "y"), n, float(a), float(b), _stream(stream))
+    if rc:
+        raise Conv2dError(rc, "apply_mul_add")

@@ -696,6 +696,14 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     return CONV2D_OK;
 }
 
+int apply_mul_add(const float *x, float *y, int64_t n, float a, float b, void *hip_stream)
+{
+    if (n < 0) return CONV2D_ERR_GEOMETRY;
+    if (n == 0) return CONV2D_OK;
+    if (!x || !y) return CONV2D_ERR_NULL;
+    return launch_status(launch_apply_mul_add(x, y, n, a, b, (hipStream_t)hip_stream));
+}
+
 const char *conv2d_status_string(int status)
 {
     switch (status) {

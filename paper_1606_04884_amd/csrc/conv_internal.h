@@ -214,4 +214,7 @@ hipError_t launch_bwd_data_smallc(const SmallCArgs &a, hipStream_t s);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Per-element operation y = fl(fl(a*x) + b) over n floats (see apply.hip).
+hipError_t launch_apply_mul_add(const float *x, float *y, int64_t n, float a, float b, hipStream_t s);
+
 }  // namespace mi355conv

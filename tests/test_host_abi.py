@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "mi355conv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(conv2d_[a-z_0-9]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:conv2d|apply)_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -117,3 +117,10 @@ def test_grouped_1x1_argument_checks():
     # not a 1x1 stride-1 unpadded layer
     d3 = B.make_desc((2, 8, 6, 6, 12, 3, 3, 1, 1, 1, 1))
     assert lib.conv2d_fwd_1x1_group(C.byref(d3), 1, 2, K, one, None, one, 1, 1 << 20, None) == -3
+
+
+def test_apply_argument_checks():
+    lib = B.load()
+    assert lib.apply_mul_add(1, 1, -1, 1.0, 0.0, None) == -2
+    assert lib.apply_mul_add(None, None, 0, 1.0, 0.0, None) == 0
+    assert lib.apply_mul_add(None, 1, 8, 1.0, 0.0, None) == -1
