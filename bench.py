@@ -64,7 +64,7 @@ def main() -> int:
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by data parallelism over the batch, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by data parallelism over the batch)", file=sys.stderr)
         return 2
 
     import torch

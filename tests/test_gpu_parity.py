@@ -23,7 +23,7 @@ def G(N, C, H, W, K, R, S, s, p):
 # tails: filters not a multiple of 32/64/128, depth not a multiple of 16, pixel
 # counts not a multiple of 128/256, odd maps, every stride/pad of the configs.
 SHAPES = [
-    G(2, 3, 16, 16, 8, 3, 3, 1, 1),          # BASELINE config 1
+    G(2, 3, 16, 16, 8, 3, 3, 1, 1),          # the single-layer benchmark configuration
     G(3, 17, 19, 23, 40, 3, 3, 1, 1),
     G(2, 64, 14, 14, 96, 3, 3, 1, 1),
     G(2, 3, 67, 67, 64, 11, 11, 4, 2),       # AlexNet conv1 geometry, small map
@@ -61,7 +61,7 @@ def test_layer_parity(geom):
 
 
 def test_config1_distribution():
-    """BASELINE config 1 with its own value distributions (U(-1,1), dy ~ N(0,1))."""
+    """The single-layer benchmark configuration with its own value distributions (U(-1,1), dy ~ N(0,1))."""
     L = synth.config_layers(0)[0]
     geom = L.desc()
     t = synth.layer_tensors(0, 0, L, oracle.output_dims(geom))
