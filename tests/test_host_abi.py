@@ -124,3 +124,23 @@ def test_apply_argument_checks():
     assert lib.apply_mul_add(1, 1, -1, 1.0, 0.0, None) == -2
     assert lib.apply_mul_add(None, None, 0, 1.0, 0.0, None) == 0
     assert lib.apply_mul_add(None, 1, 8, 1.0, 0.0, None) == -1
+
+
+def test_algo_choice_rules():
+    """AUTO policy as the header states it: Winograd for 3x3 stride-1 layers with enough
+    reduction channels whose gathered tensor fits 32-bit byte offsets, else implicit GEMM."""
+    pick = B.conv2d_pick_algo
+    vgg = (64, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1)
+    assert pick(vgg, B.OP_FWD) == B.ALGO_WINOGRAD
+    assert pick(vgg, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
+    assert pick(vgg, B.OP_BWD_WEIGHT) == B.ALGO_WINOGRAD
+    first = (64, 3, 224, 224, 64, 3, 3, 1, 1, 1, 1)              # 3 input channels
+    assert pick(first, B.OP_FWD) == B.ALGO_IGEMM
+    assert pick(first, B.OP_BWD_DATA) == B.ALGO_IGEMM
+    assert pick(first, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+    assert pick((128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2), B.OP_FWD) == B.ALGO_IGEMM      # 5x5
+    assert pick((8, 64, 56, 56, 64, 3, 3, 2, 2, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # stride 2
+    big = (256, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1)             # x and y are 3.3 GB each
+    for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+        assert pick(big, op) == B.ALGO_IGEMM
+        assert B.conv2d_workspace_bytes(big, op, B.ALGO_WINOGRAD) == 0
