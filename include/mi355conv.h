@@ -55,7 +55,9 @@ typedef struct {
 typedef enum {
     CONV2D_ALGO_AUTO = 0,        /* library picks (see conv2d_pick_algo)          */
     CONV2D_ALGO_IGEMM = 1,       /* implicit GEMM on fp32 MFMA, any geometry      */
-    CONV2D_ALGO_WINOGRAD = 2     /* F(2x2,3x3): R=S=3, stride 1 only              */
+    CONV2D_ALGO_WINOGRAD = 2     /* F(2x2,3x3), stride 1: 3x3 filters; forward and
+                                  * backward-data also filters up to 6x6, as sums of
+                                  * 3x3 sub-filters of shifted inputs              */
 } conv2d_algo;
 
 typedef enum {

@@ -215,24 +215,28 @@ WgradPlan plan_wgrad(const Geom &g)
 
 // ---- Winograd F(2x2,3x3) ---------------------------------------------------
 struct WinoPlan {
-    int Cin, Kout, Cpad, Kpad, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, tiles_t, tiles_k, mode;
+    int Cin, Kout, Cpad, Kpad, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, tiles_t, tiles_k, mode, nsub;
     int grid;                   // persistent workgroups
     size_t u_bytes, total_bytes;
 };
 
-// The fused kernel handles 3x3 stride-1 layers whose reduction channels are a
-// multiple of its 8-channel chunk and whose gathered tensor fits 32-bit byte
-// offsets.  Backward-data is the forward kernel on dy with pad' = 2 - pad.
+// The fused kernel handles stride-1 layers with 3x3 filters, and for forward /
+// backward-data also filters up to 6x6 as a sum of 3x3 sub-filters of shifted
+// inputs, whose reduction channels are a multiple of its 8-channel chunk and whose
+// gathered tensor fits 32-bit byte offsets.  Backward-data is the forward kernel on
+// dy with the rotated filter and pad' = R - 1 - pad.
 bool wino_applicable(const Geom &g, conv2d_op op)
 {
-    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1) return false;
-    if (g.ph > 2 || g.pw > 2) return false;
+    if (g.sh != 1 || g.sw != 1) return false;
     if (op == CONV2D_BWD_WEIGHT) {
+        if (g.R != 3 || g.S != 3 || g.ph > 2 || g.pw > 2) return false;
         // 64x64 output tiles handled as two halves of 32: C and K multiples of 32
         if (g.C % 32 != 0 || g.K % 32 != 0) return false;
         return (int64_t)g.N * g.C * g.H * g.W * 4 < (int64_t(1) << 31) &&
                (int64_t)g.N * g.K * g.P * g.Q * 4 < (int64_t(1) << 31);
     }
+    if (g.R < 3 || g.S < 3 || g.R > 6 || g.S > 6) return false;
+    if (g.ph > g.R - 1 || g.pw > g.S - 1) return false;
     const int cin = op == CONV2D_FWD ? g.C : g.K;
     if (cin % wino_chan_chunk() != 0) return false;
     const int64_t in_elems = op == CONV2D_FWD ? (int64_t)g.N * g.C * g.H * g.W
@@ -250,14 +254,15 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
     p.Win = fwd ? g.W : g.Q;
     p.Hout = fwd ? g.P : g.H;
     p.Wout = fwd ? g.Q : g.W;
-    p.pad_h = fwd ? g.ph : 2 - g.ph;
-    p.pad_w = fwd ? g.pw : 2 - g.pw;
-    p.Cpad = p.Cin;
+    p.pad_h = fwd ? g.ph : g.R - 1 - g.ph;
+    p.pad_w = fwd ? g.pw : g.S - 1 - g.pw;
+    p.nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);     // 3x3 sub-filters of the filter
+    p.Cpad = p.nsub * p.Cin;
     p.Kpad = round_up(p.Kout, wino_filter_tile());
     p.TH = ceil_div(p.Hout, 2);
     p.TW = ceil_div(p.Wout, 2);
     // pad_w 1, even width and an even number of tiles per row: tile-pair kernel
-    p.mode = (p.pad_w == 1 && p.Win % 2 == 0 && p.TW % 2 == 0) ? 1 : 0;
+    p.mode = (p.nsub == 1 && p.pad_w == 1 && p.Win % 2 == 0 && p.TW % 2 == 0) ? 1 : 0;
     p.T = g.N * p.TH * p.TW;
     p.tiles_t = ceil_div(p.T, wino_tile_block());
     p.tiles_k = p.Kpad / wino_filter_tile();
@@ -325,7 +330,11 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         // a direct kernel takes it when its alignment conditions hold, else the GEMM
         if (op == CONV2D_BWD_DATA && g.C <= 4) return CONV2D_ALGO_IGEMM;
         const int cin = op == CONV2D_FWD ? g.C : g.K;
-        return (wino_ok && cin >= 32) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
+        // larger filters: 16 multiplications per 2x2 outputs and 3x3 sub-filter against
+        // R*S*4 direct ones; the sub-filters of 4x4 / 4x5 filters are mostly padding
+        const int nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);
+        const bool pays = 4 * nsub * 14 <= g.R * g.S * 10;
+        return (wino_ok && cin >= 32 && pays) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
     }
     case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;
     case CONV2D_ALGO_WINOGRAD: return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ERR_ALGO;
@@ -357,7 +366,7 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
     const WinoPlan p = plan_wino(g, op);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
     float *U = (float *)ws;
-    int rc = launch_status(launch_wino_filter(w, U, g.K, g.C, p.Cin, p.Kout, p.Cpad, p.Kpad,
+    int rc = launch_status(launch_wino_filter(w, U, g.K, g.C, g.R, g.S, p.Cin, p.Kout, p.Cpad, p.Kpad,
                                               op == CONV2D_FWD ? 0 : 1, p.mode != 0, s));
     if (rc) return rc;
     WinoArgs a = {};
@@ -366,7 +375,15 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
     a.Kout = p.Kout; a.Kpad = p.Kpad; a.Hout = p.Hout; a.Wout = p.Wout;
     a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
     a.tiles_t = p.tiles_t; a.tiles_k = p.tiles_k;
-    a.nchunks = p.Cin / wino_chan_chunk();
+    a.nchunks = p.Cpad / wino_chan_chunk();
+    a.nsub = p.nsub;
+    {
+        const int nsw = ceil_div(g.S, 3);
+        for (int q = 0; q < 4; ++q) {
+            a.sub_dh[q] = q < p.nsub ? 3 * (q / nsw) : 0;
+            a.sub_dw[q] = q < p.nsub ? 3 * (q % nsw) : 0;
+        }
+    }
     a.units_total = p.tiles_t * p.tiles_k * a.nchunks;
     a.partial = (float *)((char *)ws + p.u_bytes);
     a.in_bytes = (int32_t)((int64_t)g.N * p.Cin * p.Hin * p.Win * 4);

@@ -169,14 +169,20 @@ struct WinoArgs {
     int32_t vec2;            // output rows can be stored as aligned float2
     int32_t in_bytes, u_bytes;   // sizes of `in` and `U` (both below 2^31)
     int32_t nchunks, units_total; // 8-channel chunks per tile; tiles_t*tiles_k*nchunks
+    // filters larger than 3x3 as a sum of 3x3 sub-filters of shifted inputs: the
+    // reduction runs over nsub groups of Cin channels (nchunks = nsub * Cin / 8); group q
+    // reads the input shifted by (sub_dh[q], sub_dw[q]).  nsub = 1, shifts 0: plain 3x3
+    int32_t nsub, sub_dh[4], sub_dw[4];
     float *partial;              // [grid][2] slots of 64*64*4 floats for tiles cut by a range boundary
 };
 
 int wino_filter_tile();
 int wino_tile_block();
 int wino_chan_chunk();
-hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
-                              int Kpad, int mode, int paired, hipStream_t s);
+// R x S: the full filter; its 3x3 sub-filter (a, b) holds taps (3a.., 3b..), zero where
+// the filter ends; Cpad = nsub * Cin virtual channels, group q = a * ceil(S/3) + b
+hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int R, int S, int Cin, int Kout,
+                              int Cpad, int Kpad, int mode, int paired, hipStream_t s);
 int wino_partial_slot_floats();
 // G persistent workgroups (G <= tiles_t*tiles_k)
 hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s);

@@ -33,37 +33,39 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // --------------------------------------------------------- filter transform
-// U[pos][c][k] (k contiguous, zero padded to Cpad x Kpad).
+// U[pos][c'][k] (k contiguous, zero padded to Cpad x Kpad).  A filter larger than
+// 3x3 is the sum of 3x3 sub-filters applied to shifted inputs: virtual channel
+// c' = q * Cin + c carries sub-filter q = (a, b) of channel c, taps (3a + r, 3b + s),
+// zero where the R x S filter ends (R = S = 3: one sub-filter, the filter itself).
 // mode 0: forward, filters g = w[k][c].  mode 1: backward-data, the layer that
-// maps dy to dx has filters g'[c][k][r][s] = w[k][c][2-r][2-s]; its "k" is c.
+// maps dy to dx has filters g'[c][k][r][s] = w[k][c][R-1-r][S-1-s]; its "k" is c.
 __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w,
                                                           float *__restrict__ U, int K, int C,
-                                                          int Cin, int Kout, int Cpad, int Kpad,
-                                                          int mode)
+                                                          int R, int S, int Cin, int Kout,
+                                                          int Cpad, int Kpad, int mode)
 {
     const int64_t total = (int64_t)Cpad * Kpad;
+    const int nsw = (S + 2) / 3;
+    const int RS = R * S;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
-        const int ci = (int)(i / Kpad), ko = (int)(i - (int64_t)ci * Kpad);
+        const int cv = (int)(i / Kpad), ko = (int)(i - (int64_t)cv * Kpad);
+        const int q = cv / Cin, ci = cv - q * Cin;
+        const int r0 = 3 * (q / nsw), s0 = 3 * (q - (q / nsw) * nsw);
         float g[3][3];
 #pragma unroll
         for (int r = 0; r < 3; ++r)
 #pragma unroll
             for (int s = 0; s < 3; ++s) g[r][s] = 0.f;
-        if (ci < Cin && ko < Kout) {
-            if (mode == 0) {
-                const float *p = w + ((int64_t)ko * C + ci) * 9;
+        if (ko < Kout) {
+            const float *p = mode == 0 ? w + ((int64_t)ko * C + ci) * RS : w + ((int64_t)ci * C + ko) * RS;
 #pragma unroll
-                for (int r = 0; r < 3; ++r)
+            for (int r = 0; r < 3; ++r)
 #pragma unroll
-                    for (int s = 0; s < 3; ++s) g[r][s] = p[r * 3 + s];
-            } else {
-                const float *p = w + ((int64_t)ci * C + ko) * 9;
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-#pragma unroll
-                    for (int s = 0; s < 3; ++s) g[r][s] = p[(2 - r) * 3 + (2 - s)];
-            }
+                for (int s = 0; s < 3; ++s) {
+                    const int rr = r0 + r, ss = s0 + s;
+                    if (rr < R && ss < S) g[r][s] = mode == 0 ? p[rr * S + ss] : p[(R - 1 - rr) * S + (S - 1 - ss)];
+                }
         }
         float t[4][3];
 #pragma unroll
@@ -147,10 +149,10 @@ __global__ __launch_bounds__(256) void wino_filter_paired_kernel(const float *__
     }
 }
 
-hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, int Kout, int Cpad,
-                              int Kpad, int mode, int paired, hipStream_t s)
+hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int R, int S, int Cin, int Kout,
+                              int Cpad, int Kpad, int mode, int paired, hipStream_t s)
 {
-    if (paired) {
+    if (paired) {       // 3x3 only
         int64_t blocks = ((int64_t)Cpad * Kpad / 4 + 255) / 256;
         if (blocks > 4096) blocks = 4096;
         hipLaunchKernelGGL(wino_filter_paired_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, C,
@@ -159,8 +161,8 @@ hipError_t launch_wino_filter(const float *w, float *U, int K, int C, int Cin, i
     }
     int64_t blocks = ((int64_t)Cpad * Kpad + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, K, C, Cin,
-                       Kout, Cpad, Kpad, mode);
+    hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, U, K, C, R, S,
+                       Cin, Kout, Cpad, Kpad, mode);
     return hipGetLastError();
 }
 
@@ -336,13 +338,17 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     const __amdgpu_buffer_rsrc_t ursrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.U, 0, a.u_bytes, 0x00020000);
     uint32_t eoff[16];      // byte offset of patch element 4*i+j inside channel 0 (or 2^31)
-    auto set_tile_block = [&](int tt) {
+    // (tt: tile block; q: sub-filter group, whose input is shifted by (sub_dh, sub_dw))
+    const int nch_c = nchunks / a.nsub;               // chunks per sub-filter group
+    auto set_tile_block = [&](int tt, int q) {
         const int tile = tt * TB + lane;
         const bool tv = tile < a.T;
         const int tl = tv ? tile : 0;
         const int n = tl / (a.TH * a.TW), rem = tl - n * (a.TH * a.TW);
         const int th = rem / a.TW, tw = rem - th * a.TW;
-        const int ih0 = 2 * th - a.pad_h, iw0 = 2 * tw - a.pad_w;
+        const int dh = q == 0 ? a.sub_dh[0] : q == 1 ? a.sub_dh[1] : q == 2 ? a.sub_dh[2] : a.sub_dh[3];
+        const int dw = q == 0 ? a.sub_dw[0] : q == 1 ? a.sub_dw[1] : q == 2 ? a.sub_dw[2] : a.sub_dw[3];
+        const int ih0 = 2 * th - a.pad_h + dh, iw0 = 2 * tw - a.pad_w + dw;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -374,7 +380,7 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     // load number l of an item.  VEC: row l/3: column 0, columns 1-2, column 3;
     // otherwise the 16 elements in column-major order (the order of consumption)
     auto load_x = [&](int it, int l, int chunk) {
-        const int so = chunk * x_chunk + (it ? xs1 : xs0);
+        const int so = (chunk % nch_c) * x_chunk + (it ? xs1 : xs0);
         if (VEC) {
             const int i = l / 3, part = l - 3 * i;
             if (part == 1) {
@@ -455,7 +461,10 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
     int u_unit = ub, x_unit = ub;
 
     // ---- prologue: unit 0 into LDS buffer 0, patch loads of unit 1 ----
-    set_tile_block(x_tile % a.tiles_t);
+    // (the patch offsets depend on the tile block and on the sub-filter group)
+    auto x_key = [&]() { return x_tile * a.nsub + x_chunk_i / nch_c; };
+    auto set_x_block = [&]() { set_tile_block(x_tile % a.tiles_t, x_chunk_i / nch_c); };
+    set_x_block();
 #pragma unroll
     for (int it = 0; it < 2; ++it)
 #pragma unroll
@@ -472,9 +481,9 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 #pragma unroll
     for (int i = 0; i < 8; ++i) store_u(0, i);
     {
-        const int before = x_tile;
+        const int before = x_key();
         advance(x_tile, x_chunk_i, x_unit);
-        if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
+        if (x_key() != before) set_x_block();
 #pragma unroll
         for (int it = 0; it < 2; ++it)
 #pragma unroll
@@ -504,11 +513,11 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
             const int buf = i & 1;
             const int ukt = u_tile / a.tiles_t;
             {
-                const int before = x_tile;
+                const int before = x_key();
                 advance(x_tile, x_chunk_i, x_unit);
                 // the patch registers still hold unit i+1 (transformed in slots 0..15);
                 // the offsets are only used from slot 16 on
-                if (x_tile != before) set_tile_block(x_tile % a.tiles_t);
+                if (x_key() != before) set_x_block();
             }
     #pragma unroll
             for (int pair = 0; pair < 8; ++pair) {
@@ -979,7 +988,7 @@ hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s)
 {
     hipError_t e;
     if (a.mode == 1) e = launch_wino_pair(a, G, s);
-    else if (a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
+    else if (a.nsub > 1 || a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
     else e = launch_wino_variant<true>(a, G, s);
     if (e != hipSuccess || G < 2) return e;
     hipLaunchKernelGGL(wino_fixup_kernel, dim3((unsigned)(G - 1), 4), dim3(256), 0, s, a, G);

@@ -265,3 +265,29 @@ def test_grouped_1x1_forward(case):
         got = ys[i].cpu().numpy()
         assert np.isfinite(got).all()
         assert max_err_ratio(got, ref) <= TOL_IGEMM, "group %d" % i
+
+
+WINO_LARGE_FILTER_SHAPES = [
+    G(2, 16, 12, 12, 24, 5, 5, 1, 2),
+    (3, 8, 9, 11, 16, 5, 5, 1, 1, 0, 0),
+    (2, 24, 13, 10, 40, 5, 5, 1, 1, 4, 1),
+    (2, 8, 9, 9, 8, 4, 4, 1, 1, 1, 2),
+    (2, 8, 10, 12, 16, 6, 6, 1, 1, 3, 2),
+    (2, 16, 8, 9, 8, 3, 5, 1, 1, 1, 2),
+    (2, 16, 9, 8, 8, 5, 3, 1, 1, 0, 1),
+    G(4, 64, 27, 27, 192, 5, 5, 1, 2),          # AlexNet conv2 at a small batch
+]
+
+
+@pytest.mark.parametrize("geom", WINO_LARGE_FILTER_SHAPES,
+                         ids=[("x".join(map(str, g))) for g in WINO_LARGE_FILTER_SHAPES])
+def test_winograd_large_filters(geom):
+    """Filters up to 6x6 through the Winograd path (sums of 3x3 sub-filters of shifted
+    inputs): forward and backward-data against the oracle."""
+    from gpu_util import TOL_WINOGRAD
+    x, w, b, dy = random_layer(geom, 8000 + sum(geom))
+    print("geom", geom, flush=True)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, passes=("fwd", "bwd_data"))
+    assert np.isfinite(got["y"]).all() and np.isfinite(got["dx"]).all()
+    assert max_err_ratio(got["y"], oracle.fwd(geom, x, w, b)) <= TOL_WINOGRAD
+    assert max_err_ratio(got["dx"], oracle.bwd_data(geom, dy, w)) <= TOL_WINOGRAD

@@ -138,7 +138,12 @@ def test_algo_choice_rules():
     assert pick(first, B.OP_FWD) == B.ALGO_IGEMM
     assert pick(first, B.OP_BWD_DATA) == B.ALGO_IGEMM
     assert pick(first, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
-    assert pick((128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2), B.OP_FWD) == B.ALGO_IGEMM      # 5x5
+    five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5: four 3x3 sub-filters
+    assert pick(five, B.OP_FWD) == B.ALGO_WINOGRAD
+    assert pick(five, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
+    assert pick(five, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+    assert pick((8, 64, 20, 20, 64, 4, 4, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # 4x4: no saving
+    assert pick((8, 64, 20, 20, 64, 7, 7, 1, 1, 3, 3), B.OP_FWD) == B.ALGO_IGEMM          # above 6x6
     assert pick((8, 64, 56, 56, 64, 3, 3, 2, 2, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # stride 2
     big = (256, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1)             # x and y are 3.3 GB each
     for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):

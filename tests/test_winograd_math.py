@@ -7,6 +7,9 @@ from fractions import Fraction as F
 
 import numpy as np
 
+import oracle
+from paper_1606_04884_amd import synth
+
 BT = [[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]]
 G = [[1, 0, 0], [F(1, 2), F(1, 2), F(1, 2)], [F(1, 2), F(-1, 2), F(1, 2)], [0, 0, 1]]
 AT = [[1, 1, 1, 0], [0, 1, -1, -1]]
@@ -95,3 +98,29 @@ def test_weight_gradient_identity_exact():
             for s in range(3):
                 direct = sum(dy[p][q] * d[p + r][q + s] for p in range(2) for q in range(2))
                 assert dg[r][s] == direct
+
+
+def test_large_filter_is_a_sum_of_shifted_3x3_filters():
+    """A stride-1 R x S correlation (R, S <= 6) equals the sum over 3x3 sub-filters
+    (taps 3a.., 3b.., zero where the filter ends) of 3x3 correlations of the input
+    shifted by (3a, 3b): the decomposition the Winograd path uses for 5x5 layers.
+    Exact on dyadic data; the sub-correlations are evaluated by the oracle with the
+    shift expressed through asymmetric zero padding of the input."""
+    for (R, S, ph, pw, H, W) in [(5, 5, 2, 2, 9, 8), (5, 5, 0, 0, 8, 9), (4, 6, 1, 3, 7, 9), (3, 5, 1, 2, 6, 7)]:
+        N, C, K = 2, 3, 4
+        x = synth.dyadic((N, C, H, W), 31 + R)
+        w = synth.dyadic((K, C, R, S), 32 + S)
+        full = oracle.fwd((N, C, H, W, K, R, S, 1, 1, ph, pw), x, w, None)
+        P, Q = full.shape[2:]
+        acc = np.zeros_like(full)
+        # zero-extend the input once, by the padding plus room for the sub-filter overhang
+        xe = np.zeros((N, C, H + 2 * ph + 3, W + 2 * pw + 3), dtype=np.float32)
+        xe[:, :, ph:ph + H, pw:pw + W] = x
+        for a in range((R + 2) // 3):
+            for b in range((S + 2) // 3):
+                g = np.zeros((K, C, 3, 3), dtype=np.float32)
+                rr, ss = min(3, R - 3 * a), min(3, S - 3 * b)
+                g[:, :, :rr, :ss] = w[:, :, 3 * a:3 * a + rr, 3 * b:3 * b + ss]
+                xs = np.ascontiguousarray(xe[:, :, 3 * a:3 * a + P + 2, 3 * b:3 * b + Q + 2])
+                acc += oracle.fwd((N, C, P + 2, Q + 2, K, 3, 3, 1, 1, 0, 0), xs, g, None)
+        assert np.array_equal(acc, full), (R, S)
