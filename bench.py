@@ -44,7 +44,8 @@ def executed_flops(L, P, Q, op, algo):
     if algo != 2:
         return layer_flops(L, P, Q)
     th, tw = (-(-L.H // 2), -(-L.W // 2)) if op == "bwd_data" else (-(-P // 2), -(-Q // 2))
-    return 32.0 * L.N * th * tw * L.K * L.C
+    nsub = -(-L.R // 3) * -(-L.S // 3)        # 3x3 sub-filters of a larger filter
+    return 32.0 * L.N * th * tw * L.K * L.C * nsub
 
 
 def main() -> int:

@@ -229,7 +229,7 @@ bool wino_applicable(const Geom &g, conv2d_op op)
 {
     if (g.sh != 1 || g.sw != 1) return false;
     if (op == CONV2D_BWD_WEIGHT) {
-        if (g.R != 3 || g.S != 3 || g.ph > 2 || g.pw > 2) return false;
+        if (g.R < 3 || g.S < 3 || g.R > 6 || g.S > 6 || g.ph > g.R - 1 || g.pw > g.S - 1) return false;
         // 64x64 output tiles handled as two halves of 32: C and K multiples of 32
         if (g.C % 32 != 0 || g.K % 32 != 0) return false;
         return (int64_t)g.N * g.C * g.H * g.W * 4 < (int64_t(1) << 31) &&
@@ -274,7 +274,7 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
 }
 
 struct WinoWgradPlan {
-    int TH, TW, T, tiles_k, tiles_c, splits, tiles_per_split, bias_splits, mode;
+    int TH, TW, T, tiles_k, tiles_c, splits, tiles_per_split, bias_splits, mode, nsub, tiles_c_sub;
     size_t part_bytes, bias_bytes, total_bytes;
 };
 
@@ -286,13 +286,15 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
     // pad_w 1 and an even width: tile pairs fetched with vector loads, the tile grid
     // taken with an even row width (one phantom tile per row when the true one is odd)
     p.mode = 0;
-    if (g.pw == 1 && g.W % 2 == 0) {
+    p.nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);       // 3x3 sub-filters (per-element kernel only)
+    if (p.nsub == 1 && g.pw == 1 && g.W % 2 == 0) {
         p.mode = (p.TW & 1) ? 2 : 1;
         p.TW = round_up(p.TW, 2);
     }
     p.T = g.N * p.TH * p.TW;
     p.tiles_k = ceil_div(g.K, wino_wgrad_tile());
-    p.tiles_c = ceil_div(g.C, wino_wgrad_tile());
+    p.tiles_c_sub = ceil_div(g.C, wino_wgrad_tile());
+    p.tiles_c = p.nsub * p.tiles_c_sub;
     const int tiles = p.tiles_k * p.tiles_c;
     const int step = wino_wgrad_step();
     // one workgroup per compute unit is resident: fill 256 slots a whole number of times
@@ -300,20 +302,20 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
     int max_splits = ceil_div(p.T, 8 * step);       // at least 8 steps each
     if (max_splits > 2048) max_splits = 2048;
     if (max_splits < 1) max_splits = 1;
-    const double flops = 32.0 * (double)p.T * g.K * g.C;
+    const double flops = 32.0 * (double)p.T * g.K * g.C * p.nsub;
     int best = 1;
     double best_t = 1e300;
     for (int sp = 1; sp <= max_splits; ++sp) {
         const double blocks = (double)tiles * sp;
         const double rounds = (double)((int64_t)((blocks + slots - 1) / slots));
         const double eff = blocks / (rounds * slots);
-        const double t = flops / (0.6 * 155e12) / eff + 2.0 * sp * g.K * (double)g.C * 36.0 / 3.0e12 + 0.1e-6 * sp;
+        const double t = flops / (0.6 * 155e12) / eff + 2.0 * sp * g.K * (double)g.C * p.nsub * 36.0 / 3.0e12 + 0.1e-6 * sp;
         if (t < best_t) { best_t = t; best = sp; }
     }
     p.tiles_per_split = round_up(ceil_div(p.T, best), step);
     p.splits = ceil_div(p.T, p.tiles_per_split);
     p.bias_splits = p.splits;       // the main kernel also sums dy: one partial per split
-    p.part_bytes = align_up((size_t)p.splits * g.K * g.C * 9 * sizeof(float), 256);
+    p.part_bytes = align_up((size_t)p.splits * g.K * g.C * p.nsub * 9 * sizeof(float), 256);
     p.bias_bytes = align_up((size_t)p.bias_splits * g.K * sizeof(float), 256);
     p.total_bytes = p.part_bytes + p.bias_bytes;
     return p;
@@ -325,7 +327,9 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
     switch (algo) {
     case CONV2D_ALGO_AUTO: {
         // Winograd pays once the 16 GEMMs are deep enough to amortise the transforms
-        if (op == CONV2D_BWD_WEIGHT) return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
+        const int nsub_f = ceil_div(g.R, 3) * ceil_div(g.S, 3);
+        const bool pays_f = 4 * nsub_f * 14 <= g.R * g.S * 10;
+        if (op == CONV2D_BWD_WEIGHT) return (wino_ok && pays_f) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
         // backward-data into <= 4 channels: Winograd/GEMM rows would be almost empty;
         // a direct kernel takes it when its alignment conditions hold, else the GEMM
         if (op == CONV2D_BWD_DATA && g.C <= 4) return CONV2D_ALGO_IGEMM;
@@ -676,10 +680,22 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
         a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
         a.div_THW = make_fastdiv((uint32_t)(p.TH * p.TW));
         a.div_TW = make_fastdiv((uint32_t)p.TW);
+        a.nsub = p.nsub; a.tiles_c_sub = p.tiles_c_sub;
+        {
+            const int nsw = ceil_div(g.S, 3);
+            for (int q = 0; q < 4; ++q) {
+                a.sub_dh[q] = q < p.nsub ? 3 * (q / nsw) : 0;
+                a.sub_dw[q] = q < p.nsub ? 3 * (q % nsw) : 0;
+            }
+        }
         rc = launch_status(launch_wino_wgrad(a, s));
         if (rc) return rc;
-        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale,
-                                               accumulate, s));
+        if (p.nsub > 1)
+            rc = launch_status(launch_split_reduce_sub(part, dw, g.K, g.C, g.R, g.S, p.splits, scale,
+                                                       accumulate, s));
+        else
+            rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale,
+                                                   accumulate, s));
         if (rc) return rc;
         if (dbias)
             rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, accumulate, s));

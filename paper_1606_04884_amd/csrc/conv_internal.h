@@ -148,6 +148,10 @@ hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s);
 hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
                                float scale, int accumulate, hipStream_t s);
 // db[k] = scale * sum_i part[i][k] (+ db[k])
+// dw[k][c][r][s] = scale * sum over splits of part[split][k][q*C + c][(r%3)*3 + s%3], q the
+// sub-filter holding tap (r, s) (see WinoWgradArgs)
+hipError_t launch_split_reduce_sub(const float *part, float *dw, int K, int C, int R, int S, int splits,
+                                   float scale, int accumulate, hipStream_t s);
 hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
                              int accumulate, hipStream_t s);
 // ---------------------------------------------------------------------------
@@ -202,6 +206,11 @@ struct WinoWgradArgs {
     int32_t tiles_k, tiles_c, splits;
     int32_t x_bytes, dy_bytes; // both below 2^31
     FastDiv div_THW, div_TW;
+    // filters larger than 3x3 (per-element kernel only): tiles_c = nsub * tiles_c_sub
+    // channel tiles; those of group q compute the 3x3 sub-filter gradient q from the
+    // input shifted by (sub_dh[q], sub_dw[q]) and write it as channels q*C + c of part
+    // [split][K][nsub*C][9].  nsub = 1: plain 3x3
+    int32_t nsub, tiles_c_sub, sub_dh[4], sub_dw[4];
 };
 
 int wino_wgrad_tile();

@@ -348,6 +348,48 @@ hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int
     return hipGetLastError();
 }
 
+// The same reduction for a filter gradient computed as 3x3 sub-filter gradients
+// (Winograd backward-weight of filters larger than 3x3): element (k, c, r, s) of dw
+// comes from part[split][k][q*C + c][(r % 3) * 3 + s % 3], q = (r / 3) * ceil(S / 3) + s / 3.
+__global__ __launch_bounds__(256) void split_reduce_sub_kernel(const float *__restrict__ part,
+                                                               float *__restrict__ dw, int K, int C,
+                                                               int R, int S, int splits, float scale,
+                                                               int accumulate)
+{
+    const int nsw = (S + 2) / 3, nsub = ((R + 2) / 3) * nsw;
+    const int64_t count = (int64_t)K * C * R * S;
+    const int64_t src_count = (int64_t)K * nsub * C * 9;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int ss = (int)(i % S), r = (int)((i / S) % R);
+        const int c = (int)((i / ((int64_t)R * S)) % C), k = (int)(i / ((int64_t)R * S * C));
+        const int q = (r / 3) * nsw + ss / 3;
+        const float *p = part + ((int64_t)k * nsub * C + (int64_t)q * C + c) * 9 + (r % 3) * 3 + ss % 3;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int j = 0;
+        for (; j + 8 <= splits; j += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[u] += p[(int64_t)(j + u) * src_count];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (j + u < splits) acc[u] += p[(int64_t)(j + u) * src_count];
+        float t = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+        t *= scale;
+        dw[i] = accumulate ? dw[i] + t : t;
+    }
+}
+
+hipError_t launch_split_reduce_sub(const float *part, float *dw, int K, int C, int R, int S, int splits,
+                                   float scale, int accumulate, hipStream_t s)
+{
+    int64_t blocks = ((int64_t)K * C * R * S + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(split_reduce_sub_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, dw, K, C, R,
+                       S, splits, scale, accumulate);
+    return hipGetLastError();
+}
+
 // Bias gradient, final stage: db[k] = scale * sum of the per-split partial sums.
 // One wave per filter: lane l adds the partials l, l+64, ... in order, then the 64
 // lane sums are combined in a fixed butterfly order (deterministic).

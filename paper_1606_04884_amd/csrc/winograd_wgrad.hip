@@ -68,7 +68,11 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
     const int tile_id = logical % ntile;
     const int split = logical / ntile;
     const int kt = tile_id % a.tiles_k;
-    const int ct = tile_id / a.tiles_k;
+    const int ctv = tile_id / a.tiles_k;          // channel tile over nsub * C virtual channels
+    const int sq = ctv / a.tiles_c_sub;           // sub-filter group: input shifted by (dh, dw)
+    const int ct = ctv - sq * a.tiles_c_sub;
+    const int sub_dh = sq == 0 ? a.sub_dh[0] : sq == 1 ? a.sub_dh[1] : sq == 2 ? a.sub_dh[2] : a.sub_dh[3];
+    const int sub_dw = sq == 0 ? a.sub_dw[0] : sq == 1 ? a.sub_dw[1] : sq == 2 ? a.sub_dw[2] : a.sub_dw[3];
     const int t_begin = split * a.tiles_per_split;
     const int t_end = min(a.T, t_begin + a.tiles_per_split);
     const int nsteps = (t_end - t_begin + TS - 1) / TS;
@@ -100,7 +104,7 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
         const int rem = tl - n * (a.TH * a.TW);
         const int th = (int)fast_div((uint32_t)rem, a.div_TW);
         const int tw = rem - th * a.TW;
-        const int ih0 = 2 * th - a.pad_h, iw0 = 2 * tw - a.pad_w;
+        const int ih0 = 2 * th - a.pad_h + sub_dh, iw0 = 2 * tw - a.pad_w + sub_dw;
         const int xbase = ((n * a.C + c0) * a.H + ih0) * a.W + iw0;
         bool rok[4], cok[4];
 #pragma unroll
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
 
     // ---- bias gradient: every tile of the range went through bsum exactly once.
     // Only the workgroups of channel tile 0 write it: one partial per (split, k).
-    if (a.bias_part != nullptr && ct == 0) {
+    if (a.bias_part != nullptr && ctv == 0) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             float v = bsum[it];
@@ -272,7 +276,8 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
     // ---- epilogue: dg = G^T M G in registers, partial 3x3 gradients out ----
     const int c = ct * CB + wn0 + l32;
     if (c >= a.C) return;
-    float *out = a.part + (int64_t)split * a.K * a.C * 9;
+    const int Cv = a.nsub * a.C;                  // columns of a partial matrix
+    float *out = a.part + (int64_t)split * a.K * Cv * 9 + (int64_t)sq * a.C * 9;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int k = kt * KB + wm0 + 8 * (v >> 2) + 4 * lhi + (v & 3);
@@ -286,7 +291,7 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
             tt[1][j] = hd;
             tt[2][j] = hs + m3;
         }
-        float *o = out + ((int64_t)k * a.C + c) * 9;
+        float *o = out + ((int64_t)k * Cv + c) * 9;
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
             const float hs = 0.5f * (tt[r][1] + tt[r][2]), hd = 0.5f * (tt[r][1] - tt[r][2]);

@@ -276,6 +276,12 @@ WINO_LARGE_FILTER_SHAPES = [
     (2, 16, 8, 9, 8, 3, 5, 1, 1, 1, 2),
     (2, 16, 9, 8, 8, 5, 3, 1, 1, 0, 1),
     G(4, 64, 27, 27, 192, 5, 5, 1, 2),          # AlexNet conv2 at a small batch
+    # C and K multiples of 32: backward-weight too
+    G(2, 32, 12, 12, 64, 5, 5, 1, 2),
+    (3, 64, 9, 11, 32, 5, 5, 1, 1, 0, 0),
+    (2, 32, 10, 12, 32, 6, 6, 1, 1, 3, 2),
+    (2, 32, 8, 9, 32, 3, 5, 1, 1, 1, 2),
+    (2, 96, 13, 10, 32, 5, 4, 1, 1, 4, 1),
 ]
 
 
@@ -291,3 +297,14 @@ def test_winograd_large_filters(geom):
     assert np.isfinite(got["y"]).all() and np.isfinite(got["dx"]).all()
     assert max_err_ratio(got["y"], oracle.fwd(geom, x, w, b)) <= TOL_WINOGRAD
     assert max_err_ratio(got["dx"], oracle.bwd_data(geom, dy, w)) <= TOL_WINOGRAD
+    if geom[1] % 32 == 0 and geom[4] % 32 == 0:
+        got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, passes=("bwd_weight",))
+        dw, db = oracle.bwd_weight(geom, x, dy)
+        assert np.isfinite(got["dw"]).all()
+        assert max_err_ratio(got["dw"], dw) <= TOL_WINOGRAD
+        assert max_err_ratio(got["db"], db) <= TOL_IGEMM
+        # scale / accumulate through the sub-filter reduction
+        dw0 = synth.normal(dw.shape, 18, std=2.0)
+        got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, scale=-0.5, dw0=dw0.copy(),
+                        db0=np.zeros_like(db, dtype=np.float32), passes=("bwd_weight",))
+        assert max_err_ratio(got["dw"], -0.5 * dw + dw0) <= TOL_WINOGRAD

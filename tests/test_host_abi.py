@@ -141,7 +141,7 @@ def test_algo_choice_rules():
     five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5: four 3x3 sub-filters
     assert pick(five, B.OP_FWD) == B.ALGO_WINOGRAD
     assert pick(five, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
-    assert pick(five, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+    assert pick(five, B.OP_BWD_WEIGHT) == B.ALGO_WINOGRAD
     assert pick((8, 64, 20, 20, 64, 4, 4, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # 4x4: no saving
     assert pick((8, 64, 20, 20, 64, 7, 7, 1, 1, 3, 3), B.OP_FWD) == B.ALGO_IGEMM          # above 6x6
     assert pick((8, 64, 56, 56, 64, 3, 3, 2, 2, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # stride 2
