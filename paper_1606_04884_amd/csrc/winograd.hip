@@ -781,25 +781,44 @@ __device__ __forceinline__ void wino_pair_body(const WinoArgs &a, float *lds)
             __builtin_amdgcn_sched_barrier(0);
             if (run == 0) load_a(q1, ckt, cc); else load_a(q1, ukt, u_chunk_i);
             __builtin_amdgcn_sched_barrier(0);
+            // patch loads of unit i+2 (0-2 left dwords, 3-5 the 16-byte pieces, 6-8 right
+            // dwords), each as soon as the transform has consumed its registers and a few
+            // instructions away from the next load
             if (run == 0) {
-                // columns 0..5; the left dwords are free after column 0, the 16-byte
-                // pieces after column 4
-#pragma unroll
-                for (int j = 0; j < 6; ++j) {
-                    xform_col(j);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (j < 3) load_x(j, x_chunk_i);
-                    else if (j >= 4) load_x(j - 1, x_chunk_i);       // loads 3, 4
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else if (run < 3) {
-#pragma unroll
-                for (int q = 2 * (run - 1); q < 2 * run; ++q) {
-                    xform_row_store(q >> 1, q & 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_x(5 + q, x_chunk_i);                         // loads 5 .. 8
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                xform_col(0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(0, x_chunk_i);
+                __builtin_amdgcn_sched_barrier(0);
+                xform_col(1);
+                xform_col(2);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(1, x_chunk_i);
+                __builtin_amdgcn_sched_barrier(0);
+                xform_col(3);
+                xform_col(4);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(2, x_chunk_i);
+            } else if (run == 1) {
+                xform_col(5);
+                xform_row_store(0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(3, x_chunk_i);
+                __builtin_amdgcn_sched_barrier(0);
+                xform_row_store(0, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(4, x_chunk_i);
+            } else if (run == 2) {
+                xform_row_store(1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(5, x_chunk_i);
+                __builtin_amdgcn_sched_barrier(0);
+                xform_row_store(1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(6, x_chunk_i);
+            } else {
+                load_x(7, x_chunk_i);
+                __builtin_amdgcn_sched_barrier(0);
+                load_x(8, x_chunk_i);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
