@@ -164,9 +164,9 @@ def main() -> int:
         wino = recs[li]["algo"][op] == 2
         if op == "bwd_weight":
             return ("wino_wgrad (wino_wgrad_vec_kernel / wino_wgrad_kernel: Winograd bwd_weight calls)" if wino
-                    else "wgrad (wgrad_kernel: implicit-GEMM bwd_weight calls)")
+                    else "wgrad (wgrad_kernel / pw_wgrad_kernel: implicit-GEMM bwd_weight calls)")
         return ("wino_fwd_bwd (wino_pair_kernel / wino_fused_kernel: Winograd fwd + bwd_data calls)" if wino
-                else "gemmconv (gemmconv_kernel / bwd_data_smallc_kernel: implicit-GEMM and direct fwd + bwd_data calls)")
+                else "gemmconv (gemmconv_kernel / pw_stream_kernel / bwd_data_smallc_kernel: implicit-GEMM and direct fwd + bwd_data calls)")
 
     fam = {}
     op_ms = {"fwd": 0.0, "bwd_data": 0.0, "bwd_weight": 0.0}

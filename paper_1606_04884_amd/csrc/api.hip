@@ -353,6 +353,74 @@ bool pointwise_ok(const Geom &g, const float *in, int64_t in_elems)
            (g.H * g.W) % 4 == 0 && ((uintptr_t)in & 15) == 0 && in_elems * 4 < (int64_t(1) << 31);
 }
 
+// 1x1 stride-1 unpadded layer whose small operand (filters x channels) fits in LDS and
+// whose streamed tensor fits 32-bit byte offsets: the streaming kernel of pointwise.hip
+bool pw_stream_ok(const Geom &g, conv2d_op op)
+{
+    if (g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return false;
+    const int rows = op == CONV2D_FWD ? g.K : g.C, depth = op == CONV2D_FWD ? g.C : g.K;
+    if ((int64_t)g.N * depth * g.H * g.W * 4 >= (int64_t(1) << 31)) return false;
+    if ((int64_t)g.N * rows * g.H * g.W * 4 >= (int64_t(1) << 31)) return false;
+    return pw_stream_lds_bytes(rows, depth) != 0;
+}
+
+void fill_pw_args(PwArgs &a, const Geom &g, conv2d_op op, const float *in)
+{
+    const bool fwd = op == CONV2D_FWD;
+    a.in = in;
+    a.D = fwd ? g.C : g.K;
+    a.Rout = fwd ? g.K : g.C;
+    a.HW = g.H * g.W;
+    a.M = g.N * a.HW;
+    a.ntiles = ceil_div(a.M, 32);
+    a.in_bytes = (int32_t)((int64_t)a.M * a.D * 4);
+    a.out_bytes = (int32_t)((int64_t)a.M * a.Rout * 4);
+    a.w_row_stride = fwd ? g.C : 1;
+    a.w_depth_stride = fwd ? 1 : g.C;
+    a.div_HW = make_fastdiv((uint32_t)a.HW);
+    a.div_fast = make_fastdiv((uint32_t)(fwd ? a.D : a.Rout));
+    a.ngroup = 1;
+    for (int i = 0; i <= kMaxGroups; ++i) a.r0[i] = i == 0 ? 0 : a.Rout;
+}
+
+// Pointwise backward-weight as a streaming product (pointwise.hip): plan of the split
+// of the pixel axis.  ok = the layer qualifies (pointer alignment is checked at the call).
+struct PwWgradPlan {
+    bool ok;
+    int splits, steps_per_split, quads, phases, tiles_c;
+    size_t part_bytes, bias_bytes, total_bytes;
+};
+
+PwWgradPlan plan_pw_wgrad(const Geom &g)
+{
+    PwWgradPlan p = {};
+    const int HW = g.H * g.W;
+    if (g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return p;
+    if (HW % 4 != 0 || HW < 16 || g.K > 128 || g.C > 256) return p;
+    if ((int64_t)g.N * g.C * HW * 4 >= (int64_t(1) << 31) || (int64_t)g.N * g.K * HW * 4 >= (int64_t(1) << 31))
+        return p;
+    p.ok = true;
+    p.quads = g.N * (HW / 4);
+    const int total_steps = (p.quads + 3) / 4;          // 16 pixels per step
+    // one workgroup of column groups x pixel phases waves per split: about eight waves
+    // per compute unit, at least four steps per wave; every split costs a K x C partial
+    // product to write and add
+    int NJ, BT;
+    pw_wgrad_shape(g.C, g.K, HW, &NJ, &BT, &p.phases);
+    p.tiles_c = NJ;
+    int per_cu = 8 / (NJ * p.phases);
+    if (per_cu < 1) per_cu = 1;
+    int splits = 256 * per_cu;
+    if (splits > total_steps / (4 * p.phases)) splits = total_steps / (4 * p.phases);
+    if (splits < 1) splits = 1;
+    p.steps_per_split = ceil_div(total_steps, splits);
+    p.splits = ceil_div(total_steps, p.steps_per_split);
+    p.part_bytes = align_up((size_t)p.splits * g.K * g.C * sizeof(float), 256);
+    p.bias_bytes = align_up((size_t)p.splits * g.K * sizeof(float), 256);
+    p.total_bytes = p.part_bytes + p.bias_bytes;
+    return p;
+}
+
 // first-layer backward-data on the vector ALU: 3x3, stride 1, pad_w 1, C <= 4, rows of
 // 4-pixel groups with aligned 16-byte accesses
 bool smallc_bwd_ok(const Geom &g, const float *dy, const float *dx)
@@ -431,7 +499,12 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
-    case CONV2D_BWD_WEIGHT: return plan_wgrad(g).total_bytes;
+    case CONV2D_BWD_WEIGHT: {
+        // the streaming pointwise kernel is taken when the pointers allow it: room for either
+        const size_t generic = plan_wgrad(g).total_bytes;
+        const PwWgradPlan pw = plan_pw_wgrad(g);
+        return pw.ok && pw.total_bytes > generic ? pw.total_bytes : generic;
+    }
     default: return 0;
     }
 }
@@ -450,6 +523,13 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
 
     const GatherPlan p = plan_fwd(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (pw_stream_ok(g, CONV2D_FWD)) {
+        PwArgs pa = {};
+        fill_pw_args(pa, g, CONV2D_FWD, x);
+        pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y;
+        pa.fill_vec = g.C % 4 == 0 && ((uintptr_t)w & 15) == 0;
+        return launch_status(launch_pw_stream(pa, s));
+    }
     float *wt = (float *)ws;
     DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);
 
@@ -504,6 +584,25 @@ int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, c
 
     const GatherPlan p = plan_fwd(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (pw_stream_ok(g, CONV2D_FWD)) {
+        PwArgs sa = {};
+        fill_pw_args(sa, g, CONV2D_FWD, x);
+        sa.ngroup = ngroup;
+        int r = 0;
+        for (int i = 0; i < kMaxGroups; ++i) {
+            const bool used = i < ngroup;
+            sa.r0[i] = r;
+            sa.w[i] = used ? w[i] : w[0];
+            sa.bias[i] = (used && bias) ? bias[i] : nullptr;
+            sa.out[i] = used ? y[i] : y[0];
+            if (used) r += K[i];
+        }
+        sa.r0[kMaxGroups] = r;
+        sa.fill_vec = g.C % 4 == 0;
+        for (int i = 0; i < ngroup; ++i)
+            if (((uintptr_t)w[i] & 15) != 0) sa.fill_vec = 0;
+        return launch_status(launch_pw_stream(sa, s));
+    }
     float *wt = (float *)ws;
     DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);
 
@@ -571,6 +670,13 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
 
     const GatherPlan p = plan_bwd_data(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (pw_stream_ok(g, CONV2D_BWD_DATA)) {
+        PwArgs pa = {};
+        fill_pw_args(pa, g, CONV2D_BWD_DATA, dy);
+        pa.w[0] = w; pa.bias[0] = nullptr; pa.out[0] = dx;
+        pa.fill_vec = g.C % 4 == 0 && ((uintptr_t)w & 15) == 0;
+        return launch_status(launch_pw_stream(pa, s));
+    }
     float *wt = (float *)ws;
     DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);
     const int BN = gemmconv_pixel_tile(p.tile);
@@ -699,6 +805,27 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
         if (rc) return rc;
         if (dbias)
             rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, accumulate, s));
+        return rc;
+    }
+
+    const PwWgradPlan pw = plan_pw_wgrad(g);
+    if (pw.ok && (((uintptr_t)x | (uintptr_t)dy) & 15) == 0) {
+        if (!ws || ws_bytes < pw.total_bytes) return CONV2D_ERR_WORKSPACE;
+        float *part = (float *)ws;
+        float *bias_part = (float *)((char *)ws + pw.part_bytes);
+        PwWgradArgs a = {};
+        a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
+        a.N = g.N; a.C = g.C; a.K = g.K; a.HW = g.H * g.W;
+        a.x_bytes = (int32_t)((int64_t)g.N * g.C * a.HW * 4);
+        a.dy_bytes = (int32_t)((int64_t)g.N * g.K * a.HW * 4);
+        a.quads = pw.quads; a.steps_per_split = pw.steps_per_split; a.splits = pw.splits;
+        a.tiles_c = pw.tiles_c; a.phases = pw.phases;
+        a.div_QW = make_fastdiv((uint32_t)(a.HW / 4));
+        rc = launch_status(launch_pw_wgrad(a, s));
+        if (rc) return rc;
+        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C, pw.splits, scale, accumulate, s));
+        if (rc) return rc;
+        if (dbias) rc = launch_status(launch_bias_final(bias_part, dbias, g.K, pw.splits, scale, accumulate, s));
         return rc;
     }
 

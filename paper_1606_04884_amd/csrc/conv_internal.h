@@ -227,6 +227,51 @@ struct SmallCArgs {
 };
 hipError_t launch_bwd_data_smallc(const SmallCArgs &a, hipStream_t s);
 
+// ---------------------------------------------------------------------------
+// Pointwise (1x1, stride 1, unpadded) layers as streaming products (see
+// pointwise.hip).  out[n][r][p] = bias[r] + sum_d A[r][d] * in[n][d][p], p < HW.
+// Forward: r = filter, d = input channel, A = w.  Backward-data: r = input channel,
+// d = filter, A = w transposed.  A is element (r, d) at w[(r - r0[g]) * w_row_stride
+// + d * w_depth_stride] of the group g that owns row r.
+// ---------------------------------------------------------------------------
+struct PwArgs {
+    const float *in;
+    int32_t in_bytes;                    // below 2^31
+    int32_t out_bytes;                   // size of out[0] when ngroup == 1 (below 2^31)
+    int32_t ngroup;                      // 1 .. kMaxGroups; rows r0[g] .. r0[g+1]-1 belong to group g
+    const float *w[kMaxGroups];
+    const float *bias[kMaxGroups];       // nullable
+    float *out[kMaxGroups];              // group g: [N][r0[g+1]-r0[g]][HW]
+    int32_t r0[kMaxGroups + 1];
+    int32_t w_row_stride, w_depth_stride;
+    int32_t fill_vec;                    // A may be fetched as aligned 16-byte vectors along its contiguous axis
+    int32_t D, Rout, HW, M;              // M = N*HW pixels
+    int32_t ntiles;                      // 32-pixel tiles
+    FastDiv div_HW, div_fast;            // div_fast: by D if w_depth_stride == 1, else by Rout
+};
+// largest rows x depth product the kernel keeps in LDS, in bytes; 0 if the shape does not fit
+size_t pw_stream_lds_bytes(int Rout, int D);
+hipError_t launch_pw_stream(const PwArgs &a, hipStream_t s);
+
+// Pointwise backward-weight: part[s][k][c] = sum over the pixels of range s of
+// dy[n][k][p] * x[n][c][p]; bias_part[s][k] = the same sum of dy alone.  HW % 4 == 0,
+// HW >= 16, both tensors below 2^31 bytes and 16-byte aligned, K <= 128, C <= 256.
+struct PwWgradArgs {
+    const float *x;
+    const float *dy;
+    float *part;               // [splits][K][C]
+    float *bias_part;          // [splits][K], or null
+    int32_t N, C, K, HW;
+    int32_t x_bytes, dy_bytes;
+    int32_t quads;             // N*HW/4 groups of 4 pixels
+    int32_t steps_per_split;   // 16-pixel steps per split
+    int32_t splits;
+    int32_t tiles_c, phases;   // column groups x pixel phases = waves per workgroup (pw_wgrad_shape)
+    FastDiv div_QW;            // by HW/4
+};
+void pw_wgrad_shape(int C, int K, int HW, int *NJ, int *BT, int *PH);
+hipError_t launch_pw_wgrad(const PwWgradArgs &a, hipStream_t s);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Per-element operation y = fl(fl(a*x) + b) over n floats (see apply.hip).

@@ -338,9 +338,54 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
     }
 }
 
+// The same sum for many splits of a small tensor, where one thread per element would
+// leave most of the chip idle behind long chains of loads: 64 consecutive elements per
+// workgroup, each of its eight waves adds an eighth of the splits (sixteen interleaved
+// sums, combined pairwise), and wave 0 combines the eight results in a fixed order.
+__global__ __launch_bounds__(512) void split_reduce_wide_kernel(const float *__restrict__ part,
+                                                                float *__restrict__ dst, int64_t count,
+                                                                int splits, float scale, int accumulate)
+{
+    __shared__ float sm[7][64];
+    const int e = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + e;
+    const int per = (splits + 7) / 8;
+    const int k0 = q * per, k1 = min(splits, k0 + per);
+    float s[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) s[u] = 0.f;
+    if (i < count) {
+        const float *p = part + i;
+        int k = k0;
+        for (; k + 16 <= k1; k += 16) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) s[u] += p[(int64_t)(k + u) * count];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (k + u < k1) s[u] += p[(int64_t)(k + u) * count];
+    }
+#pragma unroll
+    for (int w = 8; w >= 1; w >>= 1)
+#pragma unroll
+        for (int u = 0; u < w; ++u) s[u] += s[u + w];
+    if (q > 0) sm[q - 1][e] = s[0];
+    __syncthreads();
+    if (q == 0 && i < count) {
+        float t = ((s[0] + sm[0][e]) + (sm[1][e] + sm[2][e])) + ((sm[3][e] + sm[4][e]) + (sm[5][e] + sm[6][e]));
+        t *= scale;
+        dst[i] = accumulate ? dst[i] + t : t;
+    }
+}
+
 hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
                                float scale, int accumulate, hipStream_t s)
 {
+    if (splits >= 32 && count <= 256 * 1024) {
+        hipLaunchKernelGGL(split_reduce_wide_kernel, dim3((unsigned)((count + 63) / 64)), dim3(512), 0, s,
+                           part, dst, count, splits, scale, accumulate);
+        return hipGetLastError();
+    }
     int64_t blocks = (count + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, dst,
