@@ -43,6 +43,13 @@ def executed_flops(L, P, Q, op, algo):
     bwd_data)."""
     if algo != 2:
         return layer_flops(L, P, Q)
+    if L.stride > 1:
+        # strided layer as a stride-1 3x3 layer over stride^2 * C channels (padded to the
+        # kernels' channel granularity) on a (P+2) x (Q+2) map
+        cq = L.stride * L.stride * L.C
+        cq = -(-cq // 32) * 32 if op == "bwd_weight" else -(-cq // 8) * 8
+        th, tw = (-(-(P + 2) // 2), -(-(Q + 2) // 2)) if op == "bwd_data" else (-(-P // 2), -(-Q // 2))
+        return 32.0 * L.N * th * tw * L.K * cq
     th, tw = (-(-L.H // 2), -(-L.W // 2)) if op == "bwd_data" else (-(-P // 2), -(-Q // 2))
     nsub = -(-L.R // 3) * -(-L.S // 3)        # 3x3 sub-filters of a larger filter
     return 32.0 * L.N * th * tw * L.K * L.C * nsub

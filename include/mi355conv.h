@@ -55,9 +55,13 @@ typedef struct {
 typedef enum {
     CONV2D_ALGO_AUTO = 0,        /* library picks (see conv2d_pick_algo)          */
     CONV2D_ALGO_IGEMM = 1,       /* implicit GEMM on fp32 MFMA, any geometry      */
-    CONV2D_ALGO_WINOGRAD = 2     /* F(2x2,3x3), stride 1: 3x3 filters; forward and
-                                  * backward-data also filters up to 6x6, as sums of
-                                  * 3x3 sub-filters of shifted inputs              */
+    CONV2D_ALGO_WINOGRAD = 2     /* F(2x2,3x3), stride 1: 3x3 filters, and filters up
+                                  * to 6x6 as sums of 3x3 sub-filters of shifted
+                                  * inputs; stride 2..4 (both directions equal) with a
+                                  * filter spanning exactly 3 x 3 strides (11x11/4,
+                                  * 5x5/2, ...): as the stride-1 3x3 layer over the
+                                  * space-to-depth rearrangement of the input, which
+                                  * the workspace then holds a copy of              */
 } conv2d_algo;
 
 typedef enum {

@@ -321,11 +321,20 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
     return p;
 }
 
+bool s2d_applicable(const Geom &g, conv2d_op op);     // strided layer as a stride-1 3x3 layer, below
+
 int resolve_algo(const Geom &g, conv2d_op op, int algo)
 {
-    const bool wino_ok = wino_applicable(g, op);
+    const bool s2d_ok = s2d_applicable(g, op);
+    const bool wino_ok = wino_applicable(g, op) || s2d_ok;
     switch (algo) {
     case CONV2D_ALGO_AUTO: {
+        // strided first layers (few channels, filter of 3 x 3 strides): rearranged into a
+        // stride-1 3x3 layer over stride^2 * C channels, which Winograd takes
+        // (backward passes only: forward through the gather kernel is as fast, without the
+        // rearranged copy)
+        if (s2d_ok)
+            return (op != CONV2D_FWD && g.sh * g.sw * g.C <= 64) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
         // Winograd pays once the 16 GEMMs are deep enough to amortise the transforms
         const int nsub_f = ceil_div(g.R, 3) * ceil_div(g.S, 3);
         const bool pays_f = 4 * nsub_f * 14 <= g.R * g.S * 10;
@@ -464,6 +473,140 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
     return launch_status(launch_wino_fused(a, p.grid, s));
 }
 
+// Winograd backward-weight of a stride-1 layer; acc_w / acc_b: add to dw / dbias
+int run_wino_wgrad(const Geom &g, const float *x, const float *dy, float *dw, float *dbias, float scale,
+                   int acc_w, int acc_b, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const WinoWgradPlan p = plan_wino_wgrad(g);
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *part = (float *)ws;
+    float *bias_part = (float *)((char *)ws + p.part_bytes);
+    WinoWgradArgs a = {};
+    a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
+    a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q;
+    a.pad_h = g.ph; a.pad_w = g.pw;
+    a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
+    a.tiles_per_split = p.tiles_per_split;
+    a.tiles_k = p.tiles_k; a.tiles_c = p.tiles_c; a.splits = p.splits;
+    a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+    a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+    a.div_THW = make_fastdiv((uint32_t)(p.TH * p.TW));
+    a.div_TW = make_fastdiv((uint32_t)p.TW);
+    a.nsub = p.nsub; a.tiles_c_sub = p.tiles_c_sub;
+    {
+        const int nsw = ceil_div(g.S, 3);
+        for (int q = 0; q < 4; ++q) {
+            a.sub_dh[q] = q < p.nsub ? 3 * (q / nsw) : 0;
+            a.sub_dw[q] = q < p.nsub ? 3 * (q % nsw) : 0;
+        }
+    }
+    int rc = launch_status(launch_wino_wgrad(a, s));
+    if (rc) return rc;
+    if (p.nsub > 1)
+        rc = launch_status(launch_split_reduce_sub(part, dw, g.K, g.C, g.R, g.S, p.splits, scale, acc_w, s));
+    else
+        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale, acc_w, s));
+    if (rc) return rc;
+    if (dbias) rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, acc_b, s));
+    return rc;
+}
+
+// ---- strided layers as stride-1 3x3 layers over s*s*C channels (space_to_depth.hip) ----
+struct S2dPlan {
+    bool ok;
+    int s, Cq;                  // stride; channels of the rearranged input (s*s*C padded)
+    Geom g2;                    // the stride-1 3x3 layer
+    size_t x2_bytes, w2_bytes, dw2_bytes, inner_bytes, total_bytes;
+};
+
+size_t wino_ws_bytes(const Geom &g, conv2d_op op)
+{
+    return op == CONV2D_BWD_WEIGHT ? plan_wino_wgrad(g).total_bytes : plan_wino(g, op).total_bytes;
+}
+
+S2dPlan plan_s2d(const Geom &g, conv2d_op op)
+{
+    S2dPlan p = {};
+    const int st = g.sh;
+    if (st < 2 || st > 4 || g.sw != st) return p;
+    if (ceil_div(g.R, st) != 3 || ceil_div(g.S, st) != 3) return p;
+    if (g.N > 65535) return p;                              // the rearrangement kernels' grid
+    // channel granularity of the Winograd kernels: 8 (chunk) / 32 (backward-weight tile)
+    p.Cq = round_up(st * st * g.C, op == CONV2D_BWD_WEIGHT ? 32 : 8);
+    if (p.Cq > 65535) return p;
+    Geom &q = p.g2;
+    q.N = g.N; q.C = p.Cq; q.H = g.P + 2; q.W = g.Q + 2; q.K = g.K; q.R = 3; q.S = 3;
+    q.sh = 1; q.sw = 1; q.ph = 0; q.pw = 0; q.P = g.P; q.Q = g.Q;
+    if ((int64_t)q.N * q.C * q.H * q.W * 4 >= (int64_t(1) << 31)) return p;
+    if (!wino_applicable(q, op)) return p;
+    p.ok = true;
+    p.s = st;
+    p.x2_bytes = align_up((size_t)q.N * q.C * q.H * q.W * sizeof(float), 256);
+    p.w2_bytes = align_up((size_t)q.K * q.C * 9 * sizeof(float), 256);
+    p.dw2_bytes = op == CONV2D_BWD_WEIGHT ? p.w2_bytes : 0;
+    p.inner_bytes = wino_ws_bytes(q, op);
+    p.total_bytes = p.x2_bytes + p.w2_bytes + p.dw2_bytes + p.inner_bytes;
+    return p;
+}
+
+bool s2d_applicable(const Geom &g, conv2d_op op) { return plan_s2d(g, op).ok; }
+
+void fill_s2d_args(S2dArgs &a, const Geom &g, const S2dPlan &p)
+{
+    a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.s = p.s; a.pad_h = g.ph; a.pad_w = g.pw;
+    a.Cq = p.Cq; a.H2 = p.g2.H; a.W2 = p.g2.W;
+    a.I2 = ceil_div(g.H + g.ph, p.s) > a.H2 ? ceil_div(g.H + g.ph, p.s) : a.H2;
+    a.J2 = ceil_div(g.W + g.pw, p.s) > a.W2 ? ceil_div(g.W + g.pw, p.s) : a.W2;
+    a.div_W2 = make_fastdiv((uint32_t)a.W2);
+    a.div_J2 = make_fastdiv((uint32_t)a.J2);
+}
+
+int run_s2d(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias, float *out,
+            void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const S2dPlan p = plan_s2d(g, op);
+    if (!p.ok) return CONV2D_ERR_ALGO;
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *x2 = (float *)ws;
+    float *w2 = (float *)((char *)ws + p.x2_bytes);
+    void *inner = (char *)ws + p.x2_bytes + p.w2_bytes;
+    S2dArgs sa = {};
+    fill_s2d_args(sa, g, p);
+    int rc = launch_status(launch_filter_s2d(w, w2, g.K, g.C, g.R, g.S, p.s, p.Cq, s));
+    if (rc) return rc;
+    if (op == CONV2D_FWD) {
+        sa.x = in; sa.x2 = x2;
+        rc = launch_status(launch_space_to_depth(sa, s));
+        if (rc) return rc;
+        return run_wino(p.g2, CONV2D_FWD, x2, w2, bias, out, inner, p.inner_bytes, s);
+    }
+    // backward-data: gradient of the rearranged input, then the inverse permutation
+    rc = run_wino(p.g2, CONV2D_BWD_DATA, in, w2, nullptr, x2, inner, p.inner_bytes, s);
+    if (rc) return rc;
+    sa.x2 = x2; sa.dx = out;
+    return launch_status(launch_depth_to_space(sa, s));
+}
+
+int run_s2d_wgrad(const Geom &g, const float *x, const float *dy, float *dw, float *dbias, float scale,
+                  int accumulate, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const S2dPlan p = plan_s2d(g, CONV2D_BWD_WEIGHT);
+    if (!p.ok) return CONV2D_ERR_ALGO;
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    float *x2 = (float *)ws;
+    float *dw2 = (float *)((char *)ws + p.x2_bytes + p.w2_bytes);
+    void *inner = (char *)ws + p.x2_bytes + p.w2_bytes + p.dw2_bytes;
+    S2dArgs sa = {};
+    fill_s2d_args(sa, g, p);
+    sa.x = x; sa.x2 = x2;
+    int rc = launch_status(launch_space_to_depth(sa, s));
+    if (rc) return rc;
+    // scaled gradient of the rearranged filter (not accumulated), then back to K x C x R x S
+    rc = run_wino_wgrad(p.g2, x2, dy, dw2, dbias, scale, 0, accumulate, inner, p.inner_bytes, s);
+    if (rc) return rc;
+    return launch_status(launch_filter_d2s(dw2, dw, g.K, g.C, g.R, g.S, p.s, p.Cq, accumulate, s));
+}
+
 }  // namespace
 
 extern "C" {
@@ -495,7 +638,7 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     const int al = resolve_algo(g, op, (int)algo);
     if (al < 0) return 0;
     if (al == CONV2D_ALGO_WINOGRAD)
-        return op == CONV2D_BWD_WEIGHT ? plan_wino_wgrad(g).total_bytes : plan_wino(g, op).total_bytes;
+        return wino_applicable(g, op) ? wino_ws_bytes(g, op) : plan_s2d(g, op).total_bytes;
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
@@ -519,7 +662,9 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
     const int al = resolve_algo(g, CONV2D_FWD, (int)algo);
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
-    if (al == CONV2D_ALGO_WINOGRAD) return run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s);
+    if (al == CONV2D_ALGO_WINOGRAD)
+        return wino_applicable(g, CONV2D_FWD) ? run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s)
+                                              : run_s2d(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s);
 
     const GatherPlan p = plan_fwd(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
@@ -666,7 +811,10 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
         sa.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
         return launch_status(launch_bwd_data_smallc(sa, s));
     }
-    if (al == CONV2D_ALGO_WINOGRAD) return run_wino(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
+    if (al == CONV2D_ALGO_WINOGRAD)
+        return wino_applicable(g, CONV2D_BWD_DATA)
+                   ? run_wino(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s)
+                   : run_s2d(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
 
     const GatherPlan p = plan_bwd_data(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
@@ -771,41 +919,9 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     hipStream_t s = (hipStream_t)hip_stream;
 
     if (al == CONV2D_ALGO_WINOGRAD) {
-        const WinoWgradPlan p = plan_wino_wgrad(g);
-        if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
-        float *part = (float *)ws;
-        float *bias_part = (float *)((char *)ws + p.part_bytes);
-        WinoWgradArgs a = {};
-        a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
-        a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q;
-        a.pad_h = g.ph; a.pad_w = g.pw;
-        a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
-        a.tiles_per_split = p.tiles_per_split;
-        a.tiles_k = p.tiles_k; a.tiles_c = p.tiles_c; a.splits = p.splits;
-        a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
-        a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
-        a.div_THW = make_fastdiv((uint32_t)(p.TH * p.TW));
-        a.div_TW = make_fastdiv((uint32_t)p.TW);
-        a.nsub = p.nsub; a.tiles_c_sub = p.tiles_c_sub;
-        {
-            const int nsw = ceil_div(g.S, 3);
-            for (int q = 0; q < 4; ++q) {
-                a.sub_dh[q] = q < p.nsub ? 3 * (q / nsw) : 0;
-                a.sub_dw[q] = q < p.nsub ? 3 * (q % nsw) : 0;
-            }
-        }
-        rc = launch_status(launch_wino_wgrad(a, s));
-        if (rc) return rc;
-        if (p.nsub > 1)
-            rc = launch_status(launch_split_reduce_sub(part, dw, g.K, g.C, g.R, g.S, p.splits, scale,
-                                                       accumulate, s));
-        else
-            rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale,
-                                                   accumulate, s));
-        if (rc) return rc;
-        if (dbias)
-            rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, accumulate, s));
-        return rc;
+        if (!wino_applicable(g, CONV2D_BWD_WEIGHT))
+            return run_s2d_wgrad(g, x, dy, dw, dbias, scale, accumulate, ws, ws_bytes, s);
+        return run_wino_wgrad(g, x, dy, dw, dbias, scale, accumulate, accumulate, ws, ws_bytes, s);
     }
 
     const PwWgradPlan pw = plan_pw_wgrad(g);

@@ -272,6 +272,26 @@ struct PwWgradArgs {
 void pw_wgrad_shape(int C, int K, int HW, int *NJ, int *BT, int *PH);
 hipError_t launch_pw_wgrad(const PwWgradArgs &a, hipStream_t s);
 
+// Space-to-depth rearrangement of a strided layer's input (see space_to_depth.hip):
+// x2[n][(a*s + b)*C + c][i][j] = x[n][c][s*i + a - pad_h][s*j + b - pad_w], channels
+// s*s*C .. Cq-1 zero; x2 is N x Cq x H2 x W2.
+struct S2dArgs {
+    const float *x;            // space_to_depth: source
+    float *x2;                 // space_to_depth: destination; depth_to_space: source
+    float *dx;                 // depth_to_space: destination (shape of x)
+    int32_t N, C, H, W, s, pad_h, pad_w, Cq, H2, W2;
+    int32_t I2, J2;            // depth_to_space: (i, j) range covering all of dx
+    FastDiv div_W2, div_J2;
+};
+hipError_t launch_space_to_depth(const S2dArgs &a, hipStream_t s);
+hipError_t launch_depth_to_space(const S2dArgs &a, hipStream_t s);
+// w [K][C][R][S] -> w2 [K][Cq][3][3], w2[k][(a*s + b)*C + c][r'][t'] = w[k][c][s*r' + a][s*t' + b]
+hipError_t launch_filter_s2d(const float *w, float *w2, int K, int C, int R, int S, int stride, int Cq,
+                             hipStream_t s);
+// the inverse, dw = (dw +) the rearranged dw2
+hipError_t launch_filter_d2s(const float *dw2, float *dw, int K, int C, int R, int S, int stride, int Cq,
+                             int accumulate, hipStream_t s);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Per-element operation y = fl(fl(a*x) + b) over n floats (see apply.hip).

@@ -308,3 +308,58 @@ def test_winograd_large_filters(geom):
         got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, scale=-0.5, dw0=dw0.copy(),
                         db0=np.zeros_like(db, dtype=np.float32), passes=("bwd_weight",))
         assert max_err_ratio(got["dw"], -0.5 * dw + dw0) <= TOL_WINOGRAD
+
+
+# strided layers whose filter spans 3 x 3 strides, computed as stride-1 3x3 Winograd
+# layers over the space-to-depth rearrangement of the input
+STRIDED_WINO_SHAPES = [
+    G(2, 3, 67, 67, 64, 11, 11, 4, 2),       # AlexNet conv1 geometry, small map
+    G(2, 3, 59, 59, 96, 11, 11, 4, 0),       # Overfeat conv1 geometry
+    (3, 4, 21, 23, 32, 5, 5, 2, 2, 2, 2),    # 5x5 stride 2, odd non-square map
+    (2, 8, 20, 20, 32, 6, 6, 2, 2, 1, 1),    # filter exactly 3 strides wide
+    (2, 3, 40, 37, 64, 9, 9, 3, 3, 4, 4),    # stride 3
+    (2, 3, 50, 47, 32, 11, 10, 4, 4, 3, 1),  # 11x10 filter, pads differ, map not a multiple of the stride
+    (2, 5, 26, 26, 40, 5, 5, 2, 2, 0, 0),    # K % 32 != 0: backward-weight stays with the general kernel
+    (1, 20, 17, 17, 64, 5, 5, 2, 2, 2, 2),   # 80 rearranged channels (not chosen by default)
+]
+
+
+@pytest.mark.parametrize("geom", STRIDED_WINO_SHAPES, ids=[("x".join(map(str, g))) for g in STRIDED_WINO_SHAPES])
+def test_strided_layers_through_winograd(geom):
+    from gpu_util import TOL_WINOGRAD
+    x, w, b, dy = random_layer(geom, 9000 + sum(geom))
+    print("geom", geom, flush=True)
+    ref = oracle_layer(geom, x, w, b, dy)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, passes=("fwd", "bwd_data"))
+    for name in ("y", "dx"):
+        assert np.isfinite(got[name]).all(), name
+        r = max_err_ratio(got[name], ref[name])
+        assert r <= TOL_WINOGRAD, "%s: max err ratio %.3e" % (name, r)
+    if geom[4] % 32 != 0:
+        assert B.conv2d_pick_algo(geom, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+        return
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, passes=("bwd_weight",))
+    assert max_err_ratio(got["dw"], ref["dw"]) <= TOL_WINOGRAD
+    assert max_err_ratio(got["db"], ref["db"]) <= TOL_IGEMM
+    dw0 = synth.normal(ref["dw"].shape, 18, std=3.0)
+    db0 = synth.normal(ref["db"].shape, 19, std=3.0)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD, scale=0.5, dw0=dw0.copy(), db0=db0.copy(),
+                    passes=("bwd_weight",))
+    assert max_err_ratio(got["dw"], 0.5 * ref["dw"] + dw0) <= TOL_WINOGRAD
+    assert max_err_ratio(got["db"], 0.5 * ref["db"] + db0) <= TOL_IGEMM
+
+
+def test_strided_first_layer_backward_takes_winograd_by_default():
+    """AUTO on the AlexNet conv1 geometry: the backward passes are the rearranged Winograd
+    path (same result as asking for it), the forward pass the gather kernel."""
+    geom = G(2, 3, 67, 67, 64, 11, 11, 4, 2)
+    assert B.conv2d_pick_algo(geom, B.OP_FWD) == B.ALGO_IGEMM
+    for op in (B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+        assert B.conv2d_pick_algo(geom, op) == B.ALGO_WINOGRAD
+    x, w, b, dy = random_layer(geom, 9100)
+    a = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_AUTO)
+    c = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD)
+    d = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_IGEMM, passes=("fwd",))
+    for name in ("dx", "dw", "db"):
+        assert np.array_equal(a[name], c[name]), name
+    assert np.array_equal(a["y"], d["y"])

@@ -145,6 +145,27 @@ def test_algo_choice_rules():
     assert pick((8, 64, 20, 20, 64, 4, 4, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # 4x4: no saving
     assert pick((8, 64, 20, 20, 64, 7, 7, 1, 1, 3, 3), B.OP_FWD) == B.ALGO_IGEMM          # above 6x6
     assert pick((8, 64, 56, 56, 64, 3, 3, 2, 2, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # stride 2
+    # strided first layers whose filter spans 3 x 3 strides: the backward passes go through a
+    # rearrangement into a stride-1 3x3 layer over stride^2 * C channels (Winograd), which
+    # needs K % 8 (backward-data) / K % 32 (backward-weight) like every Winograd layer; the
+    # forward pass takes that route only on request
+    alex1 = (128, 3, 224, 224, 64, 11, 11, 4, 4, 2, 2)
+    assert pick(alex1, B.OP_FWD) == B.ALGO_IGEMM
+    assert B.conv2d_workspace_bytes(alex1, B.OP_FWD, B.ALGO_WINOGRAD) > 128 * 48 * 57 * 57 * 4
+    for op in (B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+        assert pick(alex1, op) == B.ALGO_WINOGRAD
+        # room for the rearranged tensor (128 x 48.. x 57 x 57 floats) on top of the inner workspace
+        assert B.conv2d_workspace_bytes(alex1, op, B.ALGO_AUTO) > 128 * 48 * 57 * 57 * 4
+    odd_k = (4, 3, 67, 67, 20, 11, 11, 4, 4, 2, 2)
+    assert B.conv2d_workspace_bytes(odd_k, B.OP_FWD, B.ALGO_WINOGRAD) > 0
+    assert pick(odd_k, B.OP_BWD_DATA) == B.ALGO_IGEMM
+    assert pick(odd_k, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+    assert B.conv2d_workspace_bytes(odd_k, B.OP_BWD_DATA, B.ALGO_WINOGRAD) == 0
+    assert pick((4, 3, 40, 40, 32, 5, 5, 2, 2, 2, 2), B.OP_BWD_DATA) == B.ALGO_WINOGRAD    # 5x5 stride 2
+    assert pick((4, 3, 40, 40, 32, 7, 7, 2, 2, 3, 3), B.OP_BWD_DATA) == B.ALGO_IGEMM       # 4 x 4 strides
+    assert pick((4, 64, 40, 40, 32, 5, 5, 2, 2, 2, 2), B.OP_BWD_DATA) == B.ALGO_IGEMM      # many channels: not by default
+    assert B.conv2d_workspace_bytes((4, 64, 40, 40, 32, 5, 5, 2, 2, 2, 2), B.OP_BWD_DATA, B.ALGO_WINOGRAD) > 0
+    assert pick((4, 3, 40, 40, 32, 5, 5, 2, 1, 2, 2), B.OP_BWD_DATA) == B.ALGO_IGEMM       # unequal strides
     big = (256, 64, 224, 224, 64, 3, 3, 1, 1, 1, 1)             # x and y are 3.3 GB each
     for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
         assert pick(big, op) == B.ALGO_IGEMM
