@@ -502,12 +502,11 @@ int run_wino_wgrad(const Geom &g, const float *x, const float *dy, float *dw, fl
     }
     int rc = launch_status(launch_wino_wgrad(a, s));
     if (rc) return rc;
+    const BiasJob bj = {dbias ? bias_part : nullptr, dbias, g.K, p.splits, acc_b};
     if (p.nsub > 1)
-        rc = launch_status(launch_split_reduce_sub(part, dw, g.K, g.C, g.R, g.S, p.splits, scale, acc_w, s));
+        rc = launch_status(launch_split_reduce_sub(part, dw, g.K, g.C, g.R, g.S, p.splits, scale, acc_w, bj, s));
     else
-        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale, acc_w, s));
-    if (rc) return rc;
-    if (dbias) rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, acc_b, s));
+        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C * 9, p.splits, scale, acc_w, bj, s));
     return rc;
 }
 
@@ -939,10 +938,8 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
         a.div_QW = make_fastdiv((uint32_t)(a.HW / 4));
         rc = launch_status(launch_pw_wgrad(a, s));
         if (rc) return rc;
-        rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C, pw.splits, scale, accumulate, s));
-        if (rc) return rc;
-        if (dbias) rc = launch_status(launch_bias_final(bias_part, dbias, g.K, pw.splits, scale, accumulate, s));
-        return rc;
+        const BiasJob bj = {dbias ? bias_part : nullptr, dbias, g.K, pw.splits, accumulate};
+        return launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C, pw.splits, scale, accumulate, bj, s));
     }
 
     const WgradPlan p = plan_wgrad(g);
@@ -962,13 +959,9 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     a.div_S = make_fastdiv((uint32_t)g.S);
     rc = launch_status(launch_wgrad(a, p.tile, s));
     if (rc) return rc;
-    rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * a.CRS, p.splits, scale,
-                                           accumulate, s));
+    const BiasJob bj = {dbias ? bias_part : nullptr, dbias, g.K, p.splits, accumulate};
+    rc = launch_status(launch_split_reduce(part, dw, (int64_t)g.K * a.CRS, p.splits, scale, accumulate, bj, s));
     if (rc) return rc;
-    if (dbias) {
-        rc = launch_status(launch_bias_final(bias_part, dbias, g.K, p.splits, scale, accumulate, s));
-        if (rc) return rc;
-    }
     return CONV2D_OK;
 }
 

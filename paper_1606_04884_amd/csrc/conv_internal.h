@@ -144,16 +144,20 @@ struct WgradArgs {
 int wgrad_filter_tile(int tile);
 int wgrad_col_tile(int tile);
 hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s);
+// Final stage of the bias gradient, done by extra workgroups of the split-reduce launch:
+// db[k] = scale * sum_i part[i][k] (+ db[k]).  part == nullptr: no bias gradient wanted.
+struct BiasJob {
+    const float *part;         // [nsplit][K]
+    float *db;
+    int32_t K, nsplit, accumulate;
+};
 // dst[i] = scale * sum_s part[s][i] (+ dst[i] if accumulate)
 hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
-                               float scale, int accumulate, hipStream_t s);
-// db[k] = scale * sum_i part[i][k] (+ db[k])
+                               float scale, int accumulate, const BiasJob &bj, hipStream_t s);
 // dw[k][c][r][s] = scale * sum over splits of part[split][k][q*C + c][(r%3)*3 + s%3], q the
 // sub-filter holding tap (r, s) (see WinoWgradArgs)
 hipError_t launch_split_reduce_sub(const float *part, float *dw, int K, int C, int R, int S, int splits,
-                                   float scale, int accumulate, hipStream_t s);
-hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
-                             int accumulate, hipStream_t s);
+                                   float scale, int accumulate, const BiasJob &bj, hipStream_t s);
 // ---------------------------------------------------------------------------
 // Winograd F(2x2,3x3), fused (see winograd.hip).  `in` is the tensor the 4x4
 // patches are read from (x for forward, dy for backward-data), U the

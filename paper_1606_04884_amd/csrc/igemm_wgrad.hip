@@ -313,15 +313,37 @@ hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s)
     return hipGetLastError();
 }
 
+// Bias gradient, final stage: db[k] = scale * sum of the per-split partial sums.  One wave
+// per filter: lane l adds the partials l, l+64, ... in order, then the 64 lane sums are
+// combined in a fixed butterfly order (deterministic).  It rides along with the reduction of
+// the filter gradient as extra workgroups of the same launch (wave index = filter).
+__device__ __forceinline__ void bias_final_wave(const BiasJob &b, int k, float scale)
+{
+    if (k >= b.K) return;
+    const int lane = threadIdx.x & 63;
+    float s = 0.f;
+    for (int i = lane; i < b.nsplit; i += 64) s += b.part[i * b.K + k];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+    s *= scale;
+    if (lane == 0) b.db[k] = b.accumulate ? b.db[k] + s : s;
+}
+
 // dst[i] = scale * (sum over splits of part[s][i]) (+ dst[i]).  Eight interleaved
 // partial sums (split s goes to sum s % 8) combined pairwise: a fixed order, so the
-// result is reproducible, with eight loads in flight per thread.
+// result is reproducible, with eight loads in flight per thread.  Workgroups
+// main_blocks.. do the bias job.
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ part,
                                                            float *__restrict__ dst, int64_t count,
-                                                           int splits, float scale, int accumulate)
+                                                           int splits, float scale, int accumulate,
+                                                           int main_blocks, BiasJob bj)
 {
+    if ((int)blockIdx.x >= main_blocks) {
+        bias_final_wave(bj, ((int)blockIdx.x - main_blocks) * 4 + (threadIdx.x >> 6), scale);
+        return;
+    }
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-         i += (int64_t)gridDim.x * blockDim.x) {
+         i += (int64_t)main_blocks * blockDim.x) {
         float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         const float *p = part + i;
         int k = 0;
@@ -344,9 +366,14 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
 // sums, combined pairwise), and wave 0 combines the eight results in a fixed order.
 __global__ __launch_bounds__(512) void split_reduce_wide_kernel(const float *__restrict__ part,
                                                                 float *__restrict__ dst, int64_t count,
-                                                                int splits, float scale, int accumulate)
+                                                                int splits, float scale, int accumulate,
+                                                                int main_blocks, BiasJob bj)
 {
     __shared__ float sm[7][64];
+    if ((int)blockIdx.x >= main_blocks) {
+        bias_final_wave(bj, ((int)blockIdx.x - main_blocks) * 8 + (threadIdx.x >> 6), scale);
+        return;
+    }
     const int e = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * 64 + e;
     const int per = (splits + 7) / 8;
@@ -379,17 +406,21 @@ __global__ __launch_bounds__(512) void split_reduce_wide_kernel(const float *__r
 }
 
 hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int splits,
-                               float scale, int accumulate, hipStream_t s)
+                               float scale, int accumulate, const BiasJob &bj, hipStream_t s)
 {
+    const bool bias = bj.part != nullptr && bj.db != nullptr;
     if (splits >= 32 && count <= 256 * 1024) {
-        hipLaunchKernelGGL(split_reduce_wide_kernel, dim3((unsigned)((count + 63) / 64)), dim3(512), 0, s,
-                           part, dst, count, splits, scale, accumulate);
+        const int main_blocks = (int)((count + 63) / 64);
+        const int extra = bias ? (bj.K + 7) / 8 : 0;
+        hipLaunchKernelGGL(split_reduce_wide_kernel, dim3((unsigned)(main_blocks + extra)), dim3(512), 0, s,
+                           part, dst, count, splits, scale, accumulate, main_blocks, bj);
         return hipGetLastError();
     }
     int64_t blocks = (count + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, dst,
-                       count, splits, scale, accumulate);
+    const int extra = bias ? (bj.K + 3) / 4 : 0;
+    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)(blocks + extra)), dim3(256), 0, s, part, dst,
+                       count, splits, scale, accumulate, (int)blocks, bj);
     return hipGetLastError();
 }
 
@@ -399,13 +430,17 @@ hipError_t launch_split_reduce(const float *part, float *dst, int64_t count, int
 __global__ __launch_bounds__(256) void split_reduce_sub_kernel(const float *__restrict__ part,
                                                                float *__restrict__ dw, int K, int C,
                                                                int R, int S, int splits, float scale,
-                                                               int accumulate)
+                                                               int accumulate, int main_blocks, BiasJob bj)
 {
+    if ((int)blockIdx.x >= main_blocks) {
+        bias_final_wave(bj, ((int)blockIdx.x - main_blocks) * 4 + (threadIdx.x >> 6), scale);
+        return;
+    }
     const int nsw = (S + 2) / 3, nsub = ((R + 2) / 3) * nsw;
     const int64_t count = (int64_t)K * C * R * S;
     const int64_t src_count = (int64_t)K * nsub * C * 9;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-         i += (int64_t)gridDim.x * blockDim.x) {
+         i += (int64_t)main_blocks * blockDim.x) {
         const int ss = (int)(i % S), r = (int)((i / S) % R);
         const int c = (int)((i / ((int64_t)R * S)) % C), k = (int)(i / ((int64_t)R * S * C));
         const int q = (r / 3) * nsw + ss / 3;
@@ -426,38 +461,14 @@ __global__ __launch_bounds__(256) void split_reduce_sub_kernel(const float *__re
 }
 
 hipError_t launch_split_reduce_sub(const float *part, float *dw, int K, int C, int R, int S, int splits,
-                                   float scale, int accumulate, hipStream_t s)
+                                   float scale, int accumulate, const BiasJob &bj, hipStream_t s)
 {
+    const bool bias = bj.part != nullptr && bj.db != nullptr;
     int64_t blocks = ((int64_t)K * C * R * S + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(split_reduce_sub_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, dw, K, C, R,
-                       S, splits, scale, accumulate);
-    return hipGetLastError();
-}
-
-// Bias gradient, final stage: db[k] = scale * sum of the per-split partial sums.
-// One wave per filter: lane l adds the partials l, l+64, ... in order, then the 64
-// lane sums are combined in a fixed butterfly order (deterministic).
-__global__ __launch_bounds__(256) void bias_grad_final_kernel(const float *__restrict__ part,
-                                                              float *__restrict__ db, int K,
-                                                              int nsplit, float scale, int accumulate)
-{
-    const int lane = threadIdx.x & 63;
-    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (k >= K) return;
-    float s = 0.f;
-    for (int i = lane; i < nsplit; i += 64) s += part[i * K + k];
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-    s *= scale;
-    if (lane == 0) db[k] = accumulate ? db[k] + s : s;
-}
-
-hipError_t launch_bias_final(const float *part, float *db, int K, int nsplit, float scale,
-                             int accumulate, hipStream_t s)
-{
-    hipLaunchKernelGGL(bias_grad_final_kernel, dim3((unsigned)((K + 3) / 4)), dim3(256), 0, s,
-                       part, db, K, nsplit, scale, accumulate);
+    const int extra = bias ? (bj.K + 3) / 4 : 0;
+    hipLaunchKernelGGL(split_reduce_sub_kernel, dim3((unsigned)(blocks + extra)), dim3(256), 0, s, part, dw, K,
+                       C, R, S, splits, scale, accumulate, (int)blocks, bj);
     return hipGetLastError();
 }
 
