@@ -1010,6 +1010,10 @@ hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s)
     else if (a.nsub > 1 || a.pad_w > 1 || a.Win % 2 != 0) e = launch_wino_variant<false>(a, G, s);
     else e = launch_wino_variant<true>(a, G, s);
     if (e != hipSuccess || G < 2) return e;
+    // the fix-up pass is needed only if some range boundary falls inside a tile
+    bool cut = false;
+    for (int b = 0; b + 1 < G && !cut; ++b) cut = ((int64_t)(b + 1) * a.units_total / G) % a.nchunks != 0;
+    if (!cut) return e;
     hipLaunchKernelGGL(wino_fixup_kernel, dim3((unsigned)(G - 1), 4), dim3(256), 0, s, a, G);
     return hipGetLastError();
 }

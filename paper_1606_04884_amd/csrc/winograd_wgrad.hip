@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_kernel(WinoWgradArgs a)
 // an even column: always inside the row), the two gradient tiles are one
 // 16-byte load per row, the column half of B^T d B is shared by the two
 // patches, and both tiles' values of a position go out in one paired LDS store.
-// 14 loads per step instead of 40.  The tile grid is taken with its width
+// The tile grid is taken with its width
 // rounded up to even so that a pair never straddles two tile rows; when the true
 // width is odd (ODD) the last pair of a row has a phantom right tile: its
 // gradient tile and the image columns past the edge are fetched with 8-byte
@@ -331,18 +331,27 @@ constexpr int kWvPlane = 512;                          // floats per (buf, pos):
 constexpr int kWvOperand = 2 * 16 * kWvPlane;          // floats per operand (two buffers)
 constexpr int kWvLdsBytes = 2 * kWvOperand * (int)sizeof(float);
 
-template <bool ODD>
-__global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
+// Eight waves, two per SIMD, so that the loads, LDS traffic and barrier waits of one
+// wave fall under the other wave's MFMAs.  Waves 4*PH .. 4*PH+3 keep the 8 positions
+// 8*PH .. 8*PH+7 (rows 2*PH, 2*PH+1 of the 4x4 position grid) of the four 32x32
+// quadrants; thread (PH, channel, pair) produces exactly those rows of B^T d B and
+// |A| dy |A|^T for its channel / filter and tile pair, for which it needs 3 of the 4
+// patch rows (PH .. PH+2) and both gradient rows: 11 loads per step and thread, half
+// the transform and LDS-store work of a thread that did all 16 positions.  At the end
+// the waves of PH = 1 hand their accumulators to PH = 0 through LDS (the operand
+// buffers, free by then), which applies the output transform.
+// ---------------------------------------------------------------------------
+template <bool ODD, int PH>
+__device__ __forceinline__ void wino_wgrad_vec_body(const WinoWgradArgs &a, float *lds)
 {
     constexpr int KB = kWwKB, CB = kWwCB, TS = kWwTS;
     constexpr int NXO = ODD ? 4 : 3, NDO = ODD ? 2 : 1;
-    extern __shared__ float lds[];
     float *const As = lds;
     float *const Bs = lds + kWvOperand;
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;               // index inside the PH group
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = __builtin_amdgcn_readfirstlane(tid >> 6);      // quadrant
     const int l32 = lane & 31, lhi = lane >> 5;
 
     const int ntile = a.tiles_k * a.tiles_c;
@@ -361,8 +370,8 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
     const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t drs = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.dy_bytes, 0x00020000);
 
-    uint32_t xo[4][NXO], dof[2][NDO];
-    float xr[4][6], dr[2][4];
+    uint32_t xo[3][NXO], dof[2][NDO];                // patch rows PH .. PH+2, gradient rows 0, 1
+    float xr[3][6], dr[2][4];
 
     auto setup = [&](int step) {
         const int tb = t_begin + step * TS + 2 * pr;
@@ -372,11 +381,11 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
         const int rem = tl - n * (a.TH * a.TW);
         const int th = (int)fast_div((uint32_t)rem, a.div_TW);
         const int tw = rem - th * a.TW;                 // even
-        const int ih0 = 2 * th - a.pad_h, col0 = 2 * tw;
+        const int ih0 = 2 * th - a.pad_h + PH, col0 = 2 * tw;
         const int xbase = ((n * a.C + c) * a.H + ih0) * a.W + col0;
         const bool lok = tw > 0, hok = col0 + 3 < a.W, rgt = col0 + 4 < a.W;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 3; ++i) {
             const bool rok = tv && cok && (unsigned)(ih0 + i) < (unsigned)a.H;
             const uint32_t m = (uint32_t)(xbase + i * a.W) * 4u;
             xo[i][0] = (rok && lok) ? m - 4u : 0x80000000u;
@@ -393,7 +402,6 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
             if (ODD) dof[r][1] = (dok && hok) ? m + 8u : 0x80000000u;
         }
     };
-    // one load instruction: row i of the patch pair, part 0 .. NXO-1
     auto load_x = [&](int i, int part) {
         if (part == 0) {
             xr[i][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrs, xo[i][0], 0, 0));
@@ -416,33 +424,36 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
             dr[r][2 * part] = m[0]; dr[r][2 * part + 1] = m[1];
         }
     };
-    constexpr int NLOAD = 4 * NXO + 2 * NDO;
+    constexpr int NXL = 3 * NXO;                      // image loads per step
+    constexpr int NLOAD = NXL + 2 * NDO;
     auto load_nth = [&](int l) {
-        if (l < 4 * NXO) load_x(l / NXO, l % NXO); else load_d((l - 4 * NXO) / NDO, (l - 4 * NXO) % NDO);
+        if (l < NXL) load_x(l / NXO, l % NXO); else load_d((l - NXL) / NDO, (l - NXL) % NDO);
     };
 
-    // store addresses (floats): plane of (buf, pos) + half * 256 + column * 4 + ks, this
-    // thread's left tile is reduction step ks = pr of half 0, its right tile of half 1
     const int wofs = ch * 4 + pr;
-    float tc[4][6];
+    float tc[2][6];                                   // rows 2*PH, 2*PH+1 of B^T d
     auto xform_col = [&](int j) {
-        const float d0 = xr[0][j], d1 = xr[1][j], d2 = xr[2][j], d3 = xr[3][j];
-        tc[0][j] = d0 - d2;
-        tc[1][j] = d1 + d2;
-        tc[2][j] = d2 - d1;
-        tc[3][j] = d1 - d3;
+        // xr[0..2] = patch rows PH .. PH+2
+        if (PH == 0) {
+            tc[0][j] = xr[0][j] - xr[2][j];           // d0 - d2
+            tc[1][j] = xr[1][j] + xr[2][j];           // d1 + d2
+        } else {
+            tc[0][j] = xr[1][j] - xr[0][j];           // d2 - d1
+            tc[1][j] = xr[0][j] - xr[2][j];           // d1 - d3
+        }
     };
-    auto xform_row_store = [&](int buf, int i, int h) {
-        const float t0 = tc[i][2 * h + 0], t1 = tc[i][2 * h + 1], t2 = tc[i][2 * h + 2], t3 = tc[i][2 * h + 3];
-        float *o = Bs + (buf * 16 + 4 * i) * kWvPlane + h * 256 + wofs;
+    auto xform_row_store = [&](int buf, int il, int h) {
+        const float t0 = tc[il][2 * h + 0], t1 = tc[il][2 * h + 1], t2 = tc[il][2 * h + 2], t3 = tc[il][2 * h + 3];
+        float *o = Bs + (buf * 16 + 4 * (2 * PH + il)) * kWvPlane + h * 256 + wofs;
         o[0 * kWvPlane] = t0 - t2;
         o[1 * kWvPlane] = t1 + t2;
         o[2 * kWvPlane] = t2 - t1;
         o[3 * kWvPlane] = t1 - t3;
     };
     float bsum = 0.f;
-    auto dyform_row_store = [&](int buf, int i, int h) {
+    auto dyform_row_store = [&](int buf, int il, int h) {
         const float y00 = dr[0][2 * h], y01 = dr[0][2 * h + 1], y10 = dr[1][2 * h], y11 = dr[1][2 * h + 1];
+        const int i = 2 * PH + il;
         float t0, t1;       // row i of |A| dy (row 3 without its sign)
         if (i == 0) { t0 = y00; t1 = y01; }
         else if (i == 1) { t0 = y00 + y10; t1 = y01 + y11; }
@@ -457,15 +468,15 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
         o[3 * kWvPlane] = t1;                          // column 3 without its sign
     };
 
-    floatx16 acc[16];
+    floatx16 acc[8];                                  // positions 8*PH + p
 #pragma unroll
-    for (int p = 0; p < 16; ++p)
+    for (int p = 0; p < 8; ++p)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
 
-    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
-    const float *const rdA = As + lhi * 256 + (wm0 + l32) * 4;
-    const float *const rdB = Bs + lhi * 256 + (wn0 + l32) * 4;
+    const int wm0 = (wq >> 1) * 32, wn0 = (wq & 1) * 32;
+    const float *const rdA = As + (8 * PH) * kWvPlane + lhi * 256 + (wm0 + l32) * 4;
+    const float *const rdB = Bs + (8 * PH) * kWvPlane + lhi * 256 + (wn0 + l32) * 4;
     floatx4 ao[2][2], bo[2][2];
     auto read_pair = [&](int buf, int pair, int set) {
 #pragma unroll
@@ -482,7 +493,7 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
 #pragma unroll
     for (int j = 0; j < 6; ++j) xform_col(j);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) { xform_row_store(0, q >> 1, q & 1); dyform_row_store(0, q >> 1, q & 1); }
+    for (int q = 0; q < 4; ++q) { xform_row_store(0, q >> 1, q & 1); dyform_row_store(0, q >> 1, q & 1); }
     setup(1);            // steps past the end: every offset out of range, all zeros
 #pragma unroll
     for (int l = 0; l < NLOAD; ++l) load_nth(l);
@@ -490,29 +501,22 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
     lds_barrier_ww();
     read_pair(0, 0, 0);
 
-    // Software pipeline.  A step is 8 groups of 8 back-to-back MFMAs (two positions x
-    // four reduction steps); all other work sits in the gaps between groups, because
-    // every switch from the matrix pipe to other instructions and back costs a
-    // pipeline drain (measured: ~11 cycles per gap on top of ~4-5 per instruction),
-    // so few large gaps beat one small gap per MFMA.  Inside a gap the loads are
-    // spread between the transform pieces: back-to-back vector loads hold the wave
-    // ~55 cycles each, loads a few instructions apart ~25.  Buffer index is a
-    // compile-time constant so every LDS address is a fixed register plus an immediate.
-    //   gap 0   : column half of the input transform of step t+1
-    //   gap 1-2 : row half + LDS stores of step t+1 (one patch row of one tile per
-    //             piece), an image load of step t+2 after every piece
-    //   gap 3-4 : gradient-tile transform + LDS stores, remaining image loads, first
-    //             gradient load
-    //   gap 5   : remaining gradient loads; coordinates and buffer offsets of step t+3
-    //   gap 7   : barrier, first operands of the next step
-    // every gap also reads the LDS operands of the following group
+    // A step of a wave is 4 groups of 8 back-to-back MFMAs (two positions x four
+    // reduction steps).  Gaps before the groups:
+    //   gap 0 : column half of the input transform of step t+1, first image load of t+2
+    //   gap 1 : row half + LDS stores (one piece per row and tile), an image load of step
+    //           t+2 after every piece
+    //   gap 2 : gradient-tile pieces + LDS stores, the remaining image loads
+    //   gap 3 : gradient loads of step t+2, coordinates of step t+3, barrier, first
+    //           operands of the next step
+    // (the image loads after the first are spread as evenly as they go over the 8 pieces)
+    constexpr int XREST = NXL - 1;                    // image loads after the first
     auto step_body = [&](int t, auto bufc) {
         constexpr int buf = decltype(bufc)::value;
-        constexpr int NXL = 4 * NXO;
 #pragma unroll
-        for (int pair = 0; pair < 8; ++pair) {
+        for (int pair = 0; pair < 4; ++pair) {
             const int cur = pair & 1, nxt = cur ^ 1;
-            if (pair + 1 < 8) {
+            if (pair + 1 < 4) {
                 read_pair(buf, pair + 1, nxt);
             } else {
                 lds_barrier_ww();
@@ -521,26 +525,23 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
             if (pair == 0) {
 #pragma unroll
                 for (int j = 0; j < 6; ++j) xform_col(j);
+                __builtin_amdgcn_sched_barrier(0);
+                load_nth(0);
             } else if (pair == 1 || pair == 2) {
 #pragma unroll
                 for (int q = 4 * (pair - 1); q < 4 * pair; ++q) {
-                    xform_row_store(buf ^ 1, q >> 1, q & 1);
+                    if (pair == 1) xform_row_store(buf ^ 1, q >> 1, q & 1);
+                    else dyform_row_store(buf ^ 1, (q - 4) >> 1, q & 1);
                     __builtin_amdgcn_sched_barrier(0);
-                    load_nth(q);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else if (pair == 3 || pair == 4) {
 #pragma unroll
-                for (int q = 4 * (pair - 3); q < 4 * (pair - 2); ++q) {
-                    dyform_row_store(buf ^ 1, q >> 1, q & 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (8 + q < NXL) load_nth(8 + q);
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int l = 1 + q * XREST / 8; l < 1 + (q + 1) * XREST / 8; ++l) {
+                        load_nth(l);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
-                if (pair == 4) load_nth(NXL);
-            } else if (pair == 5) {
+            } else {
 #pragma unroll
-                for (int l = NXL + 1; l < NLOAD; ++l) {
+                for (int l = NXL; l < NLOAD; ++l) {
                     load_nth(l);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -562,13 +563,25 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
         step_body(t + 1, IntC<1>());
     }
 
-    // ---- bias gradient: every tile of the range went through bsum exactly once ----
-    if (a.bias_part != nullptr && ct == 0) {
+    // ---- bias gradient: every tile of the range went through bsum exactly once (PH 0) ----
+    if (PH == 0 && a.bias_part != nullptr && ct == 0) {
         float v = bsum;
         v += __shfl_xor(v, 1);
         v += __shfl_xor(v, 2);
         if (pr == 0 && kok) a.bias_part[split * a.K + k] = v;
     }
+
+    // ---- PH 1 hands its accumulators over: [quadrant][position][v][lane] ----
+    __syncthreads();                                  // every wave is done with the operand buffers
+    float *const xch = lds + (wq * 8) * 16 * 64 + lane;
+    if (PH == 1) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xch[(p * 16 + v) * 64] = acc[p][v];
+    }
+    __syncthreads();
+    if (PH == 1) return;
 
     // ---- epilogue: dg = G^T M G in registers (index-3 rows / columns enter with a
     // minus sign, see above), partial 3x3 gradients out ----
@@ -582,7 +595,8 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
         float tt[3][4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+            const float m0 = acc[0 + j][v], m1 = acc[4 + j][v];
+            const float m2 = xch[((0 + j) * 16 + v) * 64], m3 = xch[((4 + j) * 16 + v) * 64];
             const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
             tt[0][j] = m0 + hs;
             tt[1][j] = hd;
@@ -597,6 +611,15 @@ __global__ __launch_bounds__(256, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
             o[3 * r + 2] = hs - tt[r][3];
         }
     }
+}
+
+template <bool ODD>
+__global__ __launch_bounds__(512, 1) void wino_wgrad_vec_kernel(WinoWgradArgs a)
+{
+    extern __shared__ float lds[];
+    // both halves run the same sequence of barriers
+    if (threadIdx.x < 256) wino_wgrad_vec_body<ODD, 0>(a, lds);
+    else wino_wgrad_vec_body<ODD, 1>(a, lds);
 }
 
 int wino_wgrad_tile() { return kWwKB; }
@@ -621,9 +644,9 @@ hipError_t launch_wino_wgrad(const WinoWgradArgs &a, hipStream_t s)
     if (a.mode == 0)
         hipLaunchKernelGGL(wino_wgrad_kernel, grid, dim3(256), kWwLdsBytes, s, a);
     else if (a.mode == 1)
-        hipLaunchKernelGGL(wino_wgrad_vec_kernel<false>, grid, dim3(256), kWvLdsBytes, s, a);
+        hipLaunchKernelGGL(wino_wgrad_vec_kernel<false>, grid, dim3(512), kWvLdsBytes, s, a);
     else
-        hipLaunchKernelGGL(wino_wgrad_vec_kernel<true>, grid, dim3(256), kWvLdsBytes, s, a);
+        hipLaunchKernelGGL(wino_wgrad_vec_kernel<true>, grid, dim3(512), kWvLdsBytes, s, a);
     return hipGetLastError();
 }
 
