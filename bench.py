@@ -52,7 +52,8 @@ def executed_flops(L, P, Q, op, algo):
         return 32.0 * L.N * th * tw * L.K * cq
     th, tw = (-(-L.H // 2), -(-L.W // 2)) if op == "bwd_data" else (-(-P // 2), -(-Q // 2))
     nsub = -(-L.R // 3) * -(-L.S // 3)        # 3x3 sub-filters of a larger filter
-    return 32.0 * L.N * th * tw * L.K * L.C * nsub
+    c = -(-L.C // 8) * 8 if op == "fwd" else L.C      # forward reduces over whole 8-channel chunks
+    return 32.0 * L.N * th * tw * L.K * c * nsub
 
 
 def main() -> int:

@@ -238,7 +238,13 @@ bool wino_applicable(const Geom &g, conv2d_op op)
     if (g.R < 3 || g.S < 3 || g.R > 6 || g.S > 6) return false;
     if (g.ph > g.R - 1 || g.pw > g.S - 1) return false;
     const int cin = op == CONV2D_FWD ? g.C : g.K;
-    if (cin % wino_chan_chunk() != 0) return false;
+    // the reduction channels come in chunks of 8; only the tile-pair kernel (3x3, pad_w 1,
+    // even width and tile row) also takes a ragged last chunk
+    if (cin % wino_chan_chunk() != 0) {
+        const int win = op == CONV2D_FWD ? g.W : g.Q, wout = op == CONV2D_FWD ? g.Q : g.W;
+        const int pw = op == CONV2D_FWD ? g.pw : g.S - 1 - g.pw;
+        if (!(g.R == 3 && g.S == 3 && pw == 1 && win % 2 == 0 && ceil_div(wout, 2) % 2 == 0)) return false;
+    }
     const int64_t in_elems = op == CONV2D_FWD ? (int64_t)g.N * g.C * g.H * g.W
                                               : (int64_t)g.N * g.K * g.P * g.Q;
     return in_elems * 4 < (int64_t(1) << 31);   // buffer offsets: see winograd.hip
@@ -257,7 +263,7 @@ WinoPlan plan_wino(const Geom &g, conv2d_op op)
     p.pad_h = fwd ? g.ph : g.R - 1 - g.ph;
     p.pad_w = fwd ? g.pw : g.S - 1 - g.pw;
     p.nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);     // 3x3 sub-filters of the filter
-    p.Cpad = p.nsub * p.Cin;
+    p.Cpad = p.nsub * round_up(p.Cin, wino_chan_chunk());   // (a ragged Cin only with nsub == 1)
     p.Kpad = round_up(p.Kout, wino_filter_tile());
     p.TH = ceil_div(p.Hout, 2);
     p.TW = ceil_div(p.Wout, 2);
@@ -347,6 +353,12 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         // R*S*4 direct ones; the sub-filters of 4x4 / 4x5 filters are mostly padding
         const int nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);
         const bool pays = 4 * nsub * 14 <= g.R * g.S * 10;
+        // a first layer (a handful of channels into many filters, one chunk per tile): bound
+        // by writing its output, which the tile-pair kernel does at a better rate than the
+        // gather kernel's two-tile pipeline
+        if (wino_ok && op == CONV2D_FWD && g.C <= 8 && g.K >= 32 && g.R == 3 && g.S == 3 && g.pw == 1 &&
+            g.W % 2 == 0 && ceil_div(g.Q, 2) % 2 == 0)
+            return CONV2D_ALGO_WINOGRAD;
         return (wino_ok && cin >= 32 && pays) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
     }
     case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;

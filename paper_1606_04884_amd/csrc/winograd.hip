@@ -609,7 +609,10 @@ __global__ __launch_bounds__(256, 1) void wino_fused_kernel(WinoArgs a)
 // V planes (two buffers) + the exchange area of the epilogue
 constexpr int kWinoPairLdsBytes = 2 * 16 * kWinoCB * kWinoTB * (int)sizeof(float) + 4 * 2 * 8 * 64 * 16;
 
-template <int PH>
+// RAGGED: the channel count is not a multiple of the 8-channel chunk (first layers): the
+// missing channels of the last chunk are fetched with offsets outside the buffer (zeros;
+// their rows of U are zero too).
+template <int PH, bool RAGGED>
 __device__ __forceinline__ void wino_pair_body(const WinoArgs &a, float *lds)
 {
     constexpr int KB = kWinoKB, TB = kWinoTB, CB = kWinoCB;
@@ -670,16 +673,19 @@ __device__ __forceinline__ void wino_pair_body(const WinoArgs &a, float *lds)
 
     float xr[3][6];
     floatx4 ar[8];
+    // this lane's channel does not exist in the last chunk (RAGGED only)
+    const uint32_t chbad = (RAGGED && (nchunks - 1) * CB + ch >= a.Cin) ? 0x80000000u : 0u;
     // x load l: part = l / 3 (left dword, 16 bytes, right dword), row = l % 3
     auto load_x = [&](int l, int chunk) {
         const int part = l / 3, i = l - 3 * part;
         const int so = chunk * x_chunk;
+        const uint32_t bad = RAGGED ? (chbad & (chunk == nchunks - 1 ? 0xffffffffu : 0u)) : 0u;
         if (part == 0) {
-            xr[i][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][0], so, 0));
+            xr[i][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][0] | bad, so, 0));
         } else if (part == 2) {
-            xr[i][5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][2], so, 0));
+            xr[i][5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xo[i][2] | bad, so, 0));
         } else {
-            const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xo[i][1], so, 0));
+            const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xo[i][1] | bad, so, 0));
             xr[i][1] = m[0]; xr[i][2] = m[1]; xr[i][3] = m[2]; xr[i][4] = m[3];
         }
     };
@@ -923,8 +929,15 @@ __global__ __launch_bounds__(512, 1) void wino_pair_kernel(WinoArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     // both halves run the same sequence of barriers
-    if (threadIdx.x < 256) wino_pair_body<0>(a, lds);
-    else wino_pair_body<1>(a, lds);
+    if (threadIdx.x < 256) wino_pair_body<0, false>(a, lds);
+    else wino_pair_body<1, false>(a, lds);
+}
+
+__global__ __launch_bounds__(512, 1) void wino_pair_ragged_kernel(WinoArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if (threadIdx.x < 256) wino_pair_body<0, true>(a, lds);
+    else wino_pair_body<1, true>(a, lds);
 }
 
 // Adds the two halves of every tile that a range boundary cut: boundary b lies
@@ -997,9 +1010,15 @@ static hipError_t launch_wino_pair(const WinoArgs &a, int G, hipStream_t s)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_ragged_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
+        if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(wino_pair_kernel, dim3((unsigned)G), dim3(512), kWinoPairLdsBytes, s, a);
+    if (a.Cin % kWinoCB != 0)
+        hipLaunchKernelGGL(wino_pair_ragged_kernel, dim3((unsigned)G), dim3(512), kWinoPairLdsBytes, s, a);
+    else
+        hipLaunchKernelGGL(wino_pair_kernel, dim3((unsigned)G), dim3(512), kWinoPairLdsBytes, s, a);
     return hipGetLastError();
 }
 

@@ -153,6 +153,12 @@ WINO_SHAPES = [
     (2, 16, 7, 10, 24, 3, 3, 1, 1, 0, 1),
     (3, 8, 9, 6, 16, 3, 3, 1, 1, 2, 1),
     G(3, 24, 20, 36, 40, 3, 3, 1, 1),
+    # tile-pair kernel with a ragged last channel chunk: first-layer forward (3 channels in
+    # one chunk), 12 channels (a full chunk and half a chunk), and backward-data over 20 filters
+    G(2, 3, 16, 16, 64, 3, 3, 1, 1),
+    G(3, 12, 20, 24, 40, 3, 3, 1, 1),
+    G(2, 8, 12, 12, 20, 3, 3, 1, 1),
+    G(40, 3, 32, 32, 64, 3, 3, 1, 1),        # more tile blocks than compute units, 3 channels
 ]
 
 
@@ -171,10 +177,12 @@ def test_winograd_parity(geom):
 
 def test_winograd_refused_where_it_does_not_apply():
     dev = torch.device("cuda:0")
-    geom = G(1, 4, 8, 8, 8, 3, 3, 1, 1)      # C not a multiple of the channel chunk
-    x = torch.zeros((1, 4, 8, 8), device=dev)
+    # C not a multiple of the channel chunk on an odd-width map (the tile-pair kernel, which
+    # takes a ragged chunk, needs an even width)
+    geom = G(1, 4, 9, 9, 8, 3, 3, 1, 1)
+    x = torch.zeros((1, 4, 9, 9), device=dev)
     w = torch.zeros((8, 4, 3, 3), device=dev)
-    y = torch.zeros((1, 8, 8, 8), device=dev)
+    y = torch.zeros((1, 8, 9, 9), device=dev)
     with pytest.raises(B.Conv2dError) as e:
         B.conv2d_fwd(geom, x, w, None, y, algo=B.ALGO_WINOGRAD, ws=B.alloc_workspace(1 << 20))
     assert e.value.status == -3

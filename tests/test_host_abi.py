@@ -135,9 +135,12 @@ def test_algo_choice_rules():
     assert pick(vgg, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
     assert pick(vgg, B.OP_BWD_WEIGHT) == B.ALGO_WINOGRAD
     first = (64, 3, 224, 224, 64, 3, 3, 1, 1, 1, 1)              # 3 input channels
-    assert pick(first, B.OP_FWD) == B.ALGO_IGEMM
+    assert pick(first, B.OP_FWD) == B.ALGO_WINOGRAD             # tile-pair kernel, one ragged chunk
     assert pick(first, B.OP_BWD_DATA) == B.ALGO_IGEMM
     assert pick(first, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+    assert pick((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # odd width: no pairs
+    assert pick((64, 3, 224, 224, 16, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # few filters
+    assert B.conv2d_workspace_bytes((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD, B.ALGO_WINOGRAD) == 0
     five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5: four 3x3 sub-filters
     assert pick(five, B.OP_FWD) == B.ALGO_WINOGRAD
     assert pick(five, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
