@@ -442,6 +442,35 @@ PwWgradPlan plan_pw_wgrad(const Geom &g)
     return p;
 }
 
+// Backward-weight of a small stride-1 filter over very few channels (C*R*S <= 32 taps:
+// first layers) with the taps form of the pointwise kernel; same split plan.
+PwWgradPlan plan_tap_wgrad(const Geom &g)
+{
+    PwWgradPlan p = {};
+    const int taps = g.C * g.R * g.S, PQ = g.P * g.Q;
+    if (g.sh != 1 || g.sw != 1 || g.R * g.S == 1 || taps > 32 || g.K > 128) return p;
+    if (g.Q % 4 != 0 || PQ < 16) return p;
+    if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31) || (int64_t)g.N * g.K * PQ * 4 >= (int64_t(1) << 31))
+        return p;
+    p.ok = true;
+    p.quads = g.N * (PQ / 4);
+    const int total_steps = (p.quads + 3) / 4;
+    int NJ, BT;
+    pw_wgrad_shape(taps, g.K, PQ, &NJ, &BT, &p.phases);
+    p.tiles_c = NJ;
+    int per_cu = 8 / (NJ * p.phases);
+    if (per_cu < 1) per_cu = 1;
+    int splits = 256 * per_cu;
+    if (splits > total_steps / (4 * p.phases)) splits = total_steps / (4 * p.phases);
+    if (splits < 1) splits = 1;
+    p.steps_per_split = ceil_div(total_steps, splits);
+    p.splits = ceil_div(total_steps, p.steps_per_split);
+    p.part_bytes = align_up((size_t)p.splits * g.K * taps * sizeof(float), 256);
+    p.bias_bytes = align_up((size_t)p.splits * g.K * sizeof(float), 256);
+    p.total_bytes = p.part_bytes + p.bias_bytes;
+    return p;
+}
+
 // first-layer backward-data on the vector ALU: 3x3, stride 1, pad_w 1, C <= 4, rows of
 // 4-pixel groups with aligned 16-byte accesses
 bool smallc_bwd_ok(const Geom &g, const float *dy, const float *dx)
@@ -655,9 +684,11 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
     case CONV2D_BWD_WEIGHT: {
         // the streaming pointwise kernel is taken when the pointers allow it: room for either
-        const size_t generic = plan_wgrad(g).total_bytes;
-        const PwWgradPlan pw = plan_pw_wgrad(g);
-        return pw.ok && pw.total_bytes > generic ? pw.total_bytes : generic;
+        size_t bytes = plan_wgrad(g).total_bytes;
+        const PwWgradPlan pw = plan_pw_wgrad(g), tw = plan_tap_wgrad(g);
+        if (pw.ok && pw.total_bytes > bytes) bytes = pw.total_bytes;
+        if (tw.ok && tw.total_bytes > bytes) bytes = tw.total_bytes;
+        return bytes;
     }
     default: return 0;
     }
@@ -952,6 +983,30 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
         if (rc) return rc;
         const BiasJob bj = {dbias ? bias_part : nullptr, dbias, g.K, pw.splits, accumulate};
         return launch_status(launch_split_reduce(part, dw, (int64_t)g.K * g.C, pw.splits, scale, accumulate, bj, s));
+    }
+
+    const PwWgradPlan tw = plan_tap_wgrad(g);
+    if (tw.ok && ((uintptr_t)dy & 15) == 0) {
+        if (!ws || ws_bytes < tw.total_bytes) return CONV2D_ERR_WORKSPACE;
+        float *part = (float *)ws;
+        float *bias_part = (float *)((char *)ws + tw.part_bytes);
+        const int taps = g.C * g.R * g.S, PQ = g.P * g.Q;
+        PwWgradArgs a = {};
+        a.x = x; a.dy = dy; a.part = part; a.bias_part = dbias ? bias_part : nullptr;
+        a.N = g.N; a.C = taps; a.K = g.K; a.HW = PQ;
+        a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+        a.dy_bytes = (int32_t)((int64_t)g.N * g.K * PQ * 4);
+        a.quads = tw.quads; a.steps_per_split = tw.steps_per_split; a.splits = tw.splits;
+        a.tiles_c = tw.tiles_c; a.phases = tw.phases;
+        a.div_QW = make_fastdiv((uint32_t)(PQ / 4));
+        a.xC = g.C; a.xH = g.H; a.xW = g.W; a.tP = g.P; a.Qd = g.Q; a.tR = g.R; a.tS = g.S; a.tph = g.ph; a.tpw = g.pw;
+        a.div_Q = make_fastdiv((uint32_t)g.Q);
+        a.div_RS = make_fastdiv((uint32_t)(g.R * g.S));
+        a.div_S = make_fastdiv((uint32_t)g.S);
+        rc = launch_status(launch_tap_wgrad(a, s));
+        if (rc) return rc;
+        const BiasJob bj = {dbias ? bias_part : nullptr, dbias, g.K, tw.splits, accumulate};
+        return launch_status(launch_split_reduce(part, dw, (int64_t)g.K * taps, tw.splits, scale, accumulate, bj, s));
     }
 
     const WgradPlan p = plan_wgrad(g);

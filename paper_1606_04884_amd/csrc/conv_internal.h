@@ -272,7 +272,12 @@ struct PwWgradArgs {
     int32_t splits;
     int32_t tiles_c, phases;   // column groups x pixel phases = waves per workgroup (pw_wgrad_shape)
     FastDiv div_QW;            // by HW/4
+    // taps form (launch_tap_wgrad): a small stride-1 R x S filter over xC channels of an
+    // xH x xW image; C above is then the number of taps xC*R*S and HW = tP * Qd (dy plane)
+    int32_t xC, xH, xW, tP, Qd, tR, tS, tph, tpw;
+    FastDiv div_Q, div_RS, div_S;
 };
+hipError_t launch_tap_wgrad(const PwWgradArgs &a, hipStream_t s);
 void pw_wgrad_shape(int C, int K, int HW, int *NJ, int *BT, int *PH);
 hipError_t launch_pw_wgrad(const PwWgradArgs &a, hipStream_t s);
 

@@ -414,7 +414,14 @@ hipError_t launch_pw_stream(const PwArgs &a, hipStream_t s)
 // through LDS at the end, in phase order.  The pixel axis is cut into `splits` ranges;
 // each workgroup writes its partial K x C product (and column group 0 its partial bias
 // gradient), added up by the split-reduce kernel.
-template <int AT, int BT>
+//
+// TAPS: the same kernel for a small stride-1 filter over very few channels (first layers:
+// C*R*S <= 32).  The B rows are then the taps (c, r, s) of the lowered matrix instead of
+// channels: lane l%16 owns tap t and fetches x[n][c_t][p + r_t - pad_h][q + s_t - pad_w + e],
+// e = 0..3, with four dword loads (the shifted vector is not 16-byte aligned and its ends
+// may fall into the padding: each element carries its own validity); dy, the accumulators,
+// the phases and the output part[s][k][t] (= KCRS order) are unchanged.  Needs Q % 4 == 0.
+template <int AT, int BT, bool TAPS>
 __global__ __launch_bounds__(512) void pw_wgrad_kernel(PwWgradArgs a)
 {
     constexpr int R = AT + BT <= 4 ? 4 : (AT + BT <= 6 ? 3 : 2);     // 16-pixel steps in flight
@@ -437,12 +444,25 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(PwWgradArgs a)
         kbad[ai] = k < a.K ? 0u : 0x80000000u;
         koff[ai] = (uint32_t)(k * a.HW);
     }
+    int tdr[BT], tds[BT];             // TAPS: row / column displacement of this lane's tap
 #pragma unroll
     for (int bj = 0; bj < BT; ++bj) {
         const int c = (nj * BT + bj) * 16 + l16;
         cbad[bj] = c < a.C ? 0u : 0x80000000u;
-        coff[bj] = (uint32_t)(c * a.HW);
+        if (TAPS) {
+            const int cc = c < a.C ? c : 0;
+            const int ch = (int)fast_div((uint32_t)cc, a.div_RS), rs = cc - ch * a.tR * a.tS;
+            const int r = (int)fast_div((uint32_t)rs, a.div_S), t = rs - r * a.tS;
+            tdr[bj] = r - a.tph;
+            tds[bj] = t - a.tpw;
+            coff[bj] = (uint32_t)(ch * a.xH * a.xW);
+        } else {
+            tdr[bj] = 0;
+            tds[bj] = 0;
+            coff[bj] = (uint32_t)(c * a.HW);
+        }
     }
+    const int xCHW = a.xC * a.xH * a.xW;      // TAPS: image stride of x
     const int QW = a.HW >> 2;
     const int KHW = a.K * a.HW, CHW = a.C * a.HW;
     const int total_steps = (a.quads + 3) >> 2;
@@ -473,10 +493,28 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(PwWgradArgs a)
         for (int ai = 0; ai < AT; ++ai)
             ar[u][ai] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
                                                         rs_dy, (((dyb + koff[ai]) * 4u) & 0x7fffffffu) | qbad | kbad[ai], 0, 0));
+        if (TAPS) {
+            const int p = (int)fast_div((uint32_t)pp, a.div_Q), q0 = pp - p * a.Qd;
+            const int img = pn * xCHW;
 #pragma unroll
-        for (int bj = 0; bj < BT; ++bj)
-            br[u][bj] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                        rs_x, (((xb + coff[bj]) * 4u) & 0x7fffffffu) | qbad | cbad[bj], 0, 0));
+            for (int bj = 0; bj < BT; ++bj) {
+                const int row = p + tdr[bj], col0 = q0 + tds[bj];
+                const uint32_t rbad = ((unsigned)row < (unsigned)a.xH ? 0u : 0x80000000u) | qbad | cbad[bj];
+                const int base = img + (int)coff[bj] + row * a.xW + col0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t ebad = (unsigned)(col0 + e) < (unsigned)a.xW ? 0u : 0x80000000u;
+                    br[u][bj][e] = __builtin_bit_cast(
+                        float, __builtin_amdgcn_raw_buffer_load_b32(
+                                   rs_x, (((uint32_t)(base + e) * 4u) & 0x7fffffffu) | rbad | ebad, 0, 0));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int bj = 0; bj < BT; ++bj)
+                br[u][bj] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                            rs_x, (((xb + coff[bj]) * 4u) & 0x7fffffffu) | qbad | cbad[bj], 0, 0));
+        }
         pstep += PH;
         pp += adv;
         const bool wrap = pp >= a.HW;
@@ -618,17 +656,17 @@ void pw_wgrad_shape(int C, int K, int HW, int *NJ, int *BT, int *PH)
     *PH = ph;
 }
 
-template <int AT, int BT>
+template <int AT, int BT, bool TAPS = false>
 static hipError_t launch_pw_wgrad_t(const PwWgradArgs &a, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_wgrad_kernel<AT, BT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_wgrad_kernel<AT, BT, TAPS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwWgradLdsMax);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((pw_wgrad_kernel<AT, BT>), grid, block, lds_bytes, s, a);
+    hipLaunchKernelGGL((pw_wgrad_kernel<AT, BT, TAPS>), grid, block, lds_bytes, s, a);
     return hipGetLastError();
 }
 
@@ -641,6 +679,27 @@ static hipError_t launch_pw_wgrad_bt(const PwWgradArgs &a, int BT, dim3 grid, di
     case 3: return launch_pw_wgrad_t<AT, 3>(a, grid, block, lds_bytes, s);
     case 4: return launch_pw_wgrad_t<AT, 4>(a, grid, block, lds_bytes, s);
     default: return hipErrorInvalidValue;
+    }
+}
+
+// TAPS form: a.C = number of taps (<= 32: one column group of two 16-tap tiles), a.HW = P*Q
+hipError_t launch_tap_wgrad(const PwWgradArgs &a, hipStream_t s)
+{
+    if (a.K < 1 || a.K > 128 || a.C < 1 || a.C > 32 || a.splits < 1 || a.Qd % 4 != 0 || a.HW != a.tP * a.Qd)
+        return hipErrorInvalidValue;
+    int NJ, BT, PH;
+    pw_wgrad_shape(a.C, a.K, a.HW, &NJ, &BT, &PH);
+    if (NJ != 1 || BT != 2 || a.tiles_c != NJ || a.phases != PH || a.HW < 16 * PH) return hipErrorInvalidValue;
+    const int AT = pw_wgrad_at(a.K);
+    const dim3 grid((unsigned)a.splits), block((unsigned)(64 * NJ * PH));
+    const size_t lds_bytes = (size_t)(PH - 1) * (NJ * AT * BT * 4 + AT) * 64 * sizeof(float);
+    switch (AT) {
+    case 1: return launch_pw_wgrad_t<1, 2, true>(a, grid, block, lds_bytes, s);
+    case 2: return launch_pw_wgrad_t<2, 2, true>(a, grid, block, lds_bytes, s);
+    case 3: return launch_pw_wgrad_t<3, 2, true>(a, grid, block, lds_bytes, s);
+    case 4: return launch_pw_wgrad_t<4, 2, true>(a, grid, block, lds_bytes, s);
+    case 6: return launch_pw_wgrad_t<6, 2, true>(a, grid, block, lds_bytes, s);
+    default: return launch_pw_wgrad_t<8, 2, true>(a, grid, block, lds_bytes, s);
     }
 }
 

@@ -371,3 +371,36 @@ def test_strided_first_layer_backward_takes_winograd_by_default():
     for name in ("dx", "dw", "db"):
         assert np.array_equal(a[name], c[name]), name
     assert np.array_equal(a["y"], d["y"])
+
+
+# backward-weight of small stride-1 filters over very few channels (C*R*S <= 32 taps, Q % 4
+# == 0): the taps form of the streaming backward-weight kernel.  Filter-tile counts 1, 2, 3,
+# 4, 6, 8; 3x3 and 5x5 and 2x3 filters; paddings 0, 1, 2; rows shorter than a 16-pixel step.
+TAP_WGRAD_SHAPES = [
+    G(2, 3, 16, 16, 8, 3, 3, 1, 1),
+    (3, 3, 12, 20, 64, 3, 3, 1, 1, 1, 1),
+    (2, 2, 9, 8, 40, 3, 3, 1, 1, 1, 1),
+    (2, 1, 8, 12, 24, 5, 5, 1, 1, 2, 2),
+    G(4, 3, 32, 32, 96, 3, 3, 1, 1),
+    (2, 3, 10, 14, 128, 3, 3, 1, 1, 0, 0),
+    (3, 2, 6, 6, 16, 3, 3, 1, 1, 2, 2),
+    (2, 4, 7, 9, 20, 2, 3, 1, 1, 0, 1),
+    G(9, 3, 40, 40, 64, 3, 3, 1, 1),         # enough pixels for several splits and all 8 phases
+]
+
+
+@pytest.mark.parametrize("geom", TAP_WGRAD_SHAPES, ids=[("x".join(map(str, g))) for g in TAP_WGRAD_SHAPES])
+def test_first_layer_backward_weight_taps(geom):
+    x, w, b, dy = random_layer(geom, 9500 + sum(geom))
+    print("geom", geom, flush=True)
+    assert B.conv2d_pick_algo(geom, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_AUTO, passes=("bwd_weight",))
+    dw, db = oracle.bwd_weight(geom, x, dy)
+    assert np.isfinite(got["dw"]).all()
+    assert max_err_ratio(got["dw"], dw) <= TOL_IGEMM
+    assert max_err_ratio(got["db"], db) <= TOL_IGEMM
+    dw0 = synth.normal(dw.shape, 28, std=2.0)
+    db0 = synth.normal(db.shape, 29, std=2.0)
+    got = gpu_layer(geom, x, w, b, dy, scale=0.125, dw0=dw0.copy(), db0=db0.copy(), passes=("bwd_weight",))
+    assert max_err_ratio(got["dw"], 0.125 * dw + dw0) <= TOL_IGEMM
+    assert max_err_ratio(got["db"], 0.125 * db + db0) <= TOL_IGEMM
