@@ -328,6 +328,7 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
 }
 
 bool s2d_applicable(const Geom &g, conv2d_op op);     // strided layer as a stride-1 3x3 layer, below
+bool tap_stream_ok(const Geom &g);                    // forward pass with the filter bank in LDS, below
 
 int resolve_algo(const Geom &g, conv2d_op op, int algo)
 {
@@ -353,9 +354,11 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         // R*S*4 direct ones; the sub-filters of 4x4 / 4x5 filters are mostly padding
         const int nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);
         const bool pays = 4 * nsub * 14 <= g.R * g.S * 10;
-        // a first layer (a handful of channels into many filters, one chunk per tile): bound
-        // by writing its output, which the tile-pair kernel does at a better rate than the
-        // gather kernel's two-tile pipeline
+        // a first layer (a handful of channels into many filters) is bound by writing its
+        // output.  Up to four channels the taps form of the streaming kernel does that best
+        // (the filter bank in LDS, 16-byte stores); else the tile-pair Winograd kernel (one
+        // chunk per tile) does it at a better rate than the gather kernel's two-tile pipeline
+        if (op == CONV2D_FWD && g.C <= 4 && tap_stream_ok(g)) return CONV2D_ALGO_IGEMM;
         if (wino_ok && op == CONV2D_FWD && g.C <= 8 && g.K >= 32 && g.R == 3 && g.S == 3 && g.pw == 1 &&
             g.W % 2 == 0 && ceil_div(g.Q, 2) % 2 == 0)
             return CONV2D_ALGO_WINOGRAD;
@@ -402,6 +405,37 @@ void fill_pw_args(PwArgs &a, const Geom &g, conv2d_op op, const float *in)
     a.div_fast = make_fastdiv((uint32_t)(fwd ? a.D : a.Rout));
     a.ngroup = 1;
     for (int i = 0; i <= kMaxGroups; ++i) a.r0[i] = i == 0 ? 0 : a.Rout;
+}
+
+// Forward pass of a layer whose filter bank (K x C*R*S) fits in LDS, K <= 128: the taps
+// form of the streaming kernel
+bool tap_stream_ok(const Geom &g)
+{
+    if (g.R * g.S == 1 || g.R > 16 || g.S > 16 || g.K > 128) return false;
+    if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31)) return false;
+    if ((int64_t)g.N * g.K * g.P * g.Q * 4 >= (int64_t(1) << 31)) return false;
+    return pw_stream_lds_bytes(g.K, g.C * g.R * g.S) != 0;
+}
+
+void fill_tap_args(PwArgs &a, const Geom &g, const float *x)
+{
+    a.in = x;
+    a.D = g.C * g.R * g.S;
+    a.Rout = g.K;
+    a.HW = g.P * g.Q;
+    a.M = g.N * a.HW;
+    a.ntiles = ceil_div(a.M, 32);
+    a.in_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+    a.out_bytes = (int32_t)((int64_t)a.M * a.Rout * 4);
+    a.w_row_stride = a.D;
+    a.w_depth_stride = 1;
+    a.div_HW = make_fastdiv((uint32_t)a.HW);
+    a.div_fast = make_fastdiv((uint32_t)a.D);
+    a.ngroup = 1;
+    for (int i = 0; i <= kMaxGroups; ++i) a.r0[i] = i == 0 ? 0 : a.Rout;
+    a.tC = g.C; a.tH = g.H; a.tW = g.W; a.tR = g.R; a.tS = g.S;
+    a.tsh = g.sh; a.tsw = g.sw; a.tph = g.ph; a.tpw = g.pw; a.tQ = g.Q;
+    a.div_tQ = make_fastdiv((uint32_t)g.Q);
 }
 
 // Pointwise backward-weight as a streaming product (pointwise.hip): plan of the split
@@ -716,6 +750,13 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
         pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y;
         pa.fill_vec = g.C % 4 == 0 && ((uintptr_t)w & 15) == 0;
         return launch_status(launch_pw_stream(pa, s));
+    }
+    if (tap_stream_ok(g)) {
+        PwArgs pa = {};
+        fill_tap_args(pa, g, x);
+        pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y;
+        pa.fill_vec = pa.D % 4 == 0 && ((uintptr_t)w & 15) == 0;
+        return launch_status(launch_tap_stream(pa, s));
     }
     float *wt = (float *)ws;
     DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);

@@ -249,10 +249,16 @@ struct PwArgs {
     int32_t r0[kMaxGroups + 1];
     int32_t w_row_stride, w_depth_stride;
     int32_t fill_vec;                    // A may be fetched as aligned 16-byte vectors along its contiguous axis
+    int32_t wide_store;                  // set by the launcher: 16-byte stores through the LDS staging area
     int32_t D, Rout, HW, M;              // M = N*HW pixels
     int32_t ntiles;                      // 32-pixel tiles
     FastDiv div_HW, div_fast;            // div_fast: by D if w_depth_stride == 1, else by Rout
+    // taps form (launch_tap_stream): forward pass of an R x S layer; D = tC*tR*tS taps over a
+    // tC x tH x tW input, HW = P*Q output pixels per image, tQ = Q
+    int32_t tC, tH, tW, tR, tS, tsh, tsw, tph, tpw, tQ;
+    FastDiv div_tQ;
 };
+hipError_t launch_tap_stream(const PwArgs &a, hipStream_t s);
 // largest rows x depth product the kernel keeps in LDS, in bytes; 0 if the shape does not fit
 size_t pw_stream_lds_bytes(int Rout, int D);
 hipError_t launch_pw_stream(const PwArgs &a, hipStream_t s);

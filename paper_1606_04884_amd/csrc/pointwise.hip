@@ -34,7 +34,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // so that the fill (consecutive depths or rows from consecutive threads) spreads
 // over the banks.
 constexpr int kPwBlk = 260;      // floats per block: 64 lanes x 4, + 4
-constexpr int kPwRing = 8;       // 8-channel groups in flight per wave (32 loads)
+constexpr int kPwRing = 8;       // 8-channel groups in flight per wave (32 loads); RING below
 constexpr int kPwThreads = 512;  // eight waves share one copy of A in LDS, two per SIMD
 constexpr int kPwWaves = kPwThreads / 64;
 constexpr size_t kPwLdsMax = 160 * 1024;
@@ -53,11 +53,25 @@ size_t pw_stream_lds_bytes(int Rout, int D)
     const int MI = pw_row_tiles(Rout);
     if (MI == 0) return 0;
     // A blocks, bias per row, and (grouped outputs) a 16-byte destination record per row
-    const size_t bytes = ((size_t)((D + 7) / 8) * MI * kPwBlk + 32 * MI + 4 * 32 * MI) * sizeof(float);
+    // (and, for the taps form, 8 bytes per depth index)
+    const size_t bytes = ((size_t)((D + 7) / 8) * MI * kPwBlk + 32 * MI + 4 * 32 * MI + 2 * 8 * ((D + 7) / 8)) * sizeof(float);
     return bytes <= kPwLdsMax ? bytes : 0;
 }
 
-template <int MI, bool GROUPED>
+// Wide stores: a wave passes each 32 x 32 block of results through a private LDS area
+// (rows 40 floats apart) so that a lane ends up with four consecutive pixels of one row.
+constexpr int kPwStageStride = 40;
+constexpr size_t kPwStageBytes = (size_t)kPwWaves * 32 * kPwStageStride * sizeof(float);
+
+//
+// TAPS: the same kernel as the forward pass of a layer whose whole filter bank fits in LDS
+// (K*C*R*S floats: first layers, the inception 5x5): the depth index d then runs over the
+// taps (c, r, t) of the lowered matrix, and the dword a lane fetches for depth d is
+// in[n][c][p*stride - pad_h + r][q*stride - pad_w + t] of its output pixel (p, q).  The
+// element offset and (r, t) of every tap sit in an LDS table; the two half-waves read their
+// two entries (a broadcast read each), and a lane tests a tap against the set of window
+// rows and columns that lie inside its image, worked out once per tile.
+template <int MI, bool GROUPED, bool TAPS, int RING>
 __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -66,7 +80,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     const int G8 = (a.D + 7) >> 3;
-    const int Gp = (G8 + kPwRing - 1) / kPwRing * kPwRing;     // see the ring below
+    const int Gp = (G8 + RING - 1) / RING * RING;     // see the ring below
     float *biasl = lds + G8 * MI * kPwBlk;       // [32 * MI]
     // grouped outputs: row r -> {address of its first pixel in image 0, image stride}
     struct RowDst {
@@ -74,6 +88,9 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         int32_t img_stride, unused;
     };
     RowDst *rowdst = reinterpret_cast<RowDst *>(biasl + 32 * MI);      // [32 * MI]
+    // TAPS: depth d -> {byte offset of tap (c, r, t) from the window origin, 1 << r | 1 << (16 + t)}
+    int2 *taptab = reinterpret_cast<int2 *>(biasl + 32 * MI + 4 * 32 * MI);     // [8 * G8]
+    float *stage = biasl + 32 * MI + 4 * 32 * MI + 16 * G8 + wave * (32 * kPwStageStride);   // a.wide_store
 
     // tiles gw, gw + NW, ... belong to this wave
     const int NW = gridDim.x * kPwWaves;
@@ -107,7 +124,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
     // Only the last group of a tile can hold channels past D; its per-lane invalid bits
     // are kept in four registers and switched on by a wave-uniform mask, which costs one
     // instruction per load.
-    float b[kPwRing][4];
+    float b[RING][4];
     uint32_t lastbad[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) lastbad[e] = ((G8 - 1) * 8 + 2 * e < dlim) ? 0u : 0x80000000u;
@@ -121,14 +138,55 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
             b[u][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, d0 * hwb, 0));
         }
     };
-    uint32_t cur_voff = tile_voff(gw);
-    // the first loads go out before the LDS fill
+    // TAPS: what a tile needs for its loads: the byte offset of the lane's window origin
+    // (negative when the window starts in the padding: such an offset has bit 31 set and is
+    // out of range by itself) and the complement of the lane's set of valid taps, bit r for
+    // window row r and bit 16 + t for window column t.
+    struct TapTile {
+        int base;
+        uint32_t nvalid;
+        uint32_t bad;          // bit 31: this lane has no pixel in the tile
+    };
+    auto range_mask = [](int lo, int hi) -> uint32_t {        // bits lo .. hi-1, lo >= 0, hi <= 16
+        return hi > lo ? ((1u << hi) - 1u) & ~((1u << lo) - 1u) : 0u;
+    };
+    auto tap_tile = [&](int tile) -> TapTile {
+        TapTile tt;
+        const uint32_t m = (uint32_t)(tile * 32 + l32);
+        const bool mv = tile < a.ntiles && m < (uint32_t)a.M;
+        tt.bad = mv ? 0u : 0x80000000u;
+        const uint32_t mm = mv ? m : 0u;
+        const int n = (int)fast_div(mm, a.div_HW), pq = (int)mm - n * a.HW;
+        const int p = (int)fast_div((uint32_t)pq, a.div_tQ), q = pq - p * a.tQ;
+        const int ih0 = p * a.tsh - a.tph, iw0 = q * a.tsw - a.tpw;
+        tt.base = ((n * a.tC * a.tH + ih0) * a.tW + iw0) * 4;
+        const uint32_t rows = range_mask(max(0, -ih0), min(a.tR, a.tH - ih0));
+        const uint32_t cols = range_mask(max(0, -iw0), min(a.tS, a.tW - iw0));
+        tt.nvalid = ~(rows | (cols << 16));
+        return tt;
+    };
+    auto issue_taps = [&](int u, const TapTile &tt, int grp) {
+        const uint32_t is_last = grp == G8 - 1 ? 0xffffffffu : 0u;     // wave-uniform
+        const uint32_t gbad = (grp < G8 ? 0u : 0x80000000u) | tt.bad;
+        const int g = grp < G8 ? grp : 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int2 tp = taptab[g * 8 + 2 * e + lhi];
+            const uint32_t off = (uint32_t)(tt.base + tp.x) | (((uint32_t)tp.y & tt.nvalid) ? 0x80000000u : 0u) |
+                                 ((lastbad[e] & is_last) | gbad);
+            b[u][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
+        }
+    };
+    uint32_t cur_voff = TAPS ? 0u : tile_voff(gw);
+    // the first loads go out before the LDS fill (not TAPS: they need the tap table)
     // (in slot order, and kept in that order: the wait before a slot's first use counts
     // the loads issued after the slot's own)
+    if (!TAPS) {
 #pragma unroll
-    for (int u = 0; u < kPwRing; ++u) {
-        issue(u, cur_voff, u);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int u = 0; u < RING; ++u) {
+            issue(u, cur_voff, u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // ---- A and the bias to LDS ----
@@ -234,17 +292,45 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
             }
         }
     }
+    if (TAPS) {
+        for (int d = tid; d < 8 * G8; d += kPwThreads) {
+            int2 e = make_int2(0, 0);                          // past D: masked by lastbad
+            if (d < a.D) {
+                const int RS = a.tR * a.tS;
+                const int c = d / RS, rs = d - c * RS, r = rs / a.tS, t = rs - r * a.tS;
+                e = make_int2(((c * a.tH + r) * a.tW + t) * 4, (1 << r) | (1 << (16 + t)));
+            }
+            taptab[d] = e;
+        }
+    }
     __syncthreads();
+    TapTile cur_tt = {}, next_tt = {};
+    if (TAPS) {
+        cur_tt = tap_tile(gw);
+#pragma unroll
+        for (int u = 0; u < RING; ++u) {
+            issue_taps(u, cur_tt, u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 
+    // the accumulators start from the bias of their rows (0 without one)
     floatx16 acc[MI];
+    auto init_acc = [&]() {
+        asm volatile("" ::: "memory");
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mi][v] = 0.f;
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 bv = *reinterpret_cast<const floatx4 *>(&biasl[32 * mi + 8 * q + 4 * lhi]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[mi][4 * q + i] = bv[i];
+            }
+    };
+    init_acc();
 
     const __amdgpu_buffer_rsrc_t orsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.out[0], 0, a.out_bytes, 0x00020000);
-    const bool has_bias = GROUPED || a.bias[0] != nullptr;
     auto store_tile = [&](int tile) {
         // the per-row values in LDS are re-read for every tile: kept in registers across
         // the main loop (they never change) they would crowd out the operand ring
@@ -254,37 +340,52 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         const int mm = mv ? m : 0;
         const int n = (int)fast_div((uint32_t)mm, a.div_HW);
         const int p = mm - n * a.HW;
-        if (!GROUPED) {
-            // rows 4*lhi + {0,1,2,3, 8,9,10,11, ...}: a running byte offset, one add per
-            // store; a lane without a pixel starts outside the buffer and stays there
-            uint32_t off = mv ? (uint32_t)((n * a.Rout + 4 * lhi) * a.HW + p) * 4u : 0x80000000u;
+        if (!GROUPED && a.wide_store) {
+            // lane -> (row srow of an 8-row slab, pixels 4*sq .. 4*sq+3); the row offset of
+            // a store is wave-uniform and goes into the scalar offset operand
+            const int sq = lane & 7, srow = lane >> 3;
+            const int m4 = tile * 32 + 4 * sq;
+            const bool mv4 = m4 < a.M;
+            const int mm4 = mv4 ? m4 : 0;
+            const int n4 = (int)fast_div((uint32_t)mm4, a.div_HW);
+            const int p4 = mm4 - n4 * a.HW;
+            const uint32_t voff = mv4 ? (uint32_t)((n4 * a.Rout + srow) * a.HW + p4) * 4u : 0x80000000u;
+            float *wr = stage + (4 * lhi) * kPwStageStride + l32;
+            const float *rd = stage + srow * kPwStageStride + 4 * sq;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                if (32 * mi + 32 <= a.Rout) {      // wave-uniform: every row of the tile exists
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int r = 32 * mi + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                        const float val = has_bias ? acc[mi][v] + biasl[r] : acc[mi][v];
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), orsrc, off, 0, 0);
-                        off += (uint32_t)((v & 3) == 3 ? 5 * hwb : hwb);
-                    }
-                } else {
+                for (int v = 0; v < 16; ++v) wr[(8 * (v >> 2) + (v & 3)) * kPwStageStride] = acc[mi][v];
+                const bool full = 32 * mi + 32 <= a.Rout;      // wave-uniform
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int r = 32 * mi + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                        const float val = has_bias ? acc[mi][v] + biasl[r] : acc[mi][v];
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), orsrc,
-                                                              r < a.Rout ? off : 0x80000000u, 0, 0);
-                        off += (uint32_t)((v & 3) == 3 ? 5 * hwb : hwb);
-                    }
+                for (int it = 0; it < 4; ++it) {
+                    const floatx4 val = *reinterpret_cast<const floatx4 *>(&rd[8 * it * kPwStageStride]);
+                    const uint32_t off = (full || 32 * mi + 8 * it + srow < a.Rout) ? voff : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) uint32_t, val),
+                                                           orsrc, off, (32 * mi + 8 * it) * hwb, 0);
+                }
+            }
+        } else if (!GROUPED) {
+            // rows 4*lhi + {0,1,2,3, 8,9,10,11, ...}: the row offset is wave-uniform (scalar
+            // offset operand); a lane without a pixel stays outside the buffer
+            const uint32_t off = mv ? (uint32_t)((n * a.Rout + 4 * lhi) * a.HW + p) * 4u : 0x80000000u;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const bool full = 32 * mi + 32 <= a.Rout;      // wave-uniform: every row of the tile exists
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r0 = 32 * mi + 8 * (v >> 2) + (v & 3);
+                    const float val = acc[mi][v];      // (a bit cast of the vector element itself takes element 0)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), orsrc,
+                                                          (full || r0 + 4 * lhi < a.Rout) ? off : 0x80000000u,
+                                                          r0 * hwb, 0);
                 }
             }
         } else {
-            // per-row records and bias at compile-time offsets from two lane-dependent
-            // LDS addresses (rows 4*lhi + ...); a global-memory store: a generic one
+            // per-row records at compile-time offsets from a lane-dependent LDS address
+            // (rows 4*lhi + ...); a global-memory store: a generic one
             // would make the waits for the loads in flight wait for everything
             typedef __attribute__((address_space(1))) float gfloat;
-            const float *bl = biasl + 4 * lhi;
             const RowDst *rd0 = rowdst + 4 * lhi;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
@@ -294,7 +395,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
                         for (int v = 0; v < 16; ++v) {
                             const int rr = 32 * mi + 8 * (v >> 2) + (v & 3);
                             const RowDst rd = rd0[rr];
-                            ((gfloat *)rd.base)[n * rd.img_stride + p] = acc[mi][v] + bl[rr];
+                            ((gfloat *)rd.base)[n * rd.img_stride + p] = acc[mi][v];
                         }
                     }
                 } else {
@@ -303,7 +404,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
                         const int rr = 32 * mi + 8 * (v >> 2) + (v & 3);
                         if (mv && rr + 4 * lhi < a.Rout) {
                             const RowDst rd = rd0[rr];
-                            ((gfloat *)rd.base)[n * rd.img_stride + p] = acc[mi][v] + bl[rr];
+                            ((gfloat *)rd.base)[n * rd.img_stride + p] = acc[mi][v];
                         }
                     }
                 }
@@ -320,10 +421,11 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         for (int mi = 0; mi < MI; ++mi) av[0][mi] = *reinterpret_cast<const floatx4 *>(&lds[mi * kPwBlk + lane * 4]);
     }
     for (int t = 0, tile = gw; t < mytiles; ++t, tile += NW) {
-        const uint32_t next_voff = tile_voff(tile + NW);
-        for (int g0 = 0; g0 < Gp; g0 += kPwRing) {
+        const uint32_t next_voff = TAPS ? 0u : tile_voff(tile + NW);
+        if (TAPS) next_tt = tap_tile(tile + NW);
+        for (int g0 = 0; g0 < Gp; g0 += RING) {
 #pragma unroll
-            for (int u = 0; u < kPwRing; ++u) {
+            for (int u = 0; u < RING; ++u) {
                 const int g = g0 + u;
                 if (g < G8) {
                     const int ng = (g + 1 == G8) ? 0 : g + 1;
@@ -338,8 +440,16 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
                             acc[mi] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u & 1][mi][e], b[u][e], acc[mi], 0, 0, 0);
                 }
                 // the refill is issued on every path, also after a padding group
-                const bool same = g + kPwRing < Gp;
-                issue(u, same ? cur_voff : next_voff, same ? g + kPwRing : u);
+                const bool same = g + RING < Gp;
+                if (TAPS) {
+                    TapTile tt;
+                    tt.base = same ? cur_tt.base : next_tt.base;
+                    tt.nvalid = same ? cur_tt.nvalid : next_tt.nvalid;
+                    tt.bad = same ? cur_tt.bad : next_tt.bad;
+                    issue_taps(u, tt, same ? g + RING : u);
+                } else {
+                    issue(u, same ? cur_voff : next_voff, same ? g + RING : u);
+                }
             }
         }
         if (G8 & 1) {
@@ -348,31 +458,66 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         }
         store_tile(tile);
         cur_voff = next_voff;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][v] = 0.f;
+        if (TAPS) cur_tt = next_tt;
+        init_acc();
     }
 }
 
-template <int MI, bool GROUPED>
+template <int MI, bool GROUPED, bool TAPS = false, int RING = kPwRing>
 static hipError_t launch_pw_stream_t(const PwArgs &a, size_t lds_bytes, int grid, hipStream_t s)
 {
     static size_t configured = 0;
     if (lds_bytes > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_stream_kernel<MI, GROUPED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_stream_kernel<MI, GROUPED, TAPS, RING>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwLdsMax);
         if (e != hipSuccess) return e;
         configured = kPwLdsMax;
     }
-    hipLaunchKernelGGL((pw_stream_kernel<MI, GROUPED>), dim3((unsigned)grid), dim3(kPwThreads), lds_bytes, s, a);
+    hipLaunchKernelGGL((pw_stream_kernel<MI, GROUPED, TAPS, RING>), dim3((unsigned)grid), dim3(kPwThreads), lds_bytes, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_pw_stream(const PwArgs &a, hipStream_t s)
+// taps form: forward pass of a layer with at most 128 filters whose filter bank fits in LDS
+// 16-byte stores need groups of four pixels that stay inside one image and are aligned,
+// and room for the staging area beside A
+static bool pw_wide_store(const PwArgs &a, size_t lds_bytes)
 {
-    const size_t lds_bytes = pw_stream_lds_bytes(a.Rout, a.D);
+    return a.ngroup == 1 && a.HW % 4 == 0 && ((uintptr_t)a.out[0] & 15) == 0 && lds_bytes + kPwStageBytes <= kPwLdsMax;
+}
+
+hipError_t launch_tap_stream(const PwArgs &a0, hipStream_t s)
+{
+    PwArgs a = a0;
+    size_t lds_bytes = pw_stream_lds_bytes(a.Rout, a.D);
+    if (lds_bytes == 0 || a.Rout > 128 || a.ngroup != 1 || a.D != a.tC * a.tR * a.tS) return hipErrorInvalidValue;
+    a.wide_store = pw_wide_store(a, lds_bytes);
+    if (a.wide_store) lds_bytes += kPwStageBytes;
+    int grid = (a.ntiles + kPwWaves - 1) / kPwWaves;
+    if (grid > 256) grid = 256;
+    if (grid < 1) grid = 1;
+    // at most 32 taps (3x3 over 3 channels): a ring of four groups holds a whole tile
+    const bool small = a.D <= 32;
+    switch (pw_row_tiles(a.Rout)) {
+#define TAP_CASE(M)                                                                          \
+    case M:                                                                                  \
+        return small ? launch_pw_stream_t<M, false, true, 4>(a, lds_bytes, grid, s)          \
+                     : launch_pw_stream_t<M, false, true>(a, lds_bytes, grid, s);
+        TAP_CASE(1)
+        TAP_CASE(2)
+        TAP_CASE(3)
+        TAP_CASE(4)
+#undef TAP_CASE
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_pw_stream(const PwArgs &a0, hipStream_t s)
+{
+    PwArgs a = a0;
+    size_t lds_bytes = pw_stream_lds_bytes(a.Rout, a.D);
     if (lds_bytes == 0) return hipErrorInvalidValue;
+    a.wide_store = pw_wide_store(a, lds_bytes);
+    if (a.wide_store) lds_bytes += kPwStageBytes;
     // one workgroup of eight waves per compute unit; a wave loops over its tiles
     int grid = (a.ntiles + kPwWaves - 1) / kPwWaves;
     if (grid > 256) grid = 256;

@@ -135,7 +135,9 @@ def test_algo_choice_rules():
     assert pick(vgg, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
     assert pick(vgg, B.OP_BWD_WEIGHT) == B.ALGO_WINOGRAD
     first = (64, 3, 224, 224, 64, 3, 3, 1, 1, 1, 1)              # 3 input channels
-    assert pick(first, B.OP_FWD) == B.ALGO_WINOGRAD             # tile-pair kernel, one ragged chunk
+    assert pick(first, B.OP_FWD) == B.ALGO_IGEMM                # taps kernel: the filter bank in LDS
+    assert pick((64, 6, 224, 224, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_WINOGRAD   # tile-pair kernel, one ragged chunk
+    assert pick((64, 3, 224, 224, 160, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_WINOGRAD  # too many filters for the taps kernel
     assert pick(first, B.OP_BWD_DATA) == B.ALGO_IGEMM
     assert pick(first, B.OP_BWD_WEIGHT) == B.ALGO_IGEMM
     assert pick((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # odd width: no pairs
