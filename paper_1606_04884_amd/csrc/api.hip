@@ -329,6 +329,8 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
 
 bool s2d_applicable(const Geom &g, conv2d_op op);     // strided layer as a stride-1 3x3 layer, below
 bool tap_stream_ok(const Geom &g);                    // forward pass with the filter bank in LDS, below
+bool tap_stream_bwd_ok(const Geom &g);                // the same for a stride-1 backward-data pass
+constexpr int kTapBwdMinRows = 12;                 // below that the 32-row MFMA tiles are mostly empty
 
 int resolve_algo(const Geom &g, conv2d_op op, int algo)
 {
@@ -349,6 +351,9 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         // backward-data into <= 4 channels: Winograd/GEMM rows would be almost empty;
         // a direct kernel takes it when its alignment conditions hold, else the GEMM
         if (op == CONV2D_BWD_DATA && g.C <= 4) return CONV2D_ALGO_IGEMM;
+        // filters beyond 3x3 whose bank fits in LDS: streamed over dy (pointwise.hip, taps form)
+        if (op == CONV2D_BWD_DATA && (g.R > 3 || g.S > 3) && g.C >= kTapBwdMinRows && tap_stream_bwd_ok(g))
+            return CONV2D_ALGO_IGEMM;
         const int cin = op == CONV2D_FWD ? g.C : g.K;
         // larger filters: 16 multiplications per 2x2 outputs and 3x3 sub-filter against
         // R*S*4 direct ones; the sub-filters of 4x4 / 4x5 filters are mostly padding
@@ -411,7 +416,7 @@ void fill_pw_args(PwArgs &a, const Geom &g, conv2d_op op, const float *in)
 // form of the streaming kernel
 bool tap_stream_ok(const Geom &g)
 {
-    if (g.R * g.S == 1 || g.R > 16 || g.S > 16 || g.K > 128) return false;
+    if (g.R * g.S == 1 || g.R > 15 || g.S > 15 || g.K > 128) return false;
     if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31)) return false;
     if ((int64_t)g.N * g.K * g.P * g.Q * 4 >= (int64_t(1) << 31)) return false;
     return pw_stream_lds_bytes(g.K, g.C * g.R * g.S) != 0;
@@ -436,6 +441,40 @@ void fill_tap_args(PwArgs &a, const Geom &g, const float *x)
     a.tC = g.C; a.tH = g.H; a.tW = g.W; a.tR = g.R; a.tS = g.S;
     a.tsh = g.sh; a.tsw = g.sw; a.tph = g.ph; a.tpw = g.pw; a.tQ = g.Q;
     a.div_tQ = make_fastdiv((uint32_t)g.Q);
+}
+
+// Stride-1 backward-data of a layer whose filter bank fits in LDS, C <= 128: the same kernel
+// over dy.  Worth it only when the C rows fill a good part of the 32-row MFMA tiles.
+bool tap_stream_bwd_ok(const Geom &g)
+{
+    if (g.sh != 1 || g.sw != 1 || g.R * g.S == 1 || g.R > 15 || g.S > 15 || g.C > 128) return false;
+    if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31)) return false;
+    if ((int64_t)g.N * g.K * g.P * g.Q * 4 >= (int64_t(1) << 31)) return false;
+    return pw_stream_lds_bytes(g.C, g.K * g.R * g.S) != 0;
+}
+
+void fill_tap_bwd_args(PwArgs &a, const Geom &g, const float *dy)
+{
+    a.in = dy;
+    a.D = g.K * g.R * g.S;
+    a.Rout = g.C;
+    a.HW = g.H * g.W;
+    a.M = g.N * a.HW;
+    a.ntiles = ceil_div(a.M, 32);
+    a.in_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+    a.out_bytes = (int32_t)((int64_t)a.M * a.Rout * 4);
+    a.w_row_stride = 0;
+    a.w_depth_stride = 0;
+    a.div_HW = make_fastdiv((uint32_t)a.HW);
+    a.div_fast = make_fastdiv(1u);
+    a.ngroup = 1;
+    for (int i = 0; i <= kMaxGroups; ++i) a.r0[i] = i == 0 ? 0 : a.Rout;
+    a.tC = g.K; a.tH = g.P; a.tW = g.Q; a.tR = g.R; a.tS = g.S;
+    a.tsh = 1; a.tsw = 1; a.tph = g.R - 1 - g.ph; a.tpw = g.S - 1 - g.pw; a.tQ = g.W;
+    a.tap_bwd = 1;
+    a.div_tQ = make_fastdiv((uint32_t)g.W);
+    a.div_tRS = make_fastdiv((uint32_t)(g.R * g.S));
+    a.div_rows = make_fastdiv((uint32_t)g.C);
 }
 
 // Pointwise backward-weight as a streaming product (pointwise.hip): plan of the split
@@ -907,6 +946,12 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
         pa.w[0] = w; pa.bias[0] = nullptr; pa.out[0] = dx;
         pa.fill_vec = g.C % 4 == 0 && ((uintptr_t)w & 15) == 0;
         return launch_status(launch_pw_stream(pa, s));
+    }
+    if (tap_stream_bwd_ok(g) && g.C >= kTapBwdMinRows) {
+        PwArgs pa = {};
+        fill_tap_bwd_args(pa, g, dy);
+        pa.w[0] = w; pa.bias[0] = nullptr; pa.out[0] = dx;
+        return launch_status(launch_tap_stream(pa, s));
     }
     float *wt = (float *)ws;
     DepthEntry *tab = (DepthEntry *)((char *)ws + p.wt_bytes);

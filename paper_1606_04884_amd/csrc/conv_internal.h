@@ -256,7 +256,8 @@ struct PwArgs {
     // taps form (launch_tap_stream): forward pass of an R x S layer; D = tC*tR*tS taps over a
     // tC x tH x tW input, HW = P*Q output pixels per image, tQ = Q
     int32_t tC, tH, tW, tR, tS, tsh, tsw, tph, tpw, tQ;
-    FastDiv div_tQ;
+    int32_t tap_bwd;                     // stride-1 backward-data: in = dy, w walked as [k][c][r][t], taps flipped
+    FastDiv div_tQ, div_tRS, div_rows;   // (the last two: tap_bwd fill, by tR*tS and by Rout)
 };
 hipError_t launch_tap_stream(const PwArgs &a, hipStream_t s);
 // largest rows x depth product the kernel keeps in LDS, in bytes; 0 if the shape does not fit

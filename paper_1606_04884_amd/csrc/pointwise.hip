@@ -53,8 +53,8 @@ size_t pw_stream_lds_bytes(int Rout, int D)
     const int MI = pw_row_tiles(Rout);
     if (MI == 0) return 0;
     // A blocks, bias per row, and (grouped outputs) a 16-byte destination record per row
-    // (and, for the taps form, 8 bytes per depth index)
-    const size_t bytes = ((size_t)((D + 7) / 8) * MI * kPwBlk + 32 * MI + 4 * 32 * MI + 2 * 8 * ((D + 7) / 8)) * sizeof(float);
+    // (and, for the taps form, 8 bytes per depth index, padding groups of the ring included)
+    const size_t bytes = ((size_t)((D + 7) / 8) * MI * kPwBlk + 32 * MI + 4 * 32 * MI + 2 * 8 * ((D + 7) / 8 + kPwRing)) * sizeof(float);
     return bytes <= kPwLdsMax ? bytes : 0;
 }
 
@@ -71,6 +71,10 @@ constexpr size_t kPwStageBytes = (size_t)kPwWaves * 32 * kPwStageStride * sizeof
 // element offset and (r, t) of every tap sit in an LDS table; the two half-waves read their
 // two entries (a broadcast read each), and a lane tests a tap against the set of window
 // rows and columns that lie inside its image, worked out once per tile.
+// tap_bwd: the stride-1 backward-data pass in the same form, dx[n][c][h][u] = sum over
+// (k, r, t) of w[k][c][r][t] * dy[n][k][h + pad_h - r][u + pad_w - t]: rows = c, depth =
+// (k, r, t) in the filters' memory order, the window over dy starts at (h + pad_h - (R-1),
+// u + pad_w - (S-1)) and tap (r, t) reads its element (R-1-r, S-1-t).
 template <int MI, bool GROUPED, bool TAPS, int RING>
 __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
 {
@@ -89,8 +93,8 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
     };
     RowDst *rowdst = reinterpret_cast<RowDst *>(biasl + 32 * MI);      // [32 * MI]
     // TAPS: depth d -> {byte offset of tap (c, r, t) from the window origin, 1 << r | 1 << (16 + t)}
-    int2 *taptab = reinterpret_cast<int2 *>(biasl + 32 * MI + 4 * 32 * MI);     // [8 * G8]
-    float *stage = biasl + 32 * MI + 4 * 32 * MI + 16 * G8 + wave * (32 * kPwStageStride);   // a.wide_store
+    int2 *taptab = reinterpret_cast<int2 *>(biasl + 32 * MI + 4 * 32 * MI);     // [8 * Gp]
+    float *stage = biasl + 32 * MI + 4 * 32 * MI + 16 * (G8 + kPwRing) + wave * (32 * kPwStageStride);   // a.wide_store
 
     // tiles gw, gw + NW, ... belong to this wave
     const int NW = gridDim.x * kPwWaves;
@@ -140,40 +144,38 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
     };
     // TAPS: what a tile needs for its loads: the byte offset of the lane's window origin
     // (negative when the window starts in the padding: such an offset has bit 31 set and is
-    // out of range by itself) and the complement of the lane's set of valid taps, bit r for
-    // window row r and bit 16 + t for window column t.
+    // out of range by itself; a lane without a pixel gets bit 31 as well) and the complement
+    // of the lane's set of valid taps, bit r for window row r and bit 16 + t for window column
+    // t.  Bit 15 is never a valid row: table entries past the depth (the rest of the last
+    // group, the padding groups of the ring) carry it and so never fetch.
     struct TapTile {
         int base;
         uint32_t nvalid;
-        uint32_t bad;          // bit 31: this lane has no pixel in the tile
     };
-    auto range_mask = [](int lo, int hi) -> uint32_t {        // bits lo .. hi-1, lo >= 0, hi <= 16
+    auto range_mask = [](int lo, int hi) -> uint32_t {        // bits lo .. hi-1, lo >= 0, hi <= 15
         return hi > lo ? ((1u << hi) - 1u) & ~((1u << lo) - 1u) : 0u;
     };
     auto tap_tile = [&](int tile) -> TapTile {
         TapTile tt;
         const uint32_t m = (uint32_t)(tile * 32 + l32);
         const bool mv = tile < a.ntiles && m < (uint32_t)a.M;
-        tt.bad = mv ? 0u : 0x80000000u;
         const uint32_t mm = mv ? m : 0u;
         const int n = (int)fast_div(mm, a.div_HW), pq = (int)mm - n * a.HW;
         const int p = (int)fast_div((uint32_t)pq, a.div_tQ), q = pq - p * a.tQ;
         const int ih0 = p * a.tsh - a.tph, iw0 = q * a.tsw - a.tpw;
-        tt.base = ((n * a.tC * a.tH + ih0) * a.tW + iw0) * 4;
+        tt.base = (((n * a.tC * a.tH + ih0) * a.tW + iw0) * 4) | (mv ? 0 : (int)0x80000000);
         const uint32_t rows = range_mask(max(0, -ih0), min(a.tR, a.tH - ih0));
         const uint32_t cols = range_mask(max(0, -iw0), min(a.tS, a.tW - iw0));
         tt.nvalid = ~(rows | (cols << 16));
         return tt;
     };
     auto issue_taps = [&](int u, const TapTile &tt, int grp) {
-        const uint32_t is_last = grp == G8 - 1 ? 0xffffffffu : 0u;     // wave-uniform
-        const uint32_t gbad = (grp < G8 ? 0u : 0x80000000u) | tt.bad;
-        const int g = grp < G8 ? grp : 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int2 tp = taptab[g * 8 + 2 * e + lhi];
-            const uint32_t off = (uint32_t)(tt.base + tp.x) | (((uint32_t)tp.y & tt.nvalid) ? 0x80000000u : 0u) |
-                                 ((lastbad[e] & is_last) | gbad);
+            const int2 tp = taptab[grp * 8 + 2 * e + lhi];
+            // (straight-line: a select between the sum and a constant turns into a branch
+            // around the LDS read of the offset)
+            const uint32_t off = (uint32_t)(tt.base + tp.x) | (((uint32_t)tp.y & tt.nvalid) ? 0x80000000u : 0u);
             b[u][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
         }
     };
@@ -227,6 +229,13 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         // memory index -> x = row, y = depth (branch-free: the quotient and remainder by
         // the contiguous axis, swapped for the transposed operand)
         auto split_index = [&](int idx) -> int2 {
+            if (TAPS && a.tap_bwd) {
+                // w[k][c][r][t] walked in memory order: row c, depth (k, r, t)
+                const int RS = a.tR * a.tS;
+                const int kc = (int)fast_div((uint32_t)idx, a.div_tRS), rs = idx - kc * RS;
+                const int k = (int)fast_div((uint32_t)kc, a.div_rows), c = kc - k * a.Rout;
+                return make_int2(c, k * RS + rs);
+            }
             const int q = (int)fast_div((uint32_t)idx, a.div_fast);
             const int rem = idx - q * (depth_fast ? a.D : a.Rout);
             return depth_fast ? make_int2(q, rem) : make_int2(rem, q);
@@ -282,7 +291,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
                     v[j] = 0.f;
                     if (idx < total) {
                         const int2 rd = split_index(idx);
-                        v[j] = *source(rd.x, rd.y);
+                        v[j] = (TAPS && a.tap_bwd) ? a.w[0][idx] : *source(rd.x, rd.y);
                         dst[j] = lds_index(rd.x, rd.y);
                     }
                 }
@@ -293,11 +302,16 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         }
     }
     if (TAPS) {
-        for (int d = tid; d < 8 * G8; d += kPwThreads) {
-            int2 e = make_int2(0, 0);                          // past D: masked by lastbad
+        for (int d = tid; d < 8 * Gp; d += kPwThreads) {
+            int2 e = make_int2(0, 1 << 15);                    // past D: never fetched
             if (d < a.D) {
                 const int RS = a.tR * a.tS;
-                const int c = d / RS, rs = d - c * RS, r = rs / a.tS, t = rs - r * a.tS;
+                const int c = d / RS, rs = d - c * RS;
+                int r = rs / a.tS, t = rs - r * a.tS;
+                if (a.tap_bwd) {                               // backward-data: the filter is flipped
+                    r = a.tR - 1 - r;
+                    t = a.tS - 1 - t;
+                }
                 e = make_int2(((c * a.tH + r) * a.tW + t) * 4, (1 << r) | (1 << (16 + t)));
             }
             taptab[d] = e;
@@ -445,7 +459,6 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
                     TapTile tt;
                     tt.base = same ? cur_tt.base : next_tt.base;
                     tt.nvalid = same ? cur_tt.nvalid : next_tt.nvalid;
-                    tt.bad = same ? cur_tt.bad : next_tt.bad;
                     issue_taps(u, tt, same ? g + RING : u);
                 } else {
                     issue(u, same ? cur_voff : next_voff, same ? g + RING : u);
@@ -490,6 +503,7 @@ hipError_t launch_tap_stream(const PwArgs &a0, hipStream_t s)
     PwArgs a = a0;
     size_t lds_bytes = pw_stream_lds_bytes(a.Rout, a.D);
     if (lds_bytes == 0 || a.Rout > 128 || a.ngroup != 1 || a.D != a.tC * a.tR * a.tS) return hipErrorInvalidValue;
+    if (a.tap_bwd && a.fill_vec) return hipErrorInvalidValue;
     a.wide_store = pw_wide_store(a, lds_bytes);
     if (a.wide_store) lds_bytes += kPwStageBytes;
     int grid = (a.ntiles + kPwWaves - 1) / kPwWaves;
