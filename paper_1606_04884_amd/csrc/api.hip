@@ -406,6 +406,7 @@ void fill_pw_args(PwArgs &a, const Geom &g, conv2d_op op, const float *in)
     a.out_bytes = (int32_t)((int64_t)a.M * a.Rout * 4);
     a.w_row_stride = fwd ? g.C : 1;
     a.w_depth_stride = fwd ? 1 : g.C;
+    a.depth_fast = fwd ? 1 : 0;
     a.div_HW = make_fastdiv((uint32_t)a.HW);
     a.div_fast = make_fastdiv((uint32_t)(fwd ? a.D : a.Rout));
     a.ngroup = 1;
@@ -434,6 +435,7 @@ void fill_tap_args(PwArgs &a, const Geom &g, const float *x)
     a.out_bytes = (int32_t)((int64_t)a.M * a.Rout * 4);
     a.w_row_stride = a.D;
     a.w_depth_stride = 1;
+    a.depth_fast = 1;
     a.div_HW = make_fastdiv((uint32_t)a.HW);
     a.div_fast = make_fastdiv((uint32_t)a.D);
     a.ngroup = 1;
@@ -465,6 +467,7 @@ void fill_tap_bwd_args(PwArgs &a, const Geom &g, const float *dy)
     a.out_bytes = (int32_t)((int64_t)a.M * a.Rout * 4);
     a.w_row_stride = 0;
     a.w_depth_stride = 0;
+    a.depth_fast = 0;
     a.div_HW = make_fastdiv((uint32_t)a.HW);
     a.div_fast = make_fastdiv(1u);
     a.ngroup = 1;

@@ -248,11 +248,13 @@ struct PwArgs {
     float *out[kMaxGroups];              // group g: [N][r0[g+1]-r0[g]][HW]
     int32_t r0[kMaxGroups + 1];
     int32_t w_row_stride, w_depth_stride;
+    int32_t depth_fast;                  // A's contiguous axis is the depth (forward) / the rows (backward-data);
+                                         // stated, not derived from the strides: with one channel both are 1
     int32_t fill_vec;                    // A may be fetched as aligned 16-byte vectors along its contiguous axis
     int32_t wide_store;                  // set by the launcher: 16-byte stores through the LDS staging area
     int32_t D, Rout, HW, M;              // M = N*HW pixels
     int32_t ntiles;                      // 32-pixel tiles
-    FastDiv div_HW, div_fast;            // div_fast: by D if w_depth_stride == 1, else by Rout
+    FastDiv div_HW, div_fast;            // div_fast: by D if depth_fast, else by Rout
     // taps form (launch_tap_stream): forward pass of an R x S layer; D = tC*tR*tS taps over a
     // tC x tH x tW input, HW = P*Q output pixels per image, tQ = Q
     int32_t tC, tH, tW, tR, tS, tsh, tsw, tph, tpw, tQ;

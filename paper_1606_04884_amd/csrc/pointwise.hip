@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
     // before its first MFMA
     {
         const int total = a.Rout * a.D;
-        const bool depth_fast = a.w_depth_stride == 1;
+        const bool depth_fast = a.depth_fast != 0;
         auto lds_index = [&](int r, int d) -> int {
             return ((d >> 3) * MI + (r >> 5)) * kPwBlk + (((d & 1) << 5) + (r & 31)) * 4 + ((d & 7) >> 1);
         };

@@ -45,6 +45,11 @@ POINTWISE_SHAPES = [
     # with 12 depth groups (ring of 8 + 4) one way and a single group the other way
     PW(24, 96, 56, 56, 8),
     PW(24, 8, 56, 56, 96),
+    # a single channel / a single filter: both strides of the small operand are 1, so its
+    # contiguous axis cannot be told from them
+    PW(2, 1, 17, 21, 96),
+    PW(4, 1, 4, 12, 1),
+    PW(3, 40, 5, 8, 1),
 ]
 
 
