@@ -355,8 +355,7 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
         const int n = (int)fast_div((uint32_t)mm, a.div_HW);
         const int p = mm - n * a.HW;
         if (!GROUPED && a.wide_store) {
-            // lane -> (row srow of an 8-row slab, pixels 4*sq .. 4*sq+3); the row offset of
-            // a store is wave-uniform and goes into the scalar offset operand
+            // lane -> (row srow of an 8-row slab, pixels 4*sq .. 4*sq+3)
             const int sq = lane & 7, srow = lane >> 3;
             const int m4 = tile * 32 + 4 * sq;
             const bool mv4 = m4 < a.M;
@@ -374,9 +373,16 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
                     const floatx4 val = *reinterpret_cast<const floatx4 *>(&rd[8 * it * kPwStageStride]);
-                    const uint32_t off = (full || 32 * mi + 8 * it + srow < a.Rout) ? voff : 0x80000000u;
+                    // The row offset is added into the lane offset, not passed as the scalar
+                    // offset: with a scalar-register offset the compiler assumes that the
+                    // data registers of a 16-byte store may be overwritten by the very next
+                    // vector instruction, and on this chip that store then wrote the new
+                    // value of its first register from some lanes (seen as sporadic wrong
+                    // first pixels of a quad).  In this form the compiler keeps the distance.
+                    const uint32_t off = (full || 32 * mi + 8 * it + srow < a.Rout)
+                                             ? voff + (uint32_t)((32 * mi + 8 * it) * hwb) : 0x80000000u;
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) uint32_t, val),
-                                                           orsrc, off, (32 * mi + 8 * it) * hwb, 0);
+                                                           orsrc, off, 0, 0);
                 }
             }
         } else if (!GROUPED) {
