@@ -104,6 +104,16 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
 int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias,
                float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
 
+/* Forward followed by the rectifier of the layer after it, in the same epilogue:
+ * y = max(0, conv(x, w) + bias), stored once.  (Sec. 4.1 lists the RELU layers as the
+ * small remainder of the per-layer time next to the convolutions; fusing them is the
+ * "fully fused kernels" item of Sec. 4.2 "Neon" taken one step further: the separate
+ * layer would read and write y once more.)  Same arguments, workspace, algorithm choice
+ * and errors as conv2d_fwd; the sum is the one conv2d_fwd forms, max(., 0) is applied to
+ * it in fp32 (a NaN sum gives 0). */
+int conv2d_fwd_relu(const conv2d_desc *d, const float *x, const float *w, const float *bias,
+                    float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
+
 /* Several 1x1, stride-1, unpadded convolutions of the SAME input in one pass over it
  * (Sec. 4.2 singles out GoogLeNet's 1x1 layers; its inception module applies three of
  * them to one input, and they are bound by reading that input).  Group g has K[g]

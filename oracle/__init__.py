@@ -82,6 +82,12 @@ def fwd(geom, x, w, b: Optional[np.ndarray] = None) -> np.ndarray:
     return y
 
 
+def fwd_relu(geom, x, w, b: Optional[np.ndarray] = None) -> np.ndarray:
+    """Forward followed by the rectifier layer the paper's Sec. 4.1 lists beside the
+    convolutions (RELU): max(0, y) element by element on the fp64 forward result."""
+    return np.maximum(fwd(geom, x, w, b), 0.0)
+
+
 def bwd_data(geom, dy, w) -> np.ndarray:
     g = _geom(geom)
     N, Cc, H, W, K, R, S = g[:7]

@@ -559,7 +559,7 @@ bool smallc_bwd_ok(const Geom &g, const float *dy, const float *dx)
 int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
 
 int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias,
-             float *out, void *ws, size_t ws_bytes, hipStream_t s)
+             float *out, void *ws, size_t ws_bytes, hipStream_t s, int relu = 0)
 {
     const WinoPlan p = plan_wino(g, op);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
@@ -568,7 +568,7 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
                                               op == CONV2D_FWD ? 0 : 1, p.mode != 0, s));
     if (rc) return rc;
     WinoArgs a = {};
-    a.in = in; a.U = U; a.bias = bias; a.out = out;
+    a.in = in; a.U = U; a.bias = bias; a.out = out; a.relu = relu;
     a.N = g.N; a.Cin = p.Cin; a.Cpad = p.Cpad; a.Hin = p.Hin; a.Win = p.Win;
     a.Kout = p.Kout; a.Kpad = p.Kpad; a.Hout = p.Hout; a.Wout = p.Wout;
     a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
@@ -678,7 +678,7 @@ void fill_s2d_args(S2dArgs &a, const Geom &g, const S2dPlan &p)
 }
 
 int run_s2d(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias, float *out,
-            void *ws, size_t ws_bytes, hipStream_t s)
+            void *ws, size_t ws_bytes, hipStream_t s, int relu = 0)
 {
     const S2dPlan p = plan_s2d(g, op);
     if (!p.ok) return CONV2D_ERR_ALGO;
@@ -694,7 +694,7 @@ int run_s2d(const Geom &g, conv2d_op op, const float *in, const float *w, const 
         sa.x = in; sa.x2 = x2;
         rc = launch_status(launch_space_to_depth(sa, s));
         if (rc) return rc;
-        return run_wino(p.g2, CONV2D_FWD, x2, w2, bias, out, inner, p.inner_bytes, s);
+        return run_wino(p.g2, CONV2D_FWD, x2, w2, bias, out, inner, p.inner_bytes, s, relu);
     }
     // backward-data: gradient of the rearranged input, then the inverse permutation
     rc = run_wino(p.g2, CONV2D_BWD_DATA, in, w2, nullptr, x2, inner, p.inner_bytes, s);
@@ -770,8 +770,8 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     }
 }
 
-int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
-               void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream)
+static int fwd_impl(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
+                    void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream, int relu)
 {
     Geom g;
     int rc = check_desc(d, &g);
@@ -781,22 +781,22 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
     if (al == CONV2D_ALGO_WINOGRAD)
-        return wino_applicable(g, CONV2D_FWD) ? run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s)
-                                              : run_s2d(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s);
+        return wino_applicable(g, CONV2D_FWD) ? run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu)
+                                              : run_s2d(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
 
     const GatherPlan p = plan_fwd(g);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
     if (pw_stream_ok(g, CONV2D_FWD)) {
         PwArgs pa = {};
         fill_pw_args(pa, g, CONV2D_FWD, x);
-        pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y;
+        pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y; pa.relu = relu;
         pa.fill_vec = g.C % 4 == 0 && ((uintptr_t)w & 15) == 0;
         return launch_status(launch_pw_stream(pa, s));
     }
     if (tap_stream_ok(g)) {
         PwArgs pa = {};
         fill_tap_args(pa, g, x);
-        pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y;
+        pa.w[0] = w; pa.bias[0] = bias; pa.out[0] = y; pa.relu = relu;
         pa.fill_vec = pa.D % 4 == 0 && ((uintptr_t)w & 15) == 0;
         return launch_status(launch_tap_stream(pa, s));
     }
@@ -814,7 +814,7 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
     if (rc) return rc;
 
     GemmConvArgs a = {};
-    a.in = x; a.wt = wt; a.tab = tab; a.bias = bias; a.out = y;
+    a.in = x; a.wt = wt; a.tab = tab; a.bias = bias; a.out = y; a.relu = relu;
     a.N = g.N; a.Hin = g.H; a.Win = g.W; a.in_img_stride = g.C * g.H * g.W;
     a.Kout = g.K; a.Kpad = p.Kpad; a.Hout = g.P; a.Wout = g.Q;
     a.out_chan_stride = g.P * g.Q; a.out_img_stride = g.K * g.P * g.Q;
@@ -831,6 +831,18 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
         a.in_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
     }
     return launch_status(launch_gemmconv(a, p.tile, 1, s));
+}
+
+int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
+               void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream)
+{
+    return fwd_impl(d, x, w, bias, y, ws, ws_bytes, algo, hip_stream, 0);
+}
+
+int conv2d_fwd_relu(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
+                    void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream)
+{
+    return fwd_impl(d, x, w, bias, y, ws, ws_bytes, algo, hip_stream, 1);
 }
 
 int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, const int32_t *K,

@@ -70,6 +70,7 @@ struct GemmConvArgs {
     const float *wt;           // [rows_total][Kpad]
     const DepthEntry *tab;     // [rows_total]
     const float *bias;         // nullable
+    int32_t relu;              // forward: y = max(0, product + bias)
     float *out;
     int32_t N, Hin, Win, in_img_stride;
     int32_t Kout, Kpad, Hout, Wout, out_chan_stride, out_img_stride;
@@ -167,6 +168,7 @@ struct WinoArgs {
     const float *in;
     const float *U;
     const float *bias;       // nullable
+    int32_t relu;            // forward: y = max(0, product + bias)
     float *out;
     int32_t N, Cin, Cpad, Hin, Win, Kout, Kpad, Hout, Wout;
     int32_t pad_h, pad_w;    // patch origin = 2*tile - pad
@@ -252,6 +254,7 @@ struct PwArgs {
                                          // stated, not derived from the strides: with one channel both are 1
     int32_t fill_vec;                    // A may be fetched as aligned 16-byte vectors along its contiguous axis
     int32_t wide_store;                  // set by the launcher: 16-byte stores through the LDS staging area
+    int32_t relu;                        // forward: out = max(0, product + bias) (not with grouped outputs)
     int32_t D, Rout, HW, M;              // M = N*HW pixels
     int32_t ntiles;                      // 32-pixel tiles
     FastDiv div_HW, div_fast;            // div_fast: by D if depth_fast, else by Rout

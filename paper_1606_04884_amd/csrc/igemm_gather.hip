@@ -11,7 +11,8 @@
 //     contiguous axis, so stride-1 gathers coalesce);
 //   * the filter matrix is pre-transposed to [depth][Kpad] so its tiles are
 //     plain 16-byte row reads;
-//   * bias is added in the epilogue before the only store ("fully fused").
+//   * bias (and, on request, the ReLU that follows the layer) is applied in the epilogue
+//     before the only store ("fully fused").
 // 256 threads = 4 waves; LDS tiles are double buffered, one barrier per step.
 
 #include "conv_internal.h"
@@ -419,7 +420,9 @@ __global__ __launch_bounds__(256) void gemmconv_kernel(GemmConvArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int k = kt * BM + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                if (k < a.Kout) op[(int64_t)k * a.out_chan_stride] = acc[mi][ni][v] + bz[mi][v];
+                float val = acc[mi][ni][v] + bz[mi][v];
+                if (a.relu) val = fmaxf(val, 0.f);
+                if (k < a.Kout) op[(int64_t)k * a.out_chan_stride] = val;
             }
         }
     }

@@ -10,7 +10,7 @@
 // into the registers an MFMA reads (no staging of the big operand in LDS, no
 // workgroup barrier in the main loop), with several KB of loads in flight per wave.
 //
-//   pw_stream_kernel : out[n][r][p] = bias[r] + sum_d A[r][d] * in[n][d][p]
+//   pw_stream_kernel : out[n][r][p] = bias[r] + sum_d A[r][d] * in[n][d][p]   (optionally max(0, .))
 //                      (forward: A = w; backward-data: A = w transposed)
 //   pw_wgrad_kernel  : part[s][k][c] = sum_{pixels of range s} dy[n][k][p] * x[n][c][p]
 //
@@ -372,7 +372,8 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
                 const bool full = 32 * mi + 32 <= a.Rout;      // wave-uniform
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
-                    const floatx4 val = *reinterpret_cast<const floatx4 *>(&rd[8 * it * kPwStageStride]);
+                    floatx4 val = *reinterpret_cast<const floatx4 *>(&rd[8 * it * kPwStageStride]);
+                    if (a.relu) { val[0] = fmaxf(val[0], 0.f); val[1] = fmaxf(val[1], 0.f); val[2] = fmaxf(val[2], 0.f); val[3] = fmaxf(val[3], 0.f); }
                     // The row offset is added into the lane offset, not passed as the scalar
                     // offset: with a scalar-register offset the compiler assumes that the
                     // data registers of a 16-byte store may be overwritten by the very next
@@ -395,7 +396,8 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r0 = 32 * mi + 8 * (v >> 2) + (v & 3);
-                    const float val = acc[mi][v];      // (a bit cast of the vector element itself takes element 0)
+                    float val = acc[mi][v];            // (a bit cast of the vector element itself takes element 0)
+                    if (a.relu) val = fmaxf(val, 0.f);
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), orsrc,
                                                           (full || r0 + 4 * lhi < a.Rout) ? off : 0x80000000u,
                                                           r0 * hwb, 0);

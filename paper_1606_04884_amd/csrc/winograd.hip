@@ -254,8 +254,10 @@ __device__ __forceinline__ void wino_finish_tile(const WinoArgs &a, floatx16 (&a
                     out_xform(v, y00, y01, y10, y11);
                     const float bz = bp ? bp[kr] : 0.f;
                     float *o = ob + (int64_t)kr * HWo;
-                    *reinterpret_cast<float2 *>(o) = make_float2(y00 + bz, y01 + bz);
-                    if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10 + bz, y11 + bz);
+                    y00 += bz; y01 += bz; y10 += bz; y11 += bz;
+                    if (a.relu) { y00 = fmaxf(y00, 0.f); y01 = fmaxf(y01, 0.f); y10 = fmaxf(y10, 0.f); y11 = fmaxf(y11, 0.f); }
+                    *reinterpret_cast<float2 *>(o) = make_float2(y00, y01);
+                    if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y10, y11);
                 }
             }
         } else {
@@ -268,11 +270,13 @@ __device__ __forceinline__ void wino_finish_tile(const WinoArgs &a, floatx16 (&a
                     out_xform(v, y00, y01, y10, y11);
                     const float bz = bp ? bp[kr] : 0.f;
                     float *o = ob + (int64_t)kr * HWo;
-                    o[0] = y00 + bz;
-                    if (col1) o[1] = y01 + bz;
+                    y00 += bz; y01 += bz; y10 += bz; y11 += bz;
+                    if (a.relu) { y00 = fmaxf(y00, 0.f); y01 = fmaxf(y01, 0.f); y10 = fmaxf(y10, 0.f); y11 = fmaxf(y11, 0.f); }
+                    o[0] = y00;
+                    if (col1) o[1] = y01;
                     if (row1) {
-                        o[a.Wout] = y10 + bz;
-                        if (col1) o[a.Wout + 1] = y11 + bz;
+                        o[a.Wout] = y10;
+                        if (col1) o[a.Wout + 1] = y11;
                     }
                 }
             }
@@ -892,15 +896,17 @@ __device__ __forceinline__ void wino_pair_body(const WinoArgs &a, float *lds)
             } else if (tv && kbase + kr < a.Kout) {
                 const float bz = bp ? bp[kr] : 0.f;
                 float *o = ob + (int64_t)kr * HWo;
+                y[0] += bz; y[1] += bz; y[2] += bz; y[3] += bz;
+                if (a.relu) { y[0] = fmaxf(y[0], 0.f); y[1] = fmaxf(y[1], 0.f); y[2] = fmaxf(y[2], 0.f); y[3] = fmaxf(y[3], 0.f); }
                 if (a.vec2) {
-                    *reinterpret_cast<float2 *>(o) = make_float2(y[0] + bz, y[1] + bz);
-                    if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y[2] + bz, y[3] + bz);
+                    *reinterpret_cast<float2 *>(o) = make_float2(y[0], y[1]);
+                    if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y[2], y[3]);
                 } else {
-                    o[0] = y[0] + bz;
-                    if (col1) o[1] = y[1] + bz;
+                    o[0] = y[0];
+                    if (col1) o[1] = y[1];
                     if (row1) {
-                        o[a.Wout] = y[2] + bz;
-                        if (col1) o[a.Wout + 1] = y[3] + bz;
+                        o[a.Wout] = y[2];
+                        if (col1) o[a.Wout + 1] = y[3];
                     }
                 }
             }
@@ -975,11 +981,13 @@ __global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
         const floatx4 q = *reinterpret_cast<const floatx4 *>(headp + e * 4);
         const float bz = a.bias ? a.bias[k] : 0.f;
         float *o = obase + (int64_t)k * HWo;
-        o[0] = p[0] + q[0] + bz;
-        if (col1) o[1] = p[1] + q[1] + bz;
+        floatx4 y = {p[0] + q[0] + bz, p[1] + q[1] + bz, p[2] + q[2] + bz, p[3] + q[3] + bz};
+        if (a.relu) { y[0] = fmaxf(y[0], 0.f); y[1] = fmaxf(y[1], 0.f); y[2] = fmaxf(y[2], 0.f); y[3] = fmaxf(y[3], 0.f); }
+        o[0] = y[0];
+        if (col1) o[1] = y[1];
         if (row1) {
-            o[a.Wout] = p[2] + q[2] + bz;
-            if (col1) o[a.Wout + 1] = p[3] + q[3] + bz;
+            o[a.Wout] = y[2];
+            if (col1) o[a.Wout + 1] = y[3];
         }
     }
 }

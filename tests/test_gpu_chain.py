@@ -3,7 +3,9 @@ between blocks) through the C-ABI: shows that the per-layer calls compose.  Ever
 layer's GPU output is judged against the oracle applied to that layer's ACTUAL
 device input (copied back), so an error in one layer cannot hide in the next.
 The pooling between blocks is support code (a plain tensor reduction), not part
-of the path under test; no activation function is applied between layers."""
+of the path under test.  Run twice: without an activation function between the layers,
+and with the rectifier fused into every convolution (conv2d_fwd_relu), which is how the
+stack is used: from the second layer on the inputs are then non-negative and sparse."""
 import numpy as np
 import pytest
 
@@ -17,7 +19,8 @@ pytestmark = pytest.mark.gpu
 POOL_AFTER = {"conv1_2", "conv2_2", "conv3_3", "conv4_3"}
 
 
-def test_vgg16_chained_forward_batch2():
+@pytest.mark.parametrize("relu", [False, True], ids=["linear", "relu"])
+def test_vgg16_chained_forward_batch2(relu):
     import torch
     dev = torch.device("cuda:0")
     layers = synth.config_layers(2, batch=2)
@@ -32,9 +35,10 @@ def test_vgg16_chained_forward_batch2():
         b = synth.uniform((L.K,), synth.layer_seed(2, li, 2), -0.1, 0.1)
         y = torch.full((L.N, L.K, P, Q), float("nan"), device=dev)
         print("layer", L.name, geom, flush=True)
-        B.conv2d_fwd(geom, x, torch.from_numpy(w).to(dev), torch.from_numpy(b).to(dev), y)
+        (B.conv2d_fwd_relu if relu else B.conv2d_fwd)(geom, x, torch.from_numpy(w).to(dev),
+                                                      torch.from_numpy(b).to(dev), y)
         torch.cuda.synchronize()
-        ref = oracle.fwd(geom, x.cpu().numpy(), w, b)
+        ref = (oracle.fwd_relu if relu else oracle.fwd)(geom, x.cpu().numpy(), w, b)
         got = y.cpu().numpy()
         assert np.isfinite(got).all(), L.name
         tol = TOL_WINOGRAD if B.conv2d_pick_algo(geom, B.OP_FWD) == B.ALGO_WINOGRAD else TOL_IGEMM

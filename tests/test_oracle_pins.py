@@ -407,3 +407,48 @@ def test_trailing_rows_get_zero_gradient():
     dx = oracle.bwd_data(g, dy, w)
     assert (dx[0, 0, 7, :] == 0).all() and (dx[0, 0, :, 7] == 0).all()
     assert dx[0, 0, 3, 3] == 0 and dx[0, 0, 0, 0] == 1 and dx[0, 0, 4, 4] == 1
+
+
+# ----------------------------------------------------------------------------
+# forward + rectifier (oracle.fwd_relu)
+# ----------------------------------------------------------------------------
+def test_fwd_relu_hand_worked_and_identities():
+    """Pins of max(0, conv + bias): a hand-worked case with both signs; the identity
+    filter (the result is max(x, 0) bit for bit); max(a, 0) - max(-a, 0) = a with the
+    negated filter and bias (catches a flipped sign or a rectifier on the wrong side of
+    the bias); idempotence under a second rectification; no negative and no changed
+    positive value."""
+    # orientation_2x2 of the hand-worked file gives y = -4 everywhere; with bias 5 -> 1,
+    # with bias 3 -> -1 -> 0
+    g = (1, 1, 3, 3, 1, 2, 2, 1, 1, 0, 0)
+    x = f32(np.arange(1, 10).reshape(1, 1, 3, 3))
+    w = f32(np.array([1, 0, 0, -1]).reshape(1, 1, 2, 2))
+    np.testing.assert_array_equal(oracle.fwd_relu(g, x, w, f32([5.0])).ravel(), [1, 1, 1, 1])
+    np.testing.assert_array_equal(oracle.fwd_relu(g, x, w, f32([3.0])).ravel(), [0, 0, 0, 0])
+    np.testing.assert_array_equal(oracle.fwd_relu(g, x, w, None).ravel(), [0, 0, 0, 0])
+    # a filter with mixed outputs: w = [1, -1] over a row 3 1 4 1 5 -> 2 -3 3 -4 -> 2 0 3 0
+    g2 = (1, 1, 1, 5, 1, 1, 2, 1, 1, 0, 0)
+    x2 = f32(np.array([3, 1, 4, 1, 5]).reshape(1, 1, 1, 5))
+    w2 = f32(np.array([1, -1]).reshape(1, 1, 1, 2))
+    np.testing.assert_array_equal(oracle.fwd_relu(g2, x2, w2, None).ravel(), [2, 0, 3, 0])
+    np.testing.assert_array_equal(oracle.fwd_relu(g2, x2, w2, f32([0.5])).ravel(), [2.5, 0, 3.5, 0])
+
+    rng = np.random.default_rng(77)
+    gi = (2, 4, 6, 7, 4, 3, 3, 1, 1, 1, 1)
+    xi = f32(rng.standard_normal((2, 4, 6, 7)))
+    wi = np.zeros((4, 4, 3, 3), np.float32)
+    for k in range(4):
+        wi[k, k, 1, 1] = 1.0
+    np.testing.assert_array_equal(oracle.fwd_relu(gi, xi, wi, None), np.maximum(xi.astype(np.float64), 0.0))
+
+    gr = (2, 3, 7, 6, 5, 3, 2, 2, 1, 1, 0)
+    xr = f32(rng.standard_normal((2, 3, 7, 6)))
+    wr = f32(rng.standard_normal((5, 3, 3, 2)))
+    br = f32(rng.standard_normal((5,)))
+    pos = oracle.fwd_relu(gr, xr, wr, br)
+    neg = oracle.fwd_relu(gr, xr, -wr, -br)
+    lin = oracle.fwd(gr, xr, wr, br)
+    np.testing.assert_array_equal(pos - neg, lin)
+    assert (pos >= 0).all() and (pos[lin > 0] == lin[lin > 0]).all() and (pos[lin <= 0] == 0).all()
+    assert (pos > 0).any() and (pos == 0).any()
+    np.testing.assert_array_equal(np.maximum(pos, 0.0), pos)
