@@ -363,8 +363,29 @@ def chained_forward(recs, ws, stream, algo):
             torch.cuda.synchronize()
             ms.append(e0.elapsed_time(e1))
         res[mode] = min(ms)
+    # ... and with the four poolings fused as well (conv2d_fwd_relu_pool2: the unpooled maps
+    # of conv1_2, conv2_2, conv3_3 and conv4_3 are never written)
+    pooled = {r["L"].name: torch.empty((r["L"].N, r["L"].K, r["P"] // 2, r["Q"] // 2), device=outs[0].device)
+              for r in recs if r["L"].name in pool_after}
+    ms = []
+    for _ in range(3):
+        x = recs[0]["x"]
+        e0.record(stream)
+        for r, y in zip(recs, outs):
+            if r["L"].name in pool_after:
+                x_next = pooled[r["L"].name]
+                B.conv2d_fwd_relu_pool2(r["geom"], x, r["w"], r["b"], x_next, ws=ws, stream=stream)
+                x = x_next
+            else:
+                B.conv2d_fwd_relu(r["geom"], x, r["w"], r["b"], y, ws=ws, algo=algo, stream=stream)
+                x = y
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    res["pool"] = min(ms)
     print("chained forward with ReLU after every layer: %.3f ms as 13 separate in-place passes, "
-          "%.3f ms fused into the convolutions' epilogues (conv2d_fwd_relu)" % (res["separate"], res["fused"]),
+          "%.3f ms fused into the convolutions' epilogues (conv2d_fwd_relu), %.3f ms with the four "
+          "poolings fused too (conv2d_fwd_relu_pool2)" % (res["separate"], res["fused"], res["pool"]),
           file=sys.stderr)
 
 

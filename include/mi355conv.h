@@ -114,6 +114,17 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
 int conv2d_fwd_relu(const conv2d_desc *d, const float *x, const float *w, const float *bias,
                     float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
 
+/* The same followed by 2x2 / stride-2 max pooling (the pooling layers Sec. 4.1 lists next
+ * to RELU; in the VGG stack one follows the last convolution of every block):
+ * y_pooled[n,k,i,j] = max over a, b in {0,1} of max(0, conv(x,w)[n,k,2i+a,2j+b] + bias[k]),
+ * a device tensor N x K x P/2 x Q/2, overwritten; the unpooled y is never stored.  Only for
+ * layers the Winograd path takes (its 2x2 output blocks are the pooling windows) with even
+ * P and Q: otherwise CONV2D_ERR_ALGO.  Workspace:
+ * conv2d_workspace_bytes(d, CONV2D_FWD, CONV2D_ALGO_WINOGRAD).  Other arguments and errors
+ * as conv2d_fwd. */
+int conv2d_fwd_relu_pool2(const conv2d_desc *d, const float *x, const float *w, const float *bias,
+                          float *y_pooled, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Several 1x1, stride-1, unpadded convolutions of the SAME input in one pass over it
  * (Sec. 4.2 singles out GoogLeNet's 1x1 layers; its inception module applies three of
  * them to one input, and they are bound by reading that input).  Group g has K[g]

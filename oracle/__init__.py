@@ -88,6 +88,19 @@ def fwd_relu(geom, x, w, b: Optional[np.ndarray] = None) -> np.ndarray:
     return np.maximum(fwd(geom, x, w, b), 0.0)
 
 
+def fwd_relu_pool2(geom, x, w, b: Optional[np.ndarray] = None) -> np.ndarray:
+    """fwd_relu followed by the 2x2 / stride-2 max pooling of the paper's Sec. 4.1 layer
+    list: out[n,k,i,j] = max of the four rectified outputs (2i+a, 2j+b), a, b in {0,1}.
+    P and Q must be even.  Written as explicit slices, one per window position."""
+    y = fwd_relu(geom, x, w, b)
+    if y.shape[2] % 2 or y.shape[3] % 2:
+        raise ValueError("odd output size")
+    out = y[:, :, 0::2, 0::2]
+    for a_, b_ in ((0, 1), (1, 0), (1, 1)):
+        out = np.maximum(out, y[:, :, a_::2, b_::2])
+    return np.ascontiguousarray(out)
+
+
 def bwd_data(geom, dy, w) -> np.ndarray:
     g = _geom(geom)
     N, Cc, H, W, K, R, S = g[:7]

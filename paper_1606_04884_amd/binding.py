@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libmi355conv.so")
 ALGO_AUTO, ALGO_IGEMM, ALGO_WINOGRAD = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 
-EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_fwd_relu",
+EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_fwd_relu", "conv2d_fwd_relu_pool2",
            "conv2d_fwd_1x1_group", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version",
            "apply_mul_add")
 
@@ -56,6 +56,8 @@ def load() -> C.CDLL:
     lib.conv2d_fwd.restype = C.c_int
     lib.conv2d_fwd_relu.argtypes = lib.conv2d_fwd.argtypes
     lib.conv2d_fwd_relu.restype = C.c_int
+    lib.conv2d_fwd_relu_pool2.argtypes = [dp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.conv2d_fwd_relu_pool2.restype = C.c_int
     lib.conv2d_fwd_1x1_group.argtypes = [dp, vp, C.c_int32, i32p, C.POINTER(vp), C.POINTER(vp),
                                          C.POINTER(vp), vp, C.c_size_t, vp]
     lib.conv2d_fwd_1x1_group.restype = C.c_int
@@ -174,6 +176,18 @@ def conv2d_fwd_relu(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=Non
                                 _stream(stream))
     if rc:
         raise Conv2dError(rc, "conv2d_fwd_relu")
+
+
+def conv2d_fwd_relu_pool2(d, x, w, bias, y_pooled, ws=None, stream=None) -> None:
+    dd = _desc(d)
+    P, Q = conv2d_output_dims(dd)
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, ALGO_WINOGRAD))
+    rc = load().conv2d_fwd_relu_pool2(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"),
+                                      _ptr(w, (dd.K, dd.C, dd.R, dd.S), "w"), _ptr(bias, (dd.K,), "bias"),
+                                      _ptr(y_pooled, (dd.N, dd.K, P // 2, Q // 2), "y_pooled"), wptr, wbytes,
+                                      _stream(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_fwd_relu_pool2")
 
 
 def conv2d_fwd_1x1_group(d, x, ws_list, bias_list, ys, ws=None, stream=None) -> None:

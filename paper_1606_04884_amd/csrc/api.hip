@@ -559,7 +559,7 @@ bool smallc_bwd_ok(const Geom &g, const float *dy, const float *dx)
 int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
 
 int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias,
-             float *out, void *ws, size_t ws_bytes, hipStream_t s, int relu = 0)
+             float *out, void *ws, size_t ws_bytes, hipStream_t s, int relu = 0, int pool = 0)
 {
     const WinoPlan p = plan_wino(g, op);
     if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
@@ -568,7 +568,7 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
                                               op == CONV2D_FWD ? 0 : 1, p.mode != 0, s));
     if (rc) return rc;
     WinoArgs a = {};
-    a.in = in; a.U = U; a.bias = bias; a.out = out; a.relu = relu;
+    a.in = in; a.U = U; a.bias = bias; a.out = out; a.relu = relu; a.pool = pool;
     a.N = g.N; a.Cin = p.Cin; a.Cpad = p.Cpad; a.Hin = p.Hin; a.Win = p.Win;
     a.Kout = p.Kout; a.Kpad = p.Kpad; a.Hout = p.Hout; a.Wout = p.Wout;
     a.pad_h = p.pad_h; a.pad_w = p.pad_w; a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.mode = p.mode;
@@ -843,6 +843,18 @@ int conv2d_fwd_relu(const conv2d_desc *d, const float *x, const float *w, const 
                     void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream)
 {
     return fwd_impl(d, x, w, bias, y, ws, ws_bytes, algo, hip_stream, 1);
+}
+
+int conv2d_fwd_relu_pool2(const conv2d_desc *d, const float *x, const float *w, const float *bias,
+                          float *y_pooled, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    Geom g;
+    const int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (!x || !w || !y_pooled) return CONV2D_ERR_NULL;
+    // the Winograd kernels' 2x2 output blocks are the pooling windows
+    if (!wino_applicable(g, CONV2D_FWD) || g.P % 2 != 0 || g.Q % 2 != 0) return CONV2D_ERR_ALGO;
+    return run_wino(g, CONV2D_FWD, x, w, bias, y_pooled, ws, ws_bytes, (hipStream_t)hip_stream, 1, 1);
 }
 
 int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, const int32_t *K,

@@ -169,6 +169,8 @@ struct WinoArgs {
     const float *U;
     const float *bias;       // nullable
     int32_t relu;            // forward: y = max(0, product + bias)
+    int32_t pool;            // with relu, Hout and Wout even: out is the 2x2 / stride-2 max-pooled map
+                             // [N][Kout][Hout/2][Wout/2] (one pixel per tile)
     float *out;
     int32_t N, Cin, Cpad, Hin, Win, Kout, Kpad, Hout, Wout;
     int32_t pad_h, pad_w;    // patch origin = 2*tile - pad

@@ -244,7 +244,23 @@ __device__ __forceinline__ void wino_finish_tile(const WinoArgs &a, floatx16 (&a
         const int kbase = kt * KB + wm0 + 4 * lhi;
         float *ob = obase + (int64_t)kbase * HWo;
         const float *bp = a.bias ? a.bias + kbase : nullptr;
-        if (a.vec2) {
+        if (a.pool) {
+            // 2x2 / stride-2 max pooling of the rectified output: a tile's 2x2 block is one
+            // pooled pixel (Hout and Wout are even)
+            const int HWp = HWo >> 2;
+            float *opl = a.out + ((int64_t)n * a.Kout + kbase) * HWp + th * (a.Wout >> 1) + tw;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                __builtin_amdgcn_sched_barrier(0);
+                const int kr = 8 * (v >> 2) + (v & 3);
+                if (kbase + kr < a.Kout) {
+                    float y00, y01, y10, y11;
+                    out_xform(v, y00, y01, y10, y11);
+                    const float bz = bp ? bp[kr] : 0.f;
+                    opl[(int64_t)kr * HWp] = fmaxf(fmaxf(fmaxf(y00, y01), fmaxf(y10, y11)) + bz, 0.f);
+                }
+            }
+        } else if (a.vec2) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 __builtin_amdgcn_sched_barrier(0);
@@ -898,7 +914,12 @@ __device__ __forceinline__ void wino_pair_body(const WinoArgs &a, float *lds)
                 float *o = ob + (int64_t)kr * HWo;
                 y[0] += bz; y[1] += bz; y[2] += bz; y[3] += bz;
                 if (a.relu) { y[0] = fmaxf(y[0], 0.f); y[1] = fmaxf(y[1], 0.f); y[2] = fmaxf(y[2], 0.f); y[3] = fmaxf(y[3], 0.f); }
-                if (a.vec2) {
+                if (a.pool) {
+                    // one pooled pixel per tile (2x2 / stride-2 max pooling of the rectified output)
+                    const int HWp = HWo >> 2;
+                    a.out[((int64_t)n * a.Kout + kbase + kr) * HWp + th * (a.Wout >> 1) + tw] =
+                        fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3]));
+                } else if (a.vec2) {
                     *reinterpret_cast<float2 *>(o) = make_float2(y[0], y[1]);
                     if (row1) *reinterpret_cast<float2 *>(o + a.Wout) = make_float2(y[2], y[3]);
                 } else {
@@ -983,6 +1004,11 @@ __global__ __launch_bounds__(256) void wino_fixup_kernel(WinoArgs a, int G)
         float *o = obase + (int64_t)k * HWo;
         floatx4 y = {p[0] + q[0] + bz, p[1] + q[1] + bz, p[2] + q[2] + bz, p[3] + q[3] + bz};
         if (a.relu) { y[0] = fmaxf(y[0], 0.f); y[1] = fmaxf(y[1], 0.f); y[2] = fmaxf(y[2], 0.f); y[3] = fmaxf(y[3], 0.f); }
+        if (a.pool) {
+            const int HWp = HWo >> 2;
+            a.out[((int64_t)n * a.Kout + k) * HWp + th * (a.Wout >> 1) + tw] = fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3]));
+            continue;
+        }
         o[0] = y[0];
         if (col1) o[1] = y[1];
         if (row1) {

@@ -70,3 +70,45 @@ def test_fwd_relu_without_bias_and_argument_checks():
         B.conv2d_fwd_relu((2, 16, 9, 9, 24, 9, 9, 1, 1, 0, 0), torch.zeros((2, 16, 9, 9), device=dev),
                           torch.zeros((24, 16, 9, 9), device=dev), None, torch.zeros((2, 24, 1, 1), device=dev),
                           algo=B.ALGO_WINOGRAD)
+
+
+POOL_SHAPES = [
+    (2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1),       # tile-pair kernel
+    (2, 3, 24, 24, 32, 3, 3, 1, 1, 1, 1),        # tile pairs, ragged chunk (first layer)
+    (3, 32, 14, 14, 48, 3, 3, 1, 1, 1, 1),       # general Winograd kernel (7 tiles per row)
+    (2, 32, 26, 26, 40, 5, 5, 1, 1, 2, 2),       # four 3x3 sub-filters
+    (2, 16, 10, 12, 20, 3, 3, 1, 1, 0, 0),       # unpadded: 8 x 10 output
+    (9, 128, 28, 28, 128, 3, 3, 1, 1, 1, 1),     # tiles cut by the persistent schedule: fix-up kernel pools too
+]
+
+
+@pytest.mark.parametrize("geom", POOL_SHAPES, ids=["x".join(map(str, g)) for g in POOL_SHAPES])
+def test_fwd_relu_pool2_parity(geom):
+    import torch
+    x, w, b, _ = random_layer(geom, 15200 + sum(geom))
+    print("geom", geom, flush=True)
+    dev = torch.device("cuda:0")
+    N, C, H, W, K = geom[:5]
+    P, Q = B.conv2d_output_dims(geom)
+    tx, tw, tb = (torch.from_numpy(a).to(dev) for a in (x, w, b))
+    yp = torch.full((N, K, P // 2, Q // 2), float("nan"), device=dev)
+    yr = torch.full((N, K, P, Q), float("nan"), device=dev)
+    B.conv2d_fwd_relu_pool2(geom, tx, tw, tb, yp)
+    B.conv2d_fwd_relu(geom, tx, tw, tb, yr, algo=B.ALGO_WINOGRAD)
+    torch.cuda.synchronize()
+    got = yp.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert max_err_ratio(got, oracle.fwd_relu_pool2(geom, x, w, b)) <= TOL_WINOGRAD
+    # the same sums as the unpooled entry point: pooling its output gives the same bits
+    full = yr.cpu().numpy()
+    assert np.array_equal(got, full.reshape(N, K, P // 2, 2, Q // 2, 2).max(axis=(3, 5)))
+
+
+def test_fwd_relu_pool2_refusals():
+    import torch
+    dev = torch.device("cuda:0")
+    z = lambda *s: torch.zeros(s, device=dev)
+    with pytest.raises(B.Conv2dError):      # odd map
+        B.conv2d_fwd_relu_pool2((1, 8, 13, 13, 8, 3, 3, 1, 1, 1, 1), z(1, 8, 13, 13), z(8, 8, 3, 3), None, z(1, 8, 6, 6))
+    with pytest.raises(B.Conv2dError):      # not a layer the Winograd path takes
+        B.conv2d_fwd_relu_pool2((1, 8, 12, 12, 8, 1, 1, 1, 1, 0, 0), z(1, 8, 12, 12), z(8, 8, 1, 1), None, z(1, 8, 6, 6))

@@ -452,3 +452,31 @@ def test_fwd_relu_hand_worked_and_identities():
     assert (pos >= 0).all() and (pos[lin > 0] == lin[lin > 0]).all() and (pos[lin <= 0] == 0).all()
     assert (pos > 0).any() and (pos == 0).any()
     np.testing.assert_array_equal(np.maximum(pos, 0.0), pos)
+
+
+def test_fwd_relu_pool2_hand_worked_and_bruteforce():
+    """Pins of the rectified, 2x2-max-pooled forward: a case small enough for pencil and
+    paper, a plain-loop evaluation on random data, and the refusal of odd maps."""
+    # 1x1 filter w = 1, bias -6 over x = 0..15: y = x - 6, rectified
+    #   0 0 0 0 / 0 0 0 1 / 2 3 4 5 / 6 7 8 9   ->  pooled  0 1 / 7 9
+    g = (1, 1, 4, 4, 1, 1, 1, 1, 1, 0, 0)
+    x = f32(np.arange(16).reshape(1, 1, 4, 4))
+    w = f32(np.ones((1, 1, 1, 1)))
+    np.testing.assert_array_equal(oracle.fwd_relu_pool2(g, x, w, f32([-6.0])).ravel(), [0, 1, 7, 9])
+    rng = np.random.default_rng(78)
+    gr = (2, 3, 8, 6, 4, 3, 3, 1, 1, 1, 1)
+    xr = f32(rng.standard_normal((2, 3, 8, 6)))
+    wr = f32(rng.standard_normal((4, 3, 3, 3)))
+    br = f32(rng.standard_normal((4,)))
+    got = oracle.fwd_relu_pool2(gr, xr, wr, br)
+    lin = oracle.fwd(gr, xr, wr, br)
+    assert got.shape == (2, 4, 4, 3)
+    for n in range(2):
+        for k in range(4):
+            for i in range(4):
+                for j in range(3):
+                    m = max(0.0, max(lin[n, k, 2 * i + a, 2 * j + b] for a in (0, 1) for b in (0, 1)))
+                    assert got[n, k, i, j] == m
+    with pytest.raises(ValueError):
+        oracle.fwd_relu_pool2((1, 1, 3, 3, 1, 3, 3, 1, 1, 1, 1), f32(np.zeros((1, 1, 3, 3))),
+                              f32(np.zeros((1, 1, 3, 3))), None)
