@@ -77,8 +77,13 @@ enum {
                                     H+2*pad_h < R (or W), tensor >= 2^31 elements */
     CONV2D_ERR_ALGO = -3,        /* algorithm cannot do this geometry / unknown   */
     CONV2D_ERR_WORKSPACE = -4,   /* workspace null or smaller than required       */
-    CONV2D_ERR_LAUNCH = -5       /* HIP reported a launch error                   */
+    CONV2D_ERR_LAUNCH = -5,      /* HIP reported a launch error                   */
+    CONV2D_ERR_STATIC_LIMIT = -6 /* conv2d_fwd_static: the layer needs more workspace
+                                    than CONV2D_STATIC_SCRATCH_BYTES              */
 };
+
+/* Size of the library-owned scratch area conv2d_fwd_static works in (per GPU). */
+#define CONV2D_STATIC_SCRATCH_BYTES (64u << 20)
 
 /* Output height P and width Q (Sec. 4.2 lowering: one column per output pixel).
  * Host-only, touches no device. */
@@ -103,6 +108,22 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
  * default stream). */
 int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias,
                float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
+
+/* conv2d_fwd for callers that cannot allocate or own device memory beyond their
+ * tensors: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same result as conv2d_fwd(d, x, w, bias, y, ws, ..., algo, hip_stream)
+ * (same kernels, same summation order), but the workspace is a library-owned static
+ * device array of CONV2D_STATIC_SCRATCH_BYTES (64 MiB) that every GPU the library runs
+ * on holds from the load of its code until the process ends; the call itself allocates
+ * and frees nothing.  A layer with conv2d_workspace_bytes(d, CONV2D_FWD, algo) above that
+ * size is refused with CONV2D_ERR_STATIC_LIMIT and nothing is enqueued (every layer of the
+ * AlexNet, VGG-16 and inception configurations fits; filter banks beyond about 512 x 512
+ * of 3x3 do not).  All calls on one GPU share that one area, which keeps the previous
+ * call's contents (nothing in it needs to start at zero): calls that overlap on one GPU,
+ * i.e. on different streams without ordering between them, race.  Calls on one stream
+ * are ordered and safe.  The current device must be the one the tensors live on. */
+int conv2d_fwd_static(const conv2d_desc *d, const float *x, const float *w, const float *bias,
+                      float *y, conv2d_algo algo, void *hip_stream);
 
 /* Forward followed by the rectifier of the layer after it, in the same epilogue:
  * y = max(0, conv(x, w) + bias), stored once.  (Sec. 4.1 lists the RELU layers as the

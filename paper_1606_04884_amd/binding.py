@@ -16,7 +16,10 @@ LIB_PATH = os.path.join(_HERE, "libmi355conv.so")
 ALGO_AUTO, ALGO_IGEMM, ALGO_WINOGRAD = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 
-EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_fwd_relu", "conv2d_fwd_relu_pool2",
+STATIC_SCRATCH_BYTES = 64 << 20
+
+EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_fwd_static",
+           "conv2d_fwd_relu", "conv2d_fwd_relu_pool2",
            "conv2d_fwd_1x1_group", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version",
            "apply_mul_add")
 
@@ -54,6 +57,8 @@ def load() -> C.CDLL:
     lib.conv2d_workspace_bytes.restype = C.c_size_t
     lib.conv2d_fwd.argtypes = [dp, vp, vp, vp, vp, vp, C.c_size_t, C.c_int, vp]
     lib.conv2d_fwd.restype = C.c_int
+    lib.conv2d_fwd_static.argtypes = [dp, vp, vp, vp, vp, C.c_int, vp]
+    lib.conv2d_fwd_static.restype = C.c_int
     lib.conv2d_fwd_relu.argtypes = lib.conv2d_fwd.argtypes
     lib.conv2d_fwd_relu.restype = C.c_int
     lib.conv2d_fwd_relu_pool2.argtypes = [dp, vp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -164,6 +169,18 @@ def conv2d_fwd(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=None) ->
                            _stream(stream))
     if rc:
         raise Conv2dError(rc, "conv2d_fwd")
+
+
+def conv2d_fwd_static(d, x, w, bias, y, algo: int = ALGO_AUTO, stream=None) -> None:
+    """conv2d_fwd with the library's own static scratch area as workspace: nothing is
+    allocated here or in the library."""
+    dd = _desc(d)
+    P, Q = conv2d_output_dims(dd)
+    rc = load().conv2d_fwd_static(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"),
+                                  _ptr(w, (dd.K, dd.C, dd.R, dd.S), "w"), _ptr(bias, (dd.K,), "bias"),
+                                  _ptr(y, (dd.N, dd.K, P, Q), "y"), int(algo), _stream(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_fwd_static")
 
 
 def conv2d_fwd_relu(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=None) -> None:

@@ -4,9 +4,40 @@
 #include "../../include/mi355conv.h"
 #include "conv_internal.h"
 
+#include <atomic>
+
 using namespace mi355conv;
 
+// Workspace of conv2d_fwd_static: one copy per GPU, loaded with this code object and held
+// until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returns (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[CONV2D_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device; two
+// threads racing on the first call store the same value).  nullptr + *rc on failure.
+void *static_scratch(int *rc)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        *rc = CONV2D_ERR_LAUNCH;
+        return nullptr;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            *rc = CONV2D_ERR_LAUNCH;
+            return nullptr;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *rc = CONV2D_OK;
+    return p;
+}
 
 constexpr int32_t kMaxDim = 16383;          // tap displacements are packed in 16 bits
 constexpr int64_t kMaxElems = (int64_t(1) << 31) - 1;
@@ -845,6 +876,26 @@ int conv2d_fwd_relu(const conv2d_desc *d, const float *x, const float *w, const 
     return fwd_impl(d, x, w, bias, y, ws, ws_bytes, algo, hip_stream, 1);
 }
 
+int conv2d_fwd_static(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
+                      conv2d_algo algo, void *hip_stream)
+{
+    Geom g;
+    int rc = check_desc(d, &g);
+    if (rc) return rc;
+    if (!x || !w || !y) return CONV2D_ERR_NULL;
+    const int al = resolve_algo(g, CONV2D_FWD, (int)algo);
+    if (al < 0) return al;
+    // what conv2d_fwd would ask of the caller; nothing in it has to start at zero (the
+    // filter matrix / transformed filters and the cut-tile slots are written before they
+    // are read), so the last call's contents may stay
+    const size_t need = conv2d_workspace_bytes(d, CONV2D_FWD, algo);
+    if (need == 0) return CONV2D_ERR_ALGO;
+    if (need > (size_t)CONV2D_STATIC_SCRATCH_BYTES) return CONV2D_ERR_STATIC_LIMIT;
+    void *ws = static_scratch(&rc);
+    if (!ws) return rc;
+    return fwd_impl(d, x, w, bias, y, ws, (size_t)CONV2D_STATIC_SCRATCH_BYTES, algo, hip_stream, 0);
+}
+
 int conv2d_fwd_relu_pool2(const conv2d_desc *d, const float *x, const float *w, const float *bias,
                           float *y_pooled, void *ws, size_t ws_bytes, void *hip_stream)
 {
@@ -1162,6 +1213,7 @@ const char *conv2d_status_string(int status)
     case CONV2D_ERR_ALGO: return "algorithm not applicable to this geometry";
     case CONV2D_ERR_WORKSPACE: return "workspace missing or too small";
     case CONV2D_ERR_LAUNCH: return "HIP launch error";
+    case CONV2D_ERR_STATIC_LIMIT: return "layer needs more workspace than the library's static scratch area holds";
     default: return "unknown status";
     }
 }

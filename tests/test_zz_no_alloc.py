@@ -1,0 +1,93 @@
+"""conv2d_fwd_static (the forward entry point that works in the library's own static
+scratch area and allocates nothing) against conv2d_fwd with a caller workspace, through
+the raw C ABI: two calls in a row, the second on a smaller layer, so the second call
+finds the first call's contents in the shared area."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from paper_1606_04884_amd import binding as B
+from paper_1606_04884_amd import synth
+
+from gpu_util import TOL_IGEMM, TOL_WINOGRAD, max_err_ratio
+
+pytestmark = pytest.mark.gpu
+
+# (geometry, algorithm): Winograd with cut tiles and a fix-up pass (workspace: transformed
+# filters + cut-tile slots), then a smaller layer through the gather kernel (workspace:
+# filter matrix + gather table), then smaller still through Winograd again
+CASES = [
+    ((6, 64, 30, 30, 96, 3, 3, 1, 1, 1, 1), B.ALGO_WINOGRAD),
+    ((3, 24, 17, 13, 40, 3, 3, 2, 1, 1, 1), B.ALGO_IGEMM),
+    ((2, 32, 12, 12, 64, 3, 3, 1, 1, 1, 1), B.ALGO_AUTO),
+]
+
+
+def _tensors(geom, seed, dev):
+    import torch
+    N, Cc, H, W, K, R, S = geom[:7]
+    P, Q = B.conv2d_output_dims(geom)
+    x = torch.from_numpy(synth.normal((N, Cc, H, W), seed)).to(dev)
+    w = torch.from_numpy(synth.normal((K, Cc, R, S), seed + 1, std=float(np.sqrt(2.0 / (Cc * R * S))))).to(dev)
+    b = torch.from_numpy(synth.uniform((K,), seed + 2, -0.1, 0.1)).to(dev)
+    return x, w, b, (N, K, P, Q)
+
+
+def test_static_scratch_forward_matches_workspace_forward():
+    import torch
+    dev = torch.device("cuda:0")
+    lib = B.load()
+    stream = torch.cuda.current_stream().cuda_stream
+    prepared = []
+    for i, (geom, algo) in enumerate(CASES):
+        x, w, b, yshape = _tensors(geom, 7100 + 10 * i, dev)
+        need = B.conv2d_workspace_bytes(geom, B.OP_FWD, algo)
+        assert 0 < need <= B.STATIC_SCRATCH_BYTES
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        y_ref = torch.full(yshape, float("nan"), device=dev)
+        y_new = torch.full(yshape, float("nan"), device=dev)
+        prepared.append((geom, algo, x, w, b, ws, y_ref, y_new))
+    torch.cuda.synchronize()
+    # every buffer exists: the calls below go straight to the C ABI, back to back
+    for geom, algo, x, w, b, ws, y_ref, y_new in prepared:
+        d = B.make_desc(geom)
+        rc = lib.conv2d_fwd(C.byref(d), x.data_ptr(), w.data_ptr(), b.data_ptr(), y_ref.data_ptr(),
+                            ws.data_ptr(), ws.numel(), algo, stream)
+        assert rc == 0, B.status_string(rc)
+    for geom, algo, x, w, b, ws, y_ref, y_new in prepared:
+        d = B.make_desc(geom)
+        rc = lib.conv2d_fwd_static(C.byref(d), x.data_ptr(), w.data_ptr(), b.data_ptr(), y_new.data_ptr(),
+                                   algo, stream)
+        assert rc == 0, B.status_string(rc)
+    torch.cuda.synchronize()
+    for geom, algo, x, w, b, ws, y_ref, y_new in prepared:
+        ref = y_ref.cpu().numpy()
+        got = y_new.cpu().numpy()
+        assert np.isfinite(ref).all() and np.isfinite(got).all(), geom
+        resolved = algo if algo != B.ALGO_AUTO else B.conv2d_pick_algo(geom, B.OP_FWD)
+        tol = TOL_WINOGRAD if resolved == B.ALGO_WINOGRAD else TOL_IGEMM
+        assert max_err_ratio(got, ref.astype(np.float64)) <= tol, geom
+        # same kernels, same summation order: in fact the same bits
+        np.testing.assert_array_equal(got, ref, err_msg=str(geom))
+
+
+def test_static_scratch_limit_and_argument_errors():
+    import torch
+    lib = B.load()
+    dev = torch.device("cuda:0")
+    one = torch.zeros(16, device=dev)
+    p = one.data_ptr()
+    # Overfeat-sized 1024 -> 1024 3x3 layer: transformed filters alone are 64 MiB
+    big = (2, 1024, 12, 12, 1024, 3, 3, 1, 1, 1, 1)
+    assert B.conv2d_workspace_bytes(big, B.OP_FWD) > B.STATIC_SCRATCH_BYTES
+    d = B.make_desc(big)
+    assert lib.conv2d_fwd_static(C.byref(d), p, p, None, p, B.ALGO_AUTO, None) == -6
+    assert "static" in B.status_string(-6)
+    small = B.make_desc(CASES[2][0])
+    assert lib.conv2d_fwd_static(None, p, p, None, p, 0, None) == -1
+    assert lib.conv2d_fwd_static(C.byref(small), None, p, None, p, 0, None) == -1
+    assert lib.conv2d_fwd_static(C.byref(small), p, p, None, p, 9, None) == -3
+    bad = B.make_desc((0, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1))
+    assert lib.conv2d_fwd_static(C.byref(bad), p, p, None, p, 0, None) == -2
+    torch.cuda.synchronize()
