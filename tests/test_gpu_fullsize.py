@@ -1,7 +1,10 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch
 configuration bench.py times (same entry points, same AUTO algorithm choice).
-The full tensors are too large for the oracle's full loops, so the oracle
-computes randomly sampled output elements one by one (each output element is an
+
+test_fullsize_full_tensor compares EVERY element of y, dx, dw and db of every layer of
+the four full-size configurations with the oracle's full loops (a few minutes of host
+time on the GPU machine's cores in total).  test_fullsize_sampled is the quick variant: the
+oracle computes randomly sampled output elements one by one (each output element is an
 independent sum, so a sampled oracle is still the exact definition)."""
 import numpy as np
 import pytest
@@ -17,18 +20,19 @@ from gpu_util import TOL_IGEMM, TOL_WINOGRAD           # noqa: E402
 
 # every layer of every full-size configuration (AlexNet, VGG-16, inception, Overfeat)
 CASES = [(cfg, li) for cfg in (1, 2, 3, 4) for li in range(len(synth.config_layers(cfg)))]
-MAC_BUDGET = 1.5e9          # oracle multiply-adds per sampled tensor
+MAC_BUDGET = 6e9            # oracle multiply-adds per sampled tensor
+MAX_SAMPLES = 100000
 
 
 def tol_for(geom, op):
     return TOL_WINOGRAD if B.conv2d_pick_algo(geom, op) == B.ALGO_WINOGRAD else TOL_IGEMM
 
 
-@pytest.mark.parametrize("cfg,li", CASES, ids=["cfg%d_layer%d" % c for c in CASES])
-def test_fullsize_sampled(cfg, li):
+def run_layer(cfg, li):
+    """The three passes of one layer at its full size, as bench.py launches them: inputs
+    drawn on the device (seeded), outputs pre-filled with NaN."""
     L = synth.config_layers(cfg)[li]
     geom = L.desc()
-    print("case", cfg, li, L, flush=True)
     P, Q = B.conv2d_output_dims(geom)
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
@@ -45,11 +49,53 @@ def test_fullsize_sampled(cfg, li):
     B.conv2d_bwd_data(geom, dy, w, dx)
     B.conv2d_bwd_weight(geom, x, dy, dw, db)
     torch.cuda.synchronize()
+    return L, geom, (P, Q), (x, w, b, dy), (y, dx, dw, db)
+
+
+@pytest.mark.parametrize("cfg,li", CASES, ids=["cfg%d_layer%d" % c for c in CASES])
+def test_fullsize_full_tensor(cfg, li, capsys):
+    """Every element of every output, full batch, against the oracle's full loops."""
+    L, geom, (P, Q), (x, w, b, dy), outs = run_layer(cfg, li)
+    dev = x.device
+    hx, hw, hb, hdy = (t.cpu().numpy() for t in (x, w, b, dy))
+    del x, w, b, dy
+    tols = {"y": tol_for(geom, B.OP_FWD), "dx": tol_for(geom, B.OP_BWD_DATA),
+            "dw": tol_for(geom, B.OP_BWD_WEIGHT), "db": tol_for(geom, B.OP_BWD_WEIGHT)}
+    ratios = {}
+
+    def compare(name, got, ref64):
+        # the comparison itself runs on the device (fp64), on the whole tensor
+        ref = torch.from_numpy(ref64).to(dev)
+        assert ref.shape == got.shape
+        scale = float(ref.abs().max())
+        diff = (got.double() - ref).abs()
+        assert not torch.isnan(diff).any(), "%s has unwritten or NaN elements" % name
+        ratios[name] = float(diff.max()) / scale
+        del ref, diff
+
+    y, dx, dw, db = outs
+    compare("y", y, oracle.fwd(geom, hx, hw, hb))
+    compare("dx", dx, oracle.bwd_data(geom, hdy, hw))
+    rdw, rdb = oracle.bwd_weight(geom, hx, hdy)
+    compare("dw", dw, rdw)
+    compare("db", db, rdb)
+    with capsys.disabled():
+        print("\nfull-tensor parity cfg%d layer%d %s: max|gpu-ref|/max|ref| " % (cfg, li, tuple(geom)) +
+              " ".join("%s %.2e (tol %.0e)" % (k, v, tols[k]) for k, v in ratios.items()), flush=True)
+    for k, v in ratios.items():
+        assert v <= tols[k], "%s: %.3e > %.0e" % (k, v, tols[k])
+
+
+@pytest.mark.parametrize("cfg,li", CASES, ids=["cfg%d_layer%d" % c for c in CASES])
+def test_fullsize_sampled(cfg, li):
+    print("case", cfg, li, flush=True)
+    L, geom, (P, Q), (x, w, b, dy), (y, dx, dw, db) = run_layer(cfg, li)
+    dev = x.device
     hx, hw, hb, hdy = (t.cpu().numpy() for t in (x, w, b, dy))
     rng = np.random.default_rng(1000 * cfg + li)
 
     def check(name, got_t, n_total, macs_per_elem, fn, tol):
-        n = int(max(64, min(50000, MAC_BUDGET // max(1, macs_per_elem))))
+        n = int(max(64, min(MAX_SAMPLES, MAC_BUDGET // max(1, macs_per_elem))))
         idx = rng.integers(0, n_total, size=n)
         ref = fn(idx)
         got = got_t.reshape(-1)[torch.from_numpy(idx).to(dev)].cpu().numpy().astype(np.float64)
