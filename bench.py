@@ -41,6 +41,10 @@ def executed_flops(L, P, Q, op, algo):
     direct count for the implicit GEMM; for Winograd F(2x2,3x3) the 16 GEMMs,
     2*16*K*C per 2x2 tile (tiles of the pass's output: y for fwd/bwd_weight, dx for
     bwd_data)."""
+    if algo == 3:
+        # F(4x4,3x3): 36 GEMMs, 2*36*K*C per 4x4 tile of the pass's output
+        th, tw = (-(-L.H // 4), -(-L.W // 4)) if op == "bwd_data" else (-(-P // 4), -(-Q // 4))
+        return 72.0 * L.N * th * tw * L.K * L.C
     if algo != 2:
         return layer_flops(L, P, Q)
     if L.stride > 1:
@@ -63,7 +67,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="vgg16", choices=sorted(WORKLOADS))
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
-    ap.add_argument("--algo", type=int, default=0, help="0 auto, 1 implicit GEMM, 2 Winograd")
+    ap.add_argument("--algo", type=int, default=0,
+                    help="0 auto, 1 implicit GEMM, 2 Winograd F(2x2,3x3) fused, 3 Winograd F(4x4,3x3) unfused; "
+                         "calls the algorithm cannot serve use auto")
     ap.add_argument("--detail", action="store_true", help="per-layer table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -107,13 +113,15 @@ def main() -> int:
                    y=torch.empty_like(dy), dx=torch.empty_like(x), dw=torch.empty_like(w),
                    db=torch.empty_like(b), flops=layer_flops(L, P, Q))
         rec["algo"] = {}
+        rec["req"] = {}          # the algo argument of the call: --algo where it applies, else AUTO
         rec["xflops"] = {}
         for name, op in (("fwd", B.OP_FWD), ("bwd_data", B.OP_BWD_DATA), ("bwd_weight", B.OP_BWD_WEIGHT)):
-            al = args.algo if args.algo else B.conv2d_pick_algo(rec["geom"], op)
+            req = args.algo if args.algo and B.conv2d_workspace_bytes(rec["geom"], op, args.algo) else 0
+            al = req if req else B.conv2d_pick_algo(rec["geom"], op)
+            rec["req"][name] = req
             rec["algo"][name] = al
             rec["xflops"][name] = executed_flops(L, P, Q, name, al)
-        for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
-            ws_need = max(ws_need, B.conv2d_workspace_bytes(rec["geom"], op, args.algo))
+            ws_need = max(ws_need, B.conv2d_workspace_bytes(rec["geom"], op, req))
         recs.append(rec)
     ws = B.alloc_workspace(ws_need, dev)
     stream = torch.cuda.current_stream()
@@ -125,7 +133,7 @@ def main() -> int:
             if record:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
-            B.conv2d_fwd(r["geom"], r["x"], r["w"], r["b"], r["y"], ws=ws, algo=args.algo, stream=stream)
+            B.conv2d_fwd(r["geom"], r["x"], r["w"], r["b"], r["y"], ws=ws, algo=r["req"]["fwd"], stream=stream)
             if record:
                 e1.record(stream)
                 ev.append(("fwd", li, e0, e1))
@@ -134,10 +142,10 @@ def main() -> int:
             if record:
                 e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 e0.record(stream)
-            B.conv2d_bwd_data(r["geom"], r["dy"], r["w"], r["dx"], ws=ws, algo=args.algo, stream=stream)
+            B.conv2d_bwd_data(r["geom"], r["dy"], r["w"], r["dx"], ws=ws, algo=r["req"]["bwd_data"], stream=stream)
             if record:
                 e1.record(stream)
-            B.conv2d_bwd_weight(r["geom"], r["x"], r["dy"], r["dw"], r["db"], ws=ws, algo=args.algo,
+            B.conv2d_bwd_weight(r["geom"], r["x"], r["dy"], r["dw"], r["db"], ws=ws, algo=r["req"]["bwd_weight"],
                                 stream=stream)
             if record:
                 e2.record(stream)
@@ -169,6 +177,8 @@ def main() -> int:
         per.setdefault((op, li), []).append(e0.elapsed_time(e1))
     # kernel families: which main kernel served the call
     def family(op, li):
+        if recs[li]["algo"][op] == 3:
+            return "wino4 (wino4_gemm_kernel + transform kernels: unfused F(4x4,3x3) fwd + bwd_data calls)"
         wino = recs[li]["algo"][op] == 2
         if op == "bwd_weight":
             return ("wino_wgrad (wino_wgrad_vec_kernel / wino_wgrad_kernel: Winograd bwd_weight calls)" if wino
@@ -195,7 +205,7 @@ def main() -> int:
                 tf = r["flops"] / (ms * 1e-3) / 1e12
                 xtf = r["xflops"][op] / (ms * 1e-3) / 1e12
                 print("%-12s %-10s %-5s %9.3f %10.2f %8.1f %10.2f" % (
-                    r["L"].name, op, "wino" if r["algo"][op] == 2 else "igemm", ms, tf,
+                    r["L"].name, op, {2: "wino", 3: "wino4"}.get(r["algo"][op], "igemm"), ms, tf,
                     100 * tf / PEAK_MFMA_FP32_TFLOPS, xtf), file=sys.stderr)
         for op in op_ms:
             print("total %-10s %9.3f ms/step" % (op, op_ms[op] / args.steps), file=sys.stderr)

@@ -55,13 +55,18 @@ typedef struct {
 typedef enum {
     CONV2D_ALGO_AUTO = 0,        /* library picks (see conv2d_pick_algo)          */
     CONV2D_ALGO_IGEMM = 1,       /* implicit GEMM on fp32 MFMA, any geometry      */
-    CONV2D_ALGO_WINOGRAD = 2     /* F(2x2,3x3), stride 1: 3x3 filters, and filters up
+    CONV2D_ALGO_WINOGRAD = 2,    /* F(2x2,3x3), stride 1: 3x3 filters, and filters up
                                   * to 6x6 as sums of 3x3 sub-filters of shifted
                                   * inputs; stride 2..4 (both directions equal) with a
                                   * filter spanning exactly 3 x 3 strides (11x11/4,
                                   * 5x5/2, ...): as the stride-1 3x3 layer over the
                                   * space-to-depth rearrangement of the input, which
                                   * the workspace then holds a copy of              */
+    CONV2D_ALGO_WINOGRAD4 = 3    /* F(4x4,3x3), 3x3 stride-1 filters: filter, input and
+                                  * output transforms as separate kernels around 36
+                                  * batched GEMMs; the workspace holds the transformed
+                                  * input and the products (2.25 x the layer's input and
+                                  * output each).  Forward and backward-data             */
 } conv2d_algo;
 
 typedef enum {
@@ -118,7 +123,10 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
  * and frees nothing.  A layer with conv2d_workspace_bytes(d, CONV2D_FWD, algo) above that
  * size is refused with CONV2D_ERR_STATIC_LIMIT and nothing is enqueued (every layer of the
  * AlexNet, VGG-16 and inception configurations fits; filter banks beyond about 512 x 512
- * of 3x3 do not).  All calls on one GPU share that one area, which keeps the previous
+ * of 3x3 do not).  With CONV2D_ALGO_AUTO, a layer for which AUTO's choice is the unfused
+ * F(4x4,3x3) path (whose workspace holds whole transformed tensors) and does not fit is
+ * computed by the fused F(2x2,3x3) kernels instead; the result then differs from
+ * conv2d_fwd's by rounding only.  All calls on one GPU share that one area, which keeps the previous
  * call's contents (nothing in it needs to start at zero): calls that overlap on one GPU,
  * i.e. on different streams without ordering between them, race.  Calls on one stream
  * are ordered and safe.  The current device must be the one the tensors live on. */

@@ -5,6 +5,7 @@
 #include "conv_internal.h"
 
 #include <atomic>
+#include <cstdlib>
 
 using namespace mi355conv;
 
@@ -358,6 +359,96 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
     return p;
 }
 
+int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
+
+// ---- Winograd F(4x4,3x3), unfused (wino4.hip) --------------------------------
+struct W4Plan {
+    bool ok;
+    int Cin, Kout, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, Tpad, Kpad, chunks, cfg, split, split_tiles;
+    size_t u_bytes, v_bytes, m_bytes, slot_bytes, total_bytes;
+};
+
+W4Plan plan_wino4(const Geom &g, conv2d_op op)
+{
+    W4Plan p = {};
+    if (op == CONV2D_BWD_WEIGHT) return p;
+    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph > 2 || g.pw > 2) return p;
+    const bool fwd = op == CONV2D_FWD;
+    p.Cin = fwd ? g.C : g.K;
+    p.Kout = fwd ? g.K : g.C;
+    p.Hin = fwd ? g.H : g.P;
+    p.Win = fwd ? g.W : g.Q;
+    p.Hout = fwd ? g.P : g.H;
+    p.Wout = fwd ? g.Q : g.W;
+    p.pad_h = fwd ? g.ph : 2 - g.ph;
+    p.pad_w = fwd ? g.pw : 2 - g.pw;
+    p.TH = ceil_div(p.Hout, 4);
+    p.TW = ceil_div(p.Wout, 4);
+    const int64_t T = (int64_t)g.N * p.TH * p.TW;
+    if (T > (int64_t(1) << 24) || p.Kout > 65535) return p;
+    p.T = (int)T;
+    p.chunks = ceil_div(p.Cin, 8);
+    // the workgroup tile that pads the product least (ties: the wider column tile)
+    int64_t best = -1;
+    for (int cfg = 0; cfg < 2; ++cfg) {
+        const int64_t cost = (int64_t)round_up(p.Kout, wino4_tile_m(cfg)) * round_up(p.T, wino4_tile_n(cfg));
+        if (best < 0 || cost < best) { best = cost; p.cfg = cfg; }
+    }
+    p.Kpad = round_up(p.Kout, wino4_tile_m(p.cfg));
+    p.Tpad = round_up(p.T, wino4_tile_n(p.cfg));
+    // 32-bit byte offsets inside one position's slice of each operand, and inside `in`
+    if ((int64_t)p.chunks * 2 * p.Kpad * 16 >= (int64_t(1) << 31)) return p;
+    if ((int64_t)p.chunks * 2 * p.Tpad * 16 >= (int64_t(1) << 31)) return p;
+    if ((int64_t)g.N * p.Cin * p.Hin * p.Win * 4 >= (int64_t(1) << 31)) return p;
+    p.u_bytes = align_up((size_t)36 * p.chunks * 8 * p.Kpad * sizeof(float), 256);
+    p.v_bytes = align_up((size_t)36 * p.chunks * 8 * p.Tpad * sizeof(float), 256);
+    p.m_bytes = align_up((size_t)36 * p.Kpad * p.Tpad * sizeof(float), 256);
+    // 512 workgroups are resident (two per compute unit) and all take equally long, so the
+    // GEMM runs in rounds; the tiles of the last, partly filled round are cut into `split`
+    // equal depth shares when that fills the round(s) better.  Cost of a share in chunk
+    // times: its chunks plus ~4 for start-up and the store of the partial tile.
+    const int64_t tiles = (int64_t)36 * (p.Kpad / wino4_tile_m(p.cfg)) * (p.Tpad / wino4_tile_n(p.cfg));
+    if (tiles >= (int64_t(1) << 24)) return p;
+    const int rem = (int)(tiles % 512);
+    p.split = 1;
+    p.split_tiles = 0;
+    if (rem > 0) {
+        double best_t = (double)p.chunks + 4.0;           // one more round of whole tiles
+        for (int sp = 2; sp <= 8 && sp <= p.chunks && rem * sp <= 1024; ++sp) {
+            const double t = (double)ceil_div(rem * sp, 512) * ((double)ceil_div(p.chunks, sp) + 4.0) + 2.0;
+            if (t < best_t) { best_t = t; p.split = sp; }
+        }
+        if (p.split > 1) p.split_tiles = rem;
+    }
+    p.slot_bytes = align_up((size_t)p.split_tiles * p.split * wino4_tile_m(p.cfg) * wino4_tile_n(p.cfg) * sizeof(float), 256);
+    p.total_bytes = p.u_bytes + p.v_bytes + p.m_bytes + p.slot_bytes;
+    p.ok = true;
+    return p;
+}
+
+int run_wino4(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias, float *out,
+              void *ws, size_t ws_bytes, hipStream_t s, int relu = 0)
+{
+    const W4Plan p = plan_wino4(g, op);
+    if (!p.ok) return CONV2D_ERR_ALGO;
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    W4Args a = {};
+    a.in = in; a.w = w; a.bias = bias; a.out = out; a.relu = relu;
+    a.U = (float *)ws;
+    a.V = (float *)((char *)ws + p.u_bytes);
+    a.M = (float *)((char *)ws + p.u_bytes + p.v_bytes);
+    a.slots = (float *)((char *)ws + p.u_bytes + p.v_bytes + p.m_bytes);
+    a.split = p.split; a.split_tiles = p.split_tiles;
+    a.mode = op == CONV2D_FWD ? 0 : 1;
+    a.C = g.C;
+    a.N = g.N; a.Cin = p.Cin; a.Hin = p.Hin; a.Win = p.Win; a.Kout = p.Kout; a.Kpad = p.Kpad;
+    a.Hout = p.Hout; a.Wout = p.Wout; a.pad_h = p.pad_h; a.pad_w = p.pad_w;
+    a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.Tpad = p.Tpad; a.chunks = p.chunks;
+    a.in_bytes = (int32_t)((int64_t)g.N * p.Cin * p.Hin * p.Win * 4);
+    a.tile_cfg = p.cfg;
+    return launch_status(launch_wino4(a, s));
+}
+
 bool s2d_applicable(const Geom &g, conv2d_op op);     // strided layer as a stride-1 3x3 layer, below
 bool tap_stream_ok(const Geom &g);                    // forward pass with the filter bank in LDS, below
 bool tap_stream_bwd_ok(const Geom &g);                // the same for a stride-1 backward-data pass
@@ -398,10 +489,28 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         if (wino_ok && op == CONV2D_FWD && g.C <= 8 && g.K >= 32 && g.R == 3 && g.S == 3 && g.pw == 1 &&
             g.W % 2 == 0 && ceil_div(g.Q, 2) % 2 == 0)
             return CONV2D_ALGO_WINOGRAD;
-        return (wino_ok && cin >= 32 && pays) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
+        if (wino_ok && cin >= 32 && pays) {
+            // 3x3 with many channels on a small map: the unfused F(4x4,3x3) path when its
+            // estimate beats the fused F(2x2,3x3) kernels' (measured rates on this chip:
+            // 36 GEMMs at ~125 TFLOP/s, transforms at ~4.5 TB/s over input + V and M + output,
+            // ~25 us of small launches; fused: ~105 TFLOP/s executed for the tile-pair kernel,
+            // ~80 for the one-tile-per-lane kernel)
+            const W4Plan w4 = plan_wino4(g, op);
+            if (w4.ok && cin >= 64) {
+                const WinoPlan f2 = plan_wino(g, op);
+                const double t_f2 = 32.0 * f2.T * f2.Cin * (double)f2.Kpad / (f2.mode != 0 ? 105e12 : 80e12);
+                const double bytes = 4.0 * ((double)g.N * w4.Cin * w4.Hin * w4.Win + 36.0 * w4.chunks * 8 * w4.Tpad +
+                                            36.0 * w4.Kpad * w4.Tpad + (double)g.N * w4.Kout * w4.Hout * w4.Wout);
+                const double t_w4 = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / 125e12 + bytes / 4.5e12 + 25e-6;
+                if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
+            }
+            return CONV2D_ALGO_WINOGRAD;
+        }
+        return CONV2D_ALGO_IGEMM;
     }
     case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;
     case CONV2D_ALGO_WINOGRAD: return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ERR_ALGO;
+    case CONV2D_ALGO_WINOGRAD4: return plan_wino4(g, op).ok ? CONV2D_ALGO_WINOGRAD4 : CONV2D_ERR_ALGO;
     default: return CONV2D_ERR_ALGO;
     }
 }
@@ -587,7 +696,6 @@ bool smallc_bwd_ok(const Geom &g, const float *dy, const float *dx)
            (int64_t)g.N * g.K * g.P * g.Q * 4 < (int64_t(1) << 31);
 }
 
-int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
 
 int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias,
              float *out, void *ws, size_t ws_bytes, hipStream_t s, int relu = 0, int pool = 0)
@@ -786,6 +894,7 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     if (al < 0) return 0;
     if (al == CONV2D_ALGO_WINOGRAD)
         return wino_applicable(g, op) ? wino_ws_bytes(g, op) : plan_s2d(g, op).total_bytes;
+    if (al == CONV2D_ALGO_WINOGRAD4) return plan_wino4(g, op).total_bytes;
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
@@ -811,6 +920,7 @@ static int fwd_impl(const conv2d_desc *d, const float *x, const float *w, const 
     const int al = resolve_algo(g, CONV2D_FWD, (int)algo);
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (al == CONV2D_ALGO_WINOGRAD4) return run_wino4(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
     if (al == CONV2D_ALGO_WINOGRAD)
         return wino_applicable(g, CONV2D_FWD) ? run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu)
                                               : run_s2d(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
@@ -888,8 +998,15 @@ int conv2d_fwd_static(const conv2d_desc *d, const float *x, const float *w, cons
     // what conv2d_fwd would ask of the caller; nothing in it has to start at zero (the
     // filter matrix / transformed filters and the cut-tile slots are written before they
     // are read), so the last call's contents may stay
-    const size_t need = conv2d_workspace_bytes(d, CONV2D_FWD, algo);
+    size_t need = conv2d_workspace_bytes(d, CONV2D_FWD, algo);
     if (need == 0) return CONV2D_ERR_ALGO;
+    // AUTO may pick the unfused Winograd path, whose workspace holds whole transformed
+    // tensors: where that does not fit, take the fused kernels, which need far less
+    if (need > (size_t)CONV2D_STATIC_SCRATCH_BYTES && algo == CONV2D_ALGO_AUTO && al == CONV2D_ALGO_WINOGRAD4) {
+        algo = CONV2D_ALGO_WINOGRAD;
+        need = conv2d_workspace_bytes(d, CONV2D_FWD, algo);
+        if (need == 0) return CONV2D_ERR_ALGO;
+    }
     if (need > (size_t)CONV2D_STATIC_SCRATCH_BYTES) return CONV2D_ERR_STATIC_LIMIT;
     void *ws = static_scratch(&rc);
     if (!ws) return rc;
@@ -1011,6 +1128,7 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
         sa.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
         return launch_status(launch_bwd_data_smallc(sa, s));
     }
+    if (al == CONV2D_ALGO_WINOGRAD4) return run_wino4(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
     if (al == CONV2D_ALGO_WINOGRAD)
         return wino_applicable(g, CONV2D_BWD_DATA)
                    ? run_wino(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s)

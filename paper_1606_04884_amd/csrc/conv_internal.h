@@ -199,6 +199,30 @@ int wino_partial_slot_floats();
 // G persistent workgroups (G <= tiles_t*tiles_k)
 hipError_t launch_wino_fused(const WinoArgs &a, int G, hipStream_t s);
 
+// Winograd F(4x4,3x3) with separate transform kernels around 36 batched GEMMs (see
+// wino4.hip).  `in` is x (forward) or dy (backward-data, with the rotated filter: mode 1).
+struct W4Args {
+    const float *in;
+    const float *w;            // [K][C][3][3]
+    const float *bias;         // nullable
+    float *out;
+    float *U, *V, *M;          // workspace: transformed filters, input tiles, products
+    float *slots;              // workspace: [split_tiles][split] partial GEMM tiles
+    int32_t split, split_tiles; // the last split_tiles GEMM tiles are computed as `split` depth shares each
+                                // (split <= 1: every tile by one workgroup)
+    int32_t relu;
+    int32_t mode;              // filter transform: 0 forward, 1 backward-data
+    int32_t C;                 // channel count of w (its second axis)
+    int32_t N, Cin, Hin, Win, Kout, Kpad, Hout, Wout, pad_h, pad_w;
+    int32_t TH, TW, T, Tpad;   // 4x4 output tiles per image (rows, cols), in total, padded to the GEMM tile
+    int32_t chunks;            // 8-channel chunks of the reduction (Cin rounded up)
+    int32_t in_bytes;          // size of `in` (below 2^31)
+    int32_t tile_cfg;          // workgroup tile of the GEMM, see wino4_tile_m / _n
+};
+int wino4_tile_m(int cfg);
+int wino4_tile_n(int cfg);
+hipError_t launch_wino4(const W4Args &a, hipStream_t s);
+
 // Winograd backward-weight F(3x3,2x2) (see winograd_wgrad.hip).
 struct WinoWgradArgs {
     const float *x;

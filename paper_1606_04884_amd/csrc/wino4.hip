@@ -1,0 +1,447 @@
+// Winograd F(4x4,3x3) for 3x3 stride-1 layers with many channels on small maps, with the
+// transforms as separate kernels around 36 batched GEMMs on fp32 MFMA.
+//
+// Sec. 4.2 "Winograd" of the paper: minimal filtering trades multiplications for
+// transforms, and the bulk of the work remains matrix products.  The larger tile does 36
+// multiplications per 4x4 outputs and channel pair (k, c) against 144 direct ones (4x fewer;
+// F(2x2,3x3) saves 2.25x).  Its 36 positions do not fit the accumulator registers of a
+// fused kernel, so here the transformed tensors go through HBM:
+//
+//   U[pos] = G g G^T            (filters,   wino4_filter_kernel)
+//   V[pos] = B^T d B            (6x6 input tiles, wino4_input_kernel)
+//   M[pos] = U[pos]^T V[pos]    (36 GEMMs [K x C] . [C x tiles], wino4_gemm_kernel)
+//   Y      = A^T M A + bias     (4x4 output tiles, wino4_output_kernel)
+//
+// which costs 2.25x the layer's input and output in extra writes and reads: small next to
+// the GEMMs when C and K are in the hundreds, too much for the 64/128-channel layers on
+// large maps (those stay with the fused F(2x2,3x3) kernels).  The paper prints no
+// matrices; the standard ones for the points {0, 1, -1, 2, -2, inf} are used:
+//   B^T = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0; 0 2 -1 -2 1 0; 0 4 0 -5 0 1]
+//   G   = [1/4 0 0; -1/6 -1/6 -1/6; -1/6 1/6 -1/6; 1/24 1/12 1/6; 1/24 -1/12 1/6; 0 0 1]
+//   A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]
+//
+// Operand layout of the GEMMs ("MFMA order"): a matrix X[depth][row] is stored as
+// [depth/8][depth%2][row][(depth%8)/2], so that the four values a lane of
+// v_mfma_f32_32x32x2_f32 supplies for the four reduction steps of an 8-deep chunk
+// (lane l: row l%32, depth 8*chunk + 2*step + l/32) are 16 contiguous bytes and the 32
+// lanes of a half-wave read 512 contiguous bytes.  Both transforms write this layout, so
+// the GEMM loads its operands from L2 / HBM straight into the registers the MFMAs read:
+// no LDS, no barrier, waves drift freely.
+
+#include "conv_internal.h"
+
+#include <mutex>
+
+namespace mi355conv {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------ filters
+// U[pos][chunk][half][ko][j]: reduction channel ci = 8*chunk + 2*j + half, output channel
+// ko < Kpad; zero where ci >= Cin or ko >= Kout.  mode 0: g = w[ko][ci]; mode 1
+// (backward-data: the layer mapping dy to dx): g = w[ci][ko] rotated by 180 degrees.
+__global__ __launch_bounds__(256) void wino4_filter_kernel(const float *__restrict__ w, float *__restrict__ U,
+                                                           int C, int Cin, int Kout, int chunks, int Kpad, int mode)
+{
+    const int64_t nvec = (int64_t)chunks * 2 * Kpad;           // 16-byte vectors per position
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * blockDim.x) {
+        const int ko = (int)(v % Kpad);
+        const int ch = (int)(v / Kpad);                         // chunk * 2 + half
+        floatx4 u[36];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int ci = (ch >> 1) * 8 + (ch & 1) + 2 * j;
+            float g[3][3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) g[r][s] = 0.f;
+            if (ci < Cin && ko < Kout) {
+                if (mode == 0) {
+                    const float *p = w + ((int64_t)ko * C + ci) * 9;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+#pragma unroll
+                        for (int s = 0; s < 3; ++s) g[r][s] = p[r * 3 + s];
+                } else {
+                    const float *p = w + ((int64_t)ci * C + ko) * 9;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+#pragma unroll
+                        for (int s = 0; s < 3; ++s) g[r][s] = p[(2 - r) * 3 + (2 - s)];
+                }
+            }
+            float t[6][3];
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const float g0 = g[0][s], g1 = g[1][s], g2 = g[2][s];
+                t[0][s] = 0.25f * g0;
+                t[1][s] = (-1.f / 6.f) * (g0 + g1 + g2);
+                t[2][s] = (-1.f / 6.f) * (g0 - g1 + g2);
+                t[3][s] = (1.f / 24.f) * g0 + (1.f / 12.f) * g1 + (1.f / 6.f) * g2;
+                t[4][s] = (1.f / 24.f) * g0 - (1.f / 12.f) * g1 + (1.f / 6.f) * g2;
+                t[5][s] = g2;
+            }
+#pragma unroll
+            for (int r = 0; r < 6; ++r) {
+                const float g0 = t[r][0], g1 = t[r][1], g2 = t[r][2];
+                u[6 * r + 0][j] = 0.25f * g0;
+                u[6 * r + 1][j] = (-1.f / 6.f) * (g0 + g1 + g2);
+                u[6 * r + 2][j] = (-1.f / 6.f) * (g0 - g1 + g2);
+                u[6 * r + 3][j] = (1.f / 24.f) * g0 + (1.f / 12.f) * g1 + (1.f / 6.f) * g2;
+                u[6 * r + 4][j] = (1.f / 24.f) * g0 - (1.f / 12.f) * g1 + (1.f / 6.f) * g2;
+                u[6 * r + 5][j] = g2;
+            }
+        }
+#pragma unroll
+        for (int pos = 0; pos < 36; ++pos)
+            *reinterpret_cast<floatx4 *>(U + ((int64_t)pos * nvec + v) * 4) = u[pos];
+    }
+}
+
+// B^T d on six values (one column, or one row, of the tile)
+__device__ __forceinline__ void w4_bt(const float d0, const float d1, const float d2, const float d3,
+                                      const float d4, const float d5, float (&o)[6])
+{
+    const float a = d4 - 4.f * d2, b = d3 - 4.f * d1;
+    const float c = d4 - d2, e = 2.f * (d3 - d1);
+    o[0] = 4.f * d0 - 5.f * d2 + d4;
+    o[1] = a + b;
+    o[2] = a - b;
+    o[3] = c + e;
+    o[4] = c - e;
+    o[5] = 4.f * d1 - 5.f * d3 + d5;
+}
+
+// ------------------------------------------------------------------- input
+// V[pos][chunk][half][t][j], t < Tpad (tiles past T are written as zeros), channel
+// ci = 8*chunk + 2*j + half.  A thread owns one tile and the four channels of one
+// (chunk, half): it fetches their 6x6 patches (origin 4*tile - pad; elements outside the
+// image carry an offset beyond the buffer, for which the buffer load returns 0),
+// transforms them and stores each position as one 16-byte vector; the 64 lanes of a wave
+// are consecutive tiles, so every store instruction writes 1 KB contiguously.
+__global__ __launch_bounds__(256) void wino4_input_kernel(W4Args a)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int ch = blockIdx.y;                                  // chunk * 2 + half
+    if (t >= a.Tpad) return;
+    const bool tv = t < a.T;
+    const int tl = tv ? t : 0;
+    const int THW = a.TH * a.TW;
+    const int n = tl / THW, rem = tl - n * THW;
+    const int th = rem / a.TW, tw = rem - th * a.TW;
+    const int ih0 = 4 * th - a.pad_h, iw0 = 4 * tw - a.pad_w;
+    const int HW = a.Hin * a.Win;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
+    uint32_t rowoff[6];
+    uint32_t colbad = 0;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        const bool ok = tv && (unsigned)(ih0 + i) < (unsigned)a.Hin;
+        rowoff[i] = ok ? (uint32_t)((n * a.Cin * HW + (ih0 + i) * a.Win + iw0) * 4) : 0x80000000u;
+        if (!((unsigned)(iw0 + i) < (unsigned)a.Win)) colbad |= 1u << i;
+    }
+    floatx4 v[36];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int ci = (ch >> 1) * 8 + (ch & 1) + 2 * j;
+        const uint32_t cbad = ci < a.Cin ? 0u : 0x80000000u;
+        const int so = (ci < a.Cin ? ci : 0) * HW * 4;
+        float d[6][6];
+#pragma unroll
+        for (int i = 0; i < 6; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 6; ++jj) {
+                const uint32_t off = ((colbad >> jj) & 1u) ? 0x80000000u : (rowoff[i] + 4u * jj);
+                d[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off | cbad, so, 0));
+            }
+        float tcol[6][6];       // B^T d: column pass
+#pragma unroll
+        for (int jj = 0; jj < 6; ++jj) {
+            float o[6];
+            w4_bt(d[0][jj], d[1][jj], d[2][jj], d[3][jj], d[4][jj], d[5][jj], o);
+#pragma unroll
+            for (int i = 0; i < 6; ++i) tcol[i][jj] = o[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            float o[6];
+            w4_bt(tcol[i][0], tcol[i][1], tcol[i][2], tcol[i][3], tcol[i][4], tcol[i][5], o);
+#pragma unroll
+            for (int jj = 0; jj < 6; ++jj) v[6 * i + jj][j] = o[jj];
+        }
+    }
+    const int64_t pos_stride = (int64_t)a.chunks * 2 * a.Tpad * 4;
+    float *dst = a.V + ((int64_t)ch * a.Tpad + t) * 4;
+#pragma unroll
+    for (int pos = 0; pos < 36; ++pos) *reinterpret_cast<floatx4 *>(dst + pos * pos_stride) = v[pos];
+}
+
+// ------------------------------------------------------------------- GEMMs
+// C[b][m][n] = sum_d A[b][d][m] * B[b][d][n] for b < 36, A and B in MFMA order (see the
+// head of this file), Mpad / Npad rows per half-plane, multiples of the workgroup tile, so
+// no access needs a bounds check.  A wave owns 64 rows x 128 columns (2 x 4 MFMA tiles,
+// 128 accumulator registers) and per 8-deep chunk issues 2 + 4 16-byte loads and 32
+// MFMAs; the loads of chunk i+1 go into a second register set during the MFMAs of chunk
+// i, spread over the gaps between runs of 8 MFMAs.  Four waves per workgroup as WGM x WGN
+// wave tiles, two workgroups per compute unit (two waves per SIMD: the loads of one
+// overlap the MFMAs of the other).  Workgroup ids are remapped so that each XCD walks a
+// contiguous range of tiles in the order (position, column tile, row tile): the B tile
+// column is then reused from its L2 across the row tiles, and one position's A stays there.
+struct W4GemmArgs {
+    const float *A, *B;
+    float *C;
+    float *slots;              // [tile][split] partial workgroup tiles of a launch with nsplit > 1
+    int32_t chunks, Mpad, Npad, tiles_m, tiles_n;
+    int32_t tile_base;         // first tile of this launch (tile order: row tile fastest, column tile, position)
+    int32_t nsplit;            // workgroups per tile, each taking an equal share of the chunks
+};
+
+__device__ __forceinline__ int w4_xcd_remap(int id, int nb)
+{
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = id & 7, local = id >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + local;
+}
+
+template <int WGM, int WGN>
+__global__ __launch_bounds__(256, 2) void wino4_gemm_kernel(W4GemmArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    constexpr int TM = 64 * WGM, TN = 128 * WGN;
+    const int lb = w4_xcd_remap(blockIdx.x, gridDim.x);
+    const int piece = lb / a.nsplit, split = lb - piece * a.nsplit;
+    const int tile = a.tile_base + piece;
+    const int tm = tile % a.tiles_m;
+    const int r1 = tile / a.tiles_m;
+    const int tn = r1 % a.tiles_n;
+    const int pos = r1 / a.tiles_n;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int m0 = (tm * WGM + wm) * 64, n0 = (tn * WGN + wn) * 128;
+    // this workgroup's share of the reduction
+    const int c_first = (int)((int64_t)split * a.chunks / a.nsplit);
+    const int c_end = (int)((int64_t)(split + 1) * a.chunks / a.nsplit);
+
+    const int a_chunk = 2 * a.Mpad * 16, b_chunk = 2 * a.Npad * 16;          // bytes per chunk
+    const float *Ap = a.A + (int64_t)pos * a.chunks * 2 * a.Mpad * 4;
+    const float *Bp = a.B + (int64_t)pos * a.chunks * 2 * a.Npad * 4;
+    const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void *)Ap, 0, a.chunks * a_chunk, 0x00020000);
+    const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc((void *)Bp, 0, a.chunks * b_chunk, 0x00020000);
+    const uint32_t aoff = (uint32_t)(lhi * a.Mpad + m0 + l32) * 16u;
+    const uint32_t boff = (uint32_t)(lhi * a.Npad + n0 + l32) * 16u;
+
+    // three register sets: the loads of chunk i+2 are issued during the MFMAs of chunk i
+    floatx4 ra[3][2], rb[3][4];
+    auto load_a = [&](int set, int mi, int chunk) {
+        ra[set][mi] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(ars, aoff + mi * 512u, chunk * a_chunk, 0));
+    };
+    auto load_b = [&](int set, int ni, int chunk) {
+        rb[set][ni] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(brs, boff + ni * 512u, chunk * b_chunk, 0));
+    };
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+    const int last = c_end - 1;
+    load_a(0, 0, c_first); load_a(0, 1, c_first);
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) load_b(0, ni, c_first);
+    {
+        const int c1 = last < c_first + 1 ? last : c_first + 1;
+        load_a(1, 0, c1); load_a(1, 1, c1);
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) load_b(1, ni, c1);
+    }
+
+    // one chunk: the MFMAs of register set `cur`, the loads of chunk `nc` into set `nxt`
+    auto body = [&](int cur, int nxt, int nc) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == 0) { load_a(nxt, 0, nc); }
+            if (ks == 1) { load_b(nxt, 0, nc); }
+            if (ks == 2) { load_b(nxt, 2, nc); }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int mi = q & 1, ni = q >> 1;
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(ra[cur][mi][ks], rb[cur][ni][ks], acc[mi][ni], 0, 0, 0);
+                if (q == 3) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ks == 0) { load_a(nxt, 1, nc); }
+                    if (ks == 1) { load_b(nxt, 1, nc); }
+                    if (ks == 2) { load_b(nxt, 3, nc); }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    };
+    auto clampc = [&](int c) { return c < last ? c : last; };
+    for (int c = c_first; c < c_end; c += 3) {
+        body(0, 2, clampc(c + 2));
+        if (c + 1 < c_end) body(1, 0, clampc(c + 3));
+        if (c + 2 < c_end) body(2, 1, clampc(c + 4));
+    }
+
+    // accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    // (a split tile goes to its slot, a dense TM x TN block)
+    float *Cp = a.nsplit > 1 ? a.slots + (int64_t)lb * (TM * TN) + (wm * 64 + 4 * lhi) * TN + wn * 128 + l32
+                             : a.C + (int64_t)pos * a.Mpad * a.Npad + (int64_t)(m0 + 4 * lhi) * a.Npad + n0 + l32;
+    const int64_t pitch = a.nsplit > 1 ? TN : a.Npad;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                Cp[(int64_t)(32 * mi + 8 * (v >> 2) + (v & 3)) * pitch + 32 * ni] = acc[mi][ni][v];
+}
+
+// Sum of the depth splits of the tiles that were cut (see launch_wino4): C tile j of the
+// split group = slot[j*S] + slot[j*S+1] + ... in that order.  Grid (tiles, 8): block
+// (j, part) adds an eighth of the tile, 16 bytes per thread and step.
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void wino4_gemm_fixup_kernel(W4GemmArgs a)
+{
+    const int tile = a.tile_base + blockIdx.x;
+    const int tm = tile % a.tiles_m, r1 = tile / a.tiles_m;
+    const int tn = r1 % a.tiles_n, pos = r1 / a.tiles_n;
+    const float *src = a.slots + (int64_t)blockIdx.x * a.nsplit * (TM * TN);
+    float *dst = a.C + (int64_t)pos * a.Mpad * a.Npad + (int64_t)tm * TM * a.Npad + tn * TN;
+    constexpr int NV = TM * TN / 4 / 8;                 // 16-byte vectors per part
+    for (int iv = threadIdx.x; iv < NV; iv += 256) {
+        const int e = (blockIdx.y * NV + iv) * 4;
+        const int row = e / TN, col = e - row * TN;
+        floatx4 r = *reinterpret_cast<const floatx4 *>(src + e);
+        for (int sp = 1; sp < a.nsplit; ++sp) {
+            const floatx4 q = *reinterpret_cast<const floatx4 *>(src + (int64_t)sp * (TM * TN) + e);
+            r[0] += q[0]; r[1] += q[1]; r[2] += q[2]; r[3] += q[3];
+        }
+        *reinterpret_cast<floatx4 *>(dst + (int64_t)row * a.Npad + col) = r;
+    }
+}
+
+// ------------------------------------------------------------------ output
+// Y = A^T M A + bias for one (filter, tile) per thread: 36 coalesced dword loads of
+// M[pos][k][t] (lanes = consecutive tiles), 4 rows of the 4x4 output block stored as
+// 16-byte vectors when the map allows it.
+__device__ __forceinline__ void w4_at(const float m0, const float m1, const float m2, const float m3,
+                                      const float m4, const float m5, float (&y)[4])
+{
+    const float s12 = m1 + m2, d12 = m1 - m2, s34 = m3 + m4, d34 = m3 - m4;
+    y[0] = m0 + s12 + s34;
+    y[1] = d12 + 2.f * d34;
+    y[2] = s12 + 4.f * s34;
+    y[3] = d12 + 8.f * d34 + m5;
+}
+
+__global__ __launch_bounds__(256) void wino4_output_kernel(W4Args a)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int k = blockIdx.y;
+    if (t >= a.T) return;
+    const int THW = a.TH * a.TW;
+    const int n = t / THW, rem = t - n * THW;
+    const int th = rem / a.TW, tw = rem - th * a.TW;
+    const int64_t pos_stride = (int64_t)a.Kpad * a.Tpad;
+    const float *src = a.M + (int64_t)k * a.Tpad + t;
+    float m[6][6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+#pragma unroll
+        for (int j = 0; j < 6; ++j) m[i][j] = src[(6 * i + j) * pos_stride];
+    float c[4][6];          // A^T M: column pass
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+        float y[4];
+        w4_at(m[0][j], m[1][j], m[2][j], m[3][j], m[4][j], m[5][j], y);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i][j] = y[i];
+    }
+    const float bz = a.bias ? a.bias[k] : 0.f;
+    const int oh = 4 * th, ow = 4 * tw;
+    float *o = a.out + ((int64_t)n * a.Kout + k) * a.Hout * a.Wout + (int64_t)oh * a.Wout + ow;
+    const bool vec = (a.Wout & 3) == 0 && (((uintptr_t)a.out) & 15) == 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float y[4];
+        w4_at(c[i][0], c[i][1], c[i][2], c[i][3], c[i][4], c[i][5], y);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            y[j] += bz;
+            if (a.relu) y[j] = fmaxf(y[j], 0.f);
+        }
+        if (oh + i < a.Hout) {
+            if (vec) {
+                const floatx4 y4 = {y[0], y[1], y[2], y[3]};
+                *reinterpret_cast<floatx4 *>(o + (int64_t)i * a.Wout) = y4;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (ow + j < a.Wout) o[(int64_t)i * a.Wout + j] = y[j];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- launchers
+int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : 256; }     // 2 x 2 or 4 x 1 wave tiles of 64 x 128
+int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : 128; }
+
+hipError_t launch_wino4(const W4Args &a, hipStream_t s)
+{
+    {
+        int64_t blocks = ((int64_t)a.chunks * 2 * a.Kpad + 255) / 256;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(wino4_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a.w, a.U, a.C, a.Cin, a.Kout,
+                           a.chunks, a.Kpad, a.mode);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(wino4_input_kernel, dim3((unsigned)((a.Tpad + 255) / 256), (unsigned)(a.chunks * 2)), dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    W4GemmArgs g = {};
+    g.A = a.U; g.B = a.V; g.C = a.M;
+    g.chunks = a.chunks; g.Mpad = a.Kpad; g.Npad = a.Tpad;
+    g.tiles_m = a.Kpad / wino4_tile_m(a.tile_cfg);
+    g.tiles_n = a.Tpad / wino4_tile_n(a.tile_cfg);
+    const int tiles = 36 * g.tiles_m * g.tiles_n;
+    // whole rounds of the resident workgroups, one workgroup per tile ...
+    const int full = a.split > 1 ? tiles - a.split_tiles : tiles;
+    if (full > 0) {
+        g.tile_base = 0; g.nsplit = 1;
+        if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3((unsigned)full), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3((unsigned)full), dim3(256), 0, s, g);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    // ... and the tiles of the last, partly filled round cut into equal depth shares, so that
+    // they fill the compute units too; the shares are added in a fixed order afterwards
+    if (full < tiles) {
+        g.tile_base = full; g.nsplit = a.split; g.slots = a.slots;
+        const unsigned grid = (unsigned)((tiles - full) * a.split);
+        if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (a.tile_cfg == 0)
+            hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), dim3((unsigned)(tiles - full), 8), dim3(256), 0, s, g);
+        else
+            hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128>), dim3((unsigned)(tiles - full), 8), dim3(256), 0, s, g);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(wino4_output_kernel, dim3((unsigned)((a.T + 255) / 256), (unsigned)a.Kout), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace mi355conv

@@ -130,10 +130,16 @@ def test_algo_choice_rules():
     """AUTO policy as the header states it: Winograd for 3x3 stride-1 layers with enough
     reduction channels whose gathered tensor fits 32-bit byte offsets, else implicit GEMM."""
     pick = B.conv2d_pick_algo
-    vgg = (64, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1)
+    vgg = (64, 128, 112, 112, 128, 3, 3, 1, 1, 1, 1)            # large map, few channels: fused F(2x2,3x3)
     assert pick(vgg, B.OP_FWD) == B.ALGO_WINOGRAD
     assert pick(vgg, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
     assert pick(vgg, B.OP_BWD_WEIGHT) == B.ALGO_WINOGRAD
+    deep = (64, 512, 28, 28, 512, 3, 3, 1, 1, 1, 1)             # many channels, small map: unfused F(4x4,3x3)
+    assert pick(deep, B.OP_FWD) == B.ALGO_WINOGRAD4
+    assert pick(deep, B.OP_BWD_DATA) == B.ALGO_WINOGRAD4
+    # its workspace holds the transformed input and the products: 2.25 x input + 2.25 x output at least
+    assert B.conv2d_workspace_bytes(deep, B.OP_FWD) > 2.25 * 4 * 2 * 64 * 512 * 28 * 28
+    assert B.conv2d_workspace_bytes(deep, B.OP_FWD, B.ALGO_WINOGRAD) < 64 << 20
     first = (64, 3, 224, 224, 64, 3, 3, 1, 1, 1, 1)              # 3 input channels
     assert pick(first, B.OP_FWD) == B.ALGO_IGEMM                # taps kernel: the filter bank in LDS
     assert pick((64, 6, 224, 224, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_WINOGRAD   # tile-pair kernel, one ragged chunk

@@ -124,3 +124,63 @@ def test_large_filter_is_a_sum_of_shifted_3x3_filters():
                 xs = np.ascontiguousarray(xe[:, :, 3 * a:3 * a + P + 2, 3 * b:3 * b + Q + 2])
                 acc += oracle.fwd((N, C, P + 2, Q + 2, K, 3, 3, 1, 1, 0, 0), xs, g, None)
         assert np.array_equal(acc, full), (R, S)
+
+
+# ---- F(4x4,3x3): the larger tile of the unfused Winograd path -----------------
+# Standard minimal-filtering matrices for the points {0, 1, -1, 2, -2, inf} (the paper's
+# Sec. 4.2 "Winograd" cites the algorithm and prints none).
+BT4 = [[4, 0, -5, 0, 1, 0], [0, -4, -4, 1, 1, 0], [0, 4, -4, -1, 1, 0],
+       [0, -2, -1, 2, 1, 0], [0, 2, -1, -2, 1, 0], [0, 4, 0, -5, 0, 1]]
+G4 = [[F(1, 4), 0, 0], [F(-1, 6), F(-1, 6), F(-1, 6)], [F(-1, 6), F(1, 6), F(-1, 6)],
+      [F(1, 24), F(1, 12), F(1, 6)], [F(1, 24), F(-1, 12), F(1, 6)], [0, 0, 1]]
+AT4 = [[1, 1, 1, 1, 1, 0], [0, 1, -1, 2, -2, 0], [0, 1, 1, 4, 4, 0], [0, 1, -1, 8, -8, 1]]
+
+
+def test_f4x4_1d_identity_exact():
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        d = [F(int(v)) for v in rng.integers(-9, 10, size=6)]
+        g = [F(int(v)) for v in rng.integers(-9, 10, size=3)]
+        Gg = [sum(F(G4[i][k]) * g[k] for k in range(3)) for i in range(6)]
+        Btd = [sum(F(BT4[i][k]) * d[k] for k in range(6)) for i in range(6)]
+        y = [sum(F(AT4[i][k]) * Gg[k] * Btd[k] for k in range(6)) for i in range(4)]
+        assert y == [sum(d[i + k] * g[k] for k in range(3)) for i in range(4)]
+
+
+def test_f4x4_2d_identity_exact():
+    rng = np.random.default_rng(12)
+    for _ in range(10):
+        C = 3
+        d = rng.integers(-9, 10, size=(C, 6, 6))
+        g = rng.integers(-9, 10, size=(C, 3, 3))
+        M = [[F(0)] * 6 for _ in range(6)]
+        for c in range(C):
+            U = mm(mm(G4, g[c].tolist()), tr(G4))
+            V = mm(mm(BT4, d[c].tolist()), tr(BT4))
+            for i in range(6):
+                for j in range(6):
+                    M[i][j] += U[i][j] * V[i][j]
+        Y = mm(mm(AT4, M), tr(AT4))
+        for p in range(4):
+            for q in range(4):
+                direct = sum(int(d[c, p + r, q + s]) * int(g[c, r, s])
+                             for c in range(C) for r in range(3) for s in range(3))
+                assert Y[p][q] == direct
+
+
+def test_f4x4_weight_gradient_identity_exact():
+    """dg = G^T [(A dy A^T) .* (B^T d B)] G with the F(4x4,3x3) matrices equals
+    sum_{p,q<4} dy[p][q] d[p+r][q+s] (the transpose of the bilinear tile relation)."""
+    A = tr(AT4)
+    rng = np.random.default_rng(13)
+    for _ in range(10):
+        d = rng.integers(-9, 10, size=(6, 6)).tolist()
+        dy = rng.integers(-9, 10, size=(4, 4)).tolist()
+        Dp = mm(mm(A, dy), AT4)
+        V = mm(mm(BT4, d), tr(BT4))
+        M = [[Dp[i][j] * V[i][j] for j in range(6)] for i in range(6)]
+        dg = mm(mm(tr(G4), M), G4)
+        for r in range(3):
+            for s in range(3):
+                direct = sum(dy[p][q] * d[p + r][q + s] for p in range(4) for q in range(4))
+                assert dg[r][s] == direct
