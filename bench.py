@@ -178,7 +178,9 @@ def main() -> int:
     # kernel families: which main kernel served the call
     def family(op, li):
         if recs[li]["algo"][op] == 3:
-            return "wino4 (wino4_gemm_kernel + transform kernels: unfused F(4x4,3x3) fwd + bwd_data calls)"
+            return ("wino4_wgrad (wino4_gemm_kernel + transform kernels: unfused F(4x4,3x3) bwd_weight calls)"
+                    if op == "bwd_weight" else
+                    "wino4 (wino4_gemm_kernel + transform kernels: unfused F(4x4,3x3) fwd + bwd_data calls)")
         wino = recs[li]["algo"][op] == 2
         if op == "bwd_weight":
             return ("wino_wgrad (wino_wgrad_vec_kernel / wino_wgrad_kernel: Winograd bwd_weight calls)" if wino

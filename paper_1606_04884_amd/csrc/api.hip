@@ -449,6 +449,77 @@ int run_wino4(const Geom &g, conv2d_op op, const float *in, const float *w, cons
     return launch_status(launch_wino4(a, s));
 }
 
+struct W4WgradPlan {
+    bool ok;
+    int TH, TW, T, chunks, Kpad, Cpad, cfg, split, tiles;
+    size_t wm_bytes, vm_bytes, slot_bytes, d_bytes, bias_bytes, total_bytes;
+};
+
+W4WgradPlan plan_wino4_wgrad(const Geom &g)
+{
+    W4WgradPlan p = {};
+    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph > 2 || g.pw > 2) return p;
+    if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31) || (int64_t)g.N * g.K * g.P * g.Q * 4 >= (int64_t(1) << 31))
+        return p;
+    p.TH = ceil_div(g.P, 4);
+    p.TW = ceil_div(g.Q, 4);
+    const int64_t T = (int64_t)g.N * p.TH * p.TW;
+    if (T < 16 || T > 524000 || g.K > 65535) return p;        // the chunks are a grid dimension
+    p.T = (int)T;
+    p.chunks = ceil_div(p.T, 8);
+    int64_t best = -1;
+    for (int cfg = 0; cfg < 2; ++cfg) {
+        const int64_t cost = (int64_t)round_up(g.K, wino4_tile_m(cfg)) * round_up(g.C, wino4_tile_n(cfg));
+        if (best < 0 || cost < best) { best = cost; p.cfg = cfg; }
+    }
+    p.Kpad = round_up(g.K, wino4_tile_m(p.cfg));
+    p.Cpad = round_up(g.C, wino4_tile_n(p.cfg));
+    if ((int64_t)p.chunks * 2 * p.Kpad * 16 >= (int64_t(1) << 31) || (int64_t)p.chunks * 2 * p.Cpad * 16 >= (int64_t(1) << 31))
+        return p;
+    p.tiles = 36 * (p.Kpad / wino4_tile_m(p.cfg)) * (p.Cpad / wino4_tile_n(p.cfg));
+    // depth shares per tile: fill the 512 resident workgroups a whole number of times; a
+    // share costs its chunks plus ~4 chunk times of start-up and partial-tile store
+    double best_t = 1e300;
+    p.split = 2;
+    for (int sp = 2; sp <= 64 && sp <= p.chunks && (int64_t)p.tiles * sp <= 2048; ++sp) {
+        const double t = (double)ceil_div(p.tiles * sp, 512) * ((double)ceil_div(p.chunks, sp) + 4.0);
+        if (t < best_t) { best_t = t; p.split = sp; }
+    }
+    if ((int64_t)p.tiles * p.split > 4096) return p;
+    p.wm_bytes = align_up((size_t)36 * p.chunks * 8 * p.Kpad * sizeof(float), 256);
+    p.vm_bytes = align_up((size_t)36 * p.chunks * 8 * p.Cpad * sizeof(float), 256);
+    p.slot_bytes = align_up((size_t)p.tiles * p.split * wino4_tile_m(p.cfg) * wino4_tile_n(p.cfg) * sizeof(float), 256);
+    p.d_bytes = align_up((size_t)36 * p.Kpad * p.Cpad * sizeof(float), 256);
+    p.bias_bytes = align_up((size_t)p.chunks * 2 * p.Kpad * sizeof(float), 256);
+    p.total_bytes = p.wm_bytes + p.vm_bytes + p.slot_bytes + p.d_bytes + p.bias_bytes;
+    p.ok = true;
+    return p;
+}
+
+int run_wino4_wgrad(const Geom &g, const float *x, const float *dy, float *dw, float *dbias, float scale,
+                    int accumulate, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const W4WgradPlan p = plan_wino4_wgrad(g);
+    if (!p.ok) return CONV2D_ERR_ALGO;
+    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    W4WgradArgs a = {};
+    a.x = x; a.dy = dy; a.dw = dw; a.db = dbias;
+    a.Wm = (float *)ws;
+    a.Vm = (float *)((char *)ws + p.wm_bytes);
+    a.slots = (float *)((char *)ws + p.wm_bytes + p.vm_bytes);
+    a.D = (float *)((char *)ws + p.wm_bytes + p.vm_bytes + p.slot_bytes);
+    a.bias_part = dbias ? (float *)((char *)ws + p.wm_bytes + p.vm_bytes + p.slot_bytes + p.d_bytes) : nullptr;
+    a.scale = scale; a.accumulate = accumulate;
+    a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q; a.pad_h = g.ph; a.pad_w = g.pw;
+    a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.chunks = p.chunks; a.Kpad = p.Kpad; a.Cpad = p.Cpad;
+    a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+    a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+    a.tile_cfg = p.cfg; a.split = p.split;
+    a.div_THW = make_fastdiv((uint32_t)(p.TH * p.TW));
+    a.div_TW = make_fastdiv((uint32_t)p.TW);
+    return launch_status(launch_wino4_wgrad(a, s));
+}
+
 bool s2d_applicable(const Geom &g, conv2d_op op);     // strided layer as a stride-1 3x3 layer, below
 bool tap_stream_ok(const Geom &g);                    // forward pass with the filter bank in LDS, below
 bool tap_stream_bwd_ok(const Geom &g);                // the same for a stride-1 backward-data pass
@@ -469,7 +540,26 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         // Winograd pays once the 16 GEMMs are deep enough to amortise the transforms
         const int nsub_f = ceil_div(g.R, 3) * ceil_div(g.S, 3);
         const bool pays_f = 4 * nsub_f * 14 <= g.R * g.S * 10;
-        if (op == CONV2D_BWD_WEIGHT) return (wino_ok && pays_f) ? CONV2D_ALGO_WINOGRAD : CONV2D_ALGO_IGEMM;
+        if (op == CONV2D_BWD_WEIGHT) {
+            if (!(wino_ok && pays_f)) return CONV2D_ALGO_IGEMM;
+            // many channels and filters on a small map: the unfused F(4x4,3x3) form when its
+            // estimate (36 GEMMs at ~130 TFLOP/s, transforms at ~4 TB/s over x + V and dy + W,
+            // the partial products written and read once, ~40 us of small launches) beats the
+            // fused F(3x3,2x2) kernels' (~108 TFLOP/s executed with vector loads, ~85 without)
+            const W4WgradPlan w4 = plan_wino4_wgrad(g);
+            if (w4.ok && g.R == 3 && g.S == 3 && g.C >= 64 && g.K >= 64) {
+                const WinoWgradPlan f2 = plan_wino_wgrad(g);
+                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K / (f2.mode != 0 ? 108e12 : 85e12);
+                const double tile_b = 4.0 * wino4_tile_m(w4.cfg) * wino4_tile_n(w4.cfg);
+                const double bytes = 4.0 * ((double)g.N * g.C * g.H * g.W + (double)g.N * g.K * g.P * g.Q) +
+                                     4.0 * 36.0 * w4.chunks * 8 * ((double)w4.Kpad + w4.Cpad) +
+                                     2.0 * w4.tiles * (double)w4.split * tile_b;
+                const double eff = (double)w4.tiles * w4.split / (512.0 * ceil_div(w4.tiles * w4.split, 512));
+                const double t_w4 = 72.0 * w4.chunks * 8.0 * w4.Kpad * w4.Cpad / (130e12 * eff) + bytes / 4.0e12 + 40e-6;
+                if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
+            }
+            return CONV2D_ALGO_WINOGRAD;
+        }
         // backward-data into <= 4 channels: Winograd/GEMM rows would be almost empty;
         // a direct kernel takes it when its alignment conditions hold, else the GEMM
         if (op == CONV2D_BWD_DATA && g.C <= 4) return CONV2D_ALGO_IGEMM;
@@ -510,7 +600,9 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
     }
     case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;
     case CONV2D_ALGO_WINOGRAD: return wino_ok ? CONV2D_ALGO_WINOGRAD : CONV2D_ERR_ALGO;
-    case CONV2D_ALGO_WINOGRAD4: return plan_wino4(g, op).ok ? CONV2D_ALGO_WINOGRAD4 : CONV2D_ERR_ALGO;
+    case CONV2D_ALGO_WINOGRAD4:
+        return (op == CONV2D_BWD_WEIGHT ? plan_wino4_wgrad(g).ok : plan_wino4(g, op).ok) ? CONV2D_ALGO_WINOGRAD4
+                                                                                       : CONV2D_ERR_ALGO;
     default: return CONV2D_ERR_ALGO;
     }
 }
@@ -894,7 +986,8 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
     if (al < 0) return 0;
     if (al == CONV2D_ALGO_WINOGRAD)
         return wino_applicable(g, op) ? wino_ws_bytes(g, op) : plan_s2d(g, op).total_bytes;
-    if (al == CONV2D_ALGO_WINOGRAD4) return plan_wino4(g, op).total_bytes;
+    if (al == CONV2D_ALGO_WINOGRAD4)
+        return op == CONV2D_BWD_WEIGHT ? plan_wino4_wgrad(g).total_bytes : plan_wino4(g, op).total_bytes;
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
@@ -1242,6 +1335,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
 
+    if (al == CONV2D_ALGO_WINOGRAD4) return run_wino4_wgrad(g, x, dy, dw, dbias, scale, accumulate, ws, ws_bytes, s);
     if (al == CONV2D_ALGO_WINOGRAD) {
         if (!wino_applicable(g, CONV2D_BWD_WEIGHT))
             return run_s2d_wgrad(g, x, dy, dw, dbias, scale, accumulate, ws, ws_bytes, s);

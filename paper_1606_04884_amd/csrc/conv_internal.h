@@ -219,6 +219,25 @@ struct W4Args {
     int32_t in_bytes;          // size of `in` (below 2^31)
     int32_t tile_cfg;          // workgroup tile of the GEMM, see wino4_tile_m / _n
 };
+// Backward-weight of the same path: dy and x tiles transformed with the tile index as the
+// GEMM depth, every GEMM tile cut into `split` >= 2 depth shares (slots), summed by the
+// kernel that applies the final filter transform.
+struct W4WgradArgs {
+    const float *x, *dy;
+    float *dw, *db;            // db nullable
+    float *Wm, *Vm, *slots;    // workspace: transformed dy / x tiles, partial products [tile][split]
+    float *D;                  // workspace: the 36 reduced products [pos][Kpad][Cpad]
+    float *bias_part;          // workspace: [K][chunks*2], or null
+    float scale;
+    int32_t accumulate;
+    int32_t N, C, H, W, K, P, Q, pad_h, pad_w;
+    int32_t TH, TW, T, chunks; // 4x4 output tiles per image (rows, cols), in total; 8-tile chunks of the depth
+    int32_t Kpad, Cpad;        // rows of the two operands, multiples of the GEMM tile
+    int32_t x_bytes, dy_bytes; // both below 2^31
+    int32_t tile_cfg, split;
+    FastDiv div_THW, div_TW;
+};
+hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s);
 int wino4_tile_m(int cfg);
 int wino4_tile_n(int cfg);
 hipError_t launch_wino4(const W4Args &a, hipStream_t s);

@@ -392,6 +392,206 @@ __global__ __launch_bounds__(256) void wino4_output_kernel(W4Args a)
     }
 }
 
+// ---------------------------------------------------------- backward-weight
+// The tile relation is bilinear in (g, d), so the filter gradient is
+//   dg = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
+// (checked exactly on the CPU): 36 GEMMs  D[pos][k][c] = sum_t W[pos][t][k] V[pos][t][c]
+// whose reduction axis is the tiles of the whole batch.  The same GEMM kernel serves: both
+// operands are written in MFMA order with the TILE index as the depth, rows = filters /
+// channels.  K x C is only a few workgroup tiles, so every tile is cut into depth shares
+// (all go to slots); the last kernel adds the shares in order and applies G^T . G.
+//
+
+// A y on four values (a column or a row of the 4x4 gradient tile)
+__device__ __forceinline__ void w4_a(const float y0, const float y1, const float y2, const float y3, float (&o)[6])
+{
+    const float e = y0 + y2, f = y1 + y3, g = y0 + 4.f * y2, h = 2.f * y1 + 8.f * y3;
+    o[0] = y0;
+    o[1] = e + f;
+    o[2] = e - f;
+    o[3] = g + h;
+    o[4] = g - h;
+    o[5] = y3;
+}
+
+// Thread mapping of the two transforms: a wave takes 8 rows (channels / filters) x the 8
+// tiles of one chunk, lane = row*8 + half*4 + j with tile = 8*chunk + 2*j + half, so that a
+// store instruction writes, per position, two runs of 128 contiguous bytes (the [row][j]
+// vectors of both halves) and a load instruction reads 8 planes x 8 neighbouring tiles.
+__global__ __launch_bounds__(256) void wino4_wg_input_kernel(W4WgradArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 3, h = (lane >> 2) & 1;
+    const int c = blockIdx.x * 32 + wave * 8 + (lane >> 3);
+    const int tc = blockIdx.y;
+    if (c >= a.Cpad) return;
+    const int t = tc * 8 + 2 * j + h;
+    const bool tv = t < a.T && c < a.C;
+    const int tl = t < a.T ? t : 0;
+    const int HW = a.H * a.W;
+    const int n = (int)fast_div((uint32_t)tl, a.div_THW), rem = tl - n * (a.TH * a.TW);
+    const int th = (int)fast_div((uint32_t)rem, a.div_TW), tw = rem - th * a.TW;
+    const int ih0 = 4 * th - a.pad_h, iw0 = 4 * tw - a.pad_w;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
+    const int cl = c < a.C ? c : 0;
+    uint32_t colbad = 0;
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+        if (!((unsigned)(iw0 + i) < (unsigned)a.W)) colbad |= 1u << i;
+    float d[6][6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        const bool ok = tv && (unsigned)(ih0 + i) < (unsigned)a.H;
+        const uint32_t rowoff = ok ? (uint32_t)(((n * a.C + cl) * HW + (ih0 + i) * a.W + iw0) * 4) : 0x80000000u;
+#pragma unroll
+        for (int jj = 0; jj < 6; ++jj) {
+            const uint32_t off = ((colbad >> jj) & 1u) ? 0x80000000u : (rowoff + 4u * jj);
+            d[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+        }
+    }
+    float tcol[6][6];
+#pragma unroll
+    for (int jj = 0; jj < 6; ++jj) {
+        float o[6];
+        w4_bt(d[0][jj], d[1][jj], d[2][jj], d[3][jj], d[4][jj], d[5][jj], o);
+#pragma unroll
+        for (int i = 0; i < 6; ++i) tcol[i][jj] = o[i];
+    }
+    const int64_t pos_stride = (int64_t)a.chunks * 2 * a.Cpad * 4;
+    float *dst = a.Vm + ((int64_t)(tc * 2 + h) * a.Cpad + c) * 4 + j;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        float o[6];
+        w4_bt(tcol[i][0], tcol[i][1], tcol[i][2], tcol[i][3], tcol[i][4], tcol[i][5], o);
+#pragma unroll
+        for (int jj = 0; jj < 6; ++jj) dst[(6 * i + jj) * pos_stride] = o[jj];
+    }
+}
+
+// W[pos][chunk][half][k][j] = (A dy_t A^T)[pos]; also each tile's gradient sum (position
+// (1,1) of A dy A^T), added over the four tiles of a (chunk, half) by lane shuffles, as
+// bias_part[k][chunk*2+half]
+__global__ __launch_bounds__(256) void wino4_wg_dy_kernel(W4WgradArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 3, h = (lane >> 2) & 1;
+    const int k = blockIdx.x * 32 + wave * 8 + (lane >> 3);
+    const int tc = blockIdx.y;
+    if (k >= a.Kpad) return;
+    const int t = tc * 8 + 2 * j + h;
+    const bool tv = t < a.T && k < a.K;
+    const int tl = t < a.T ? t : 0;
+    const int PQ = a.P * a.Q;
+    const int n = (int)fast_div((uint32_t)tl, a.div_THW), rem = tl - n * (a.TH * a.TW);
+    const int th = (int)fast_div((uint32_t)rem, a.div_TW), tw = rem - th * a.TW;
+    const int oh = 4 * th, ow = 4 * tw;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.dy_bytes, 0x00020000);
+    const int kl = k < a.K ? k : 0;
+    float y[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const bool ok = tv && oh + i < a.P;
+        const uint32_t rowoff = ok ? (uint32_t)(((n * a.K + kl) * PQ + (oh + i) * a.Q + ow) * 4) : 0x80000000u;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const uint32_t off = ow + jj < a.Q ? rowoff + 4u * jj : 0x80000000u;
+            y[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+        }
+    }
+    float tcol[6][4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        float o[6];
+        w4_a(y[0][jj], y[1][jj], y[2][jj], y[3][jj], o);
+#pragma unroll
+        for (int i = 0; i < 6; ++i) tcol[i][jj] = o[i];
+    }
+    const int64_t pos_stride = (int64_t)a.chunks * 2 * a.Kpad * 4;
+    float *dst = a.Wm + ((int64_t)(tc * 2 + h) * a.Kpad + k) * 4 + j;
+    float tsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        float o[6];
+        w4_a(tcol[i][0], tcol[i][1], tcol[i][2], tcol[i][3], o);
+#pragma unroll
+        for (int jj = 0; jj < 6; ++jj) dst[(6 * i + jj) * pos_stride] = o[jj];
+        if (i == 1) tsum = o[1];
+    }
+    if (a.bias_part) {
+        // tiles j = 0..3 of this (row, half) sit in four neighbouring lanes
+        const float s1 = tsum + __shfl_xor(tsum, 1);
+        const float s2 = s1 + __shfl_xor(s1, 2);
+        if (j == 0 && k < a.K) a.bias_part[(int64_t)k * (a.chunks * 2) + tc * 2 + h] = s2;
+    }
+}
+
+// G^T m on six values
+__device__ __forceinline__ void w4_gt(const float m0, const float m1, const float m2, const float m3,
+                                      const float m4, const float m5, float (&o)[3])
+{
+    const float s12 = m1 + m2, s34 = m3 + m4;
+    o[0] = 0.25f * m0 - (1.f / 6.f) * s12 + (1.f / 24.f) * s34;
+    o[1] = (1.f / 6.f) * (m2 - m1) + (1.f / 12.f) * (m3 - m4);
+    o[2] = (1.f / 6.f) * (s34 - s12) + m5;
+}
+
+// dw[k][c] = scale * G^T D[.][k][c] G (+ dw[k][c]) from the reduced products D[pos][Kpad][Cpad];
+// a thread takes one filter and four consecutive channels (lanes along c).
+__global__ __launch_bounds__(256) void wino4_wg_output_kernel(W4WgradArgs a)
+{
+    const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const int k = blockIdx.y;
+    if (c0 >= a.C) return;
+    const int64_t pos_stride = (int64_t)a.Kpad * a.Cpad;
+    const float *p = a.D + (int64_t)k * a.Cpad + c0;
+    floatx4 m[6][6];
+#pragma unroll
+    for (int pos = 0; pos < 36; ++pos) m[pos / 6][pos % 6] = *reinterpret_cast<const floatx4 *>(p + pos * pos_stride);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (c0 + e >= a.C) break;
+        float tc[3][6];
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            float o[3];
+            w4_gt(m[0][j][e], m[1][j][e], m[2][j][e], m[3][j][e], m[4][j][e], m[5][j][e], o);
+#pragma unroll
+            for (int i = 0; i < 3; ++i) tc[i][j] = o[i];
+        }
+        float *dst = a.dw + ((int64_t)k * a.C + c0 + e) * 9;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            float o[3];
+            w4_gt(tc[i][0], tc[i][1], tc[i][2], tc[i][3], tc[i][4], tc[i][5], o);
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const float g = a.scale * o[j];
+                dst[3 * i + j] = a.accumulate ? dst[3 * i + j] + g : g;
+            }
+        }
+    }
+}
+
+// db[k] = scale * sum_q bias_part[k][q] (+ db[k]), q over the chunk halves: one wave per
+// filter, lane l adds elements l, l+64, ... in order, the 64 lane sums are combined by a
+// fixed tree of lane exchanges: deterministic.
+__global__ __launch_bounds__(256) void wino4_wg_bias_kernel(W4WgradArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= a.K) return;
+    const int n = a.chunks * 2;
+    const float *p = a.bias_part + (int64_t)k * n;
+    float sacc = 0.f;
+    for (int i = lane; i < n; i += 64) sacc += p[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sacc += __shfl_xor(sacc, o);
+    if (lane == 0) {
+        const float g = a.scale * sacc;
+        a.db[k] = a.accumulate ? a.db[k] + g : g;
+    }
+}
+
 // ---------------------------------------------------------------- launchers
 int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : 256; }     // 2 x 2 or 4 x 1 wave tiles of 64 x 128
 int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : 128; }
@@ -441,6 +641,41 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(wino4_output_kernel, dim3((unsigned)((a.T + 255) / 256), (unsigned)a.Kout), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s)
+{
+    const dim3 gx((unsigned)((a.Cpad + 31) / 32), (unsigned)a.chunks);
+    hipLaunchKernelGGL(wino4_wg_input_kernel, gx, dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 gy((unsigned)((a.Kpad + 31) / 32), (unsigned)a.chunks);
+    hipLaunchKernelGGL(wino4_wg_dy_kernel, gy, dim3(256), 0, s, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    W4GemmArgs g = {};
+    g.A = a.Wm; g.B = a.Vm; g.C = a.D; g.slots = a.slots;
+    g.chunks = a.chunks; g.Mpad = a.Kpad; g.Npad = a.Cpad;
+    g.tiles_m = a.Kpad / wino4_tile_m(a.tile_cfg);
+    g.tiles_n = a.Cpad / wino4_tile_n(a.tile_cfg);
+    g.tile_base = 0; g.nsplit = a.split;                // >= 2: every share goes to its slot
+    const unsigned grid = (unsigned)(36 * g.tiles_m * g.tiles_n * a.split);
+    if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // the depth shares of every tile added in order into D, then the filter transform
+    const dim3 gf((unsigned)(36 * g.tiles_m * g.tiles_n), 8);
+    if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), gf, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128>), gf, dim3(256), 0, s, g);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 go((unsigned)((a.C + 1023) / 1024), (unsigned)a.K);
+    hipLaunchKernelGGL(wino4_wg_output_kernel, go, dim3(256), 0, s, a);
+    e = hipGetLastError();
+    if (e != hipSuccess || !a.db) return e;
+    hipLaunchKernelGGL(wino4_wg_bias_kernel, dim3((unsigned)((a.K + 3) / 4)), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

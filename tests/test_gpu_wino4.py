@@ -40,6 +40,48 @@ def test_wino4_parity(geom):
         assert r <= TOL_WINOGRAD, "%s: %.3e" % (name, r)
 
 
+WG_SHAPES = [
+    (2, 32, 16, 16, 64, 3, 3, 1, 1, 1, 1),
+    (3, 64, 28, 28, 128, 3, 3, 1, 1, 1, 1),
+    (2, 20, 13, 13, 40, 3, 3, 1, 1, 1, 1),        # odd map: gradient tiles cut by the edge; ragged rows
+    (5, 300, 14, 14, 200, 3, 3, 1, 1, 1, 1),      # several row and column tiles
+    (4, 16, 9, 11, 24, 3, 3, 1, 1, 0, 0),
+    (2, 24, 7, 10, 72, 3, 3, 1, 1, 2, 2),
+    (2, 3, 12, 12, 8, 3, 3, 1, 1, 1, 0),
+    (37, 48, 12, 12, 136, 3, 3, 1, 1, 1, 1),      # 333 tiles: last chunk ragged, unequal depth shares
+]
+
+
+@pytest.mark.parametrize("geom", WG_SHAPES, ids=[str(i) for i in range(len(WG_SHAPES))])
+def test_wino4_wgrad_parity(geom):
+    print("case", geom, flush=True)
+    x, w, b, dy = random_layer(geom, seed=4600 + sum(geom))
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD4, passes=("bwd_weight",))
+    ref = oracle_layer(geom, x, w, b, dy)
+    for name in ("dw", "db"):
+        assert np.isfinite(got[name]).all(), name
+        r = max_err_ratio(got[name], ref[name])
+        assert r <= TOL_WINOGRAD, "%s: %.3e" % (name, r)
+
+
+def test_wino4_wgrad_scale_accumulate_and_no_dbias():
+    import oracle
+    geom = (3, 32, 14, 14, 64, 3, 3, 1, 1, 1, 1)
+    x, w, b, dy = random_layer(geom, seed=4699)
+    rng = np.random.default_rng(5)
+    dw0 = rng.standard_normal(w.shape).astype(np.float32)
+    db0 = rng.standard_normal(b.shape).astype(np.float32)
+    got = gpu_layer(geom, x, w, b, dy, algo=B.ALGO_WINOGRAD4, passes=("bwd_weight",), scale=0.5, dw0=dw0, db0=db0)
+    rdw, rdb = oracle.bwd_weight(geom, x, dy, 0.5)
+    assert max_err_ratio(got["dw"], rdw + dw0) <= TOL_WINOGRAD
+    assert max_err_ratio(got["db"], rdb + db0) <= TOL_WINOGRAD
+    import torch
+    dev = torch.device("cuda:0")
+    dw = torch.full(w.shape, float("nan"), device=dev)
+    B.conv2d_bwd_weight(geom, torch.from_numpy(x).to(dev), torch.from_numpy(dy).to(dev), dw, None, algo=B.ALGO_WINOGRAD4)
+    assert max_err_ratio(dw.cpu().numpy(), oracle.bwd_weight(geom, x, dy, 1.0)[0]) <= TOL_WINOGRAD
+
+
 def test_wino4_relu_and_no_bias():
     import torch
     geom = (2, 32, 14, 14, 64, 3, 3, 1, 1, 1, 1)
@@ -60,5 +102,5 @@ def test_wino4_relu_and_no_bias():
 def test_wino4_refuses_what_it_cannot_do():
     for geom, op in (((2, 8, 16, 16, 8, 5, 5, 1, 1, 2, 2), B.OP_FWD),
                      ((2, 8, 16, 16, 8, 3, 3, 2, 2, 1, 1), B.OP_FWD),
-                     ((2, 8, 16, 16, 8, 3, 3, 1, 1, 1, 1), B.OP_BWD_WEIGHT)):
+                     ((1, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1), B.OP_BWD_WEIGHT)):        # 4 tiles: too few to split
         assert B.conv2d_workspace_bytes(geom, op, B.ALGO_WINOGRAD4) == 0
