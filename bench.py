@@ -28,6 +28,16 @@ if ROOT not in sys.path:
 PEAK_MFMA_FP32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
 
+# kernels whose roofline is HBM bandwidth over their minimal bytes (streaming and transform
+# kernels); every other main kernel is a dense contraction on fp32 MFMA
+HBM_BOUND_KERNELS = {"pw_stream_kernel", "pw_wgrad_kernel", "bwd_data_smallc_kernel", "wino4_input_kernel",
+                     "wino4_output_kernel", "wino4_wg_input_kernel", "wino4_wg_dy_kernel"}
+
+# main kernel of a call by (resolved algorithm, pass), for the call-level cross-check of the
+# roofline block (3x3 layers with even maps; other shapes take sibling kernels)
+CALL_KERNEL = {(3, "fwd"): "wino4_gemm_kernel", (3, "bwd_data"): "wino4_gemm_kernel", (3, "bwd_weight"): "wino4_gemm_kernel",
+               (2, "fwd"): "wino_pair_kernel", (2, "bwd_data"): "wino_pair_kernel", (2, "bwd_weight"): "wino_wgrad_vec_kernel"}
+
 WORKLOADS = {"tiny": 0, "alexnet": 1, "vgg16": 2, "inception": 3, "overfeat": 4, "apply": -1}
 
 
@@ -72,9 +82,11 @@ def main() -> int:
                          "calls the algorithm cannot serve use auto")
     ap.add_argument("--detail", action="store_true", help="per-layer table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-calib", action="store_true", help="skip the MFMA / copy probes (roofline.measured_peak)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
-                    help="run one device-to-device copy of this many MiB before the warm-up (a kernel of "
-                         "known traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+                    help="run the library's probe_copy_kernel once over this many MiB before the warm-up (a kernel "
+                         "of known traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters, see "
+                         "paper_1606_04884_amd/profsum.py)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -155,9 +167,10 @@ def main() -> int:
     if args.calib_copy_mib > 0:
         src = torch.ones(args.calib_copy_mib * (1 << 18), dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        B.conv2d_probe_copy(src, dst, stream=stream)
         torch.cuda.synchronize()
         del src, dst
+    calib = None if args.no_calib else calibrate(dev, stream)
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -168,6 +181,15 @@ def main() -> int:
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # the same K steps once more with the library's per-kernel events on (two events per
+    # main-kernel launch: they cost a few percent of the step, so they stay out of `value`)
+    B.conv2d_profile_begin(args.steps * (16 * len(recs) + 16))
+    tp0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(False)
+    torch.cuda.synchronize()
+    ms_per_step_profiled = (time.perf_counter() - tp0) * 1e3 / args.steps
+    nrec = B.conv2d_profile_end()
     total_flops = 3.0 * sum(r["flops"] for r in recs)
     tflops = total_flops / (ms_per_step * 1e-3) / 1e12
 
@@ -175,47 +197,60 @@ def main() -> int:
     per = {}
     for op, li, e0, e1 in ev:
         per.setdefault((op, li), []).append(e0.elapsed_time(e1))
-    # kernel families: which main kernel served the call
-    def family(op, li):
-        if recs[li]["algo"][op] == 3:
-            return ("wino4_wgrad (wino4_gemm_kernel + transform kernels: unfused F(4x4,3x3) bwd_weight calls)"
-                    if op == "bwd_weight" else
-                    "wino4 (wino4_gemm_kernel + transform kernels: unfused F(4x4,3x3) fwd + bwd_data calls)")
-        wino = recs[li]["algo"][op] == 2
-        if op == "bwd_weight":
-            return ("wino_wgrad (wino_wgrad_vec_kernel / wino_wgrad_kernel: Winograd bwd_weight calls)" if wino
-                    else "wgrad (wgrad_kernel / pw_wgrad_kernel: implicit-GEMM bwd_weight calls)")
-        return ("wino_fwd_bwd (wino_pair_kernel / wino_fused_kernel: Winograd fwd + bwd_data calls)" if wino
-                else "gemmconv (gemmconv_kernel / pw_stream_kernel / bwd_data_smallc_kernel: implicit-GEMM and direct fwd + bwd_data calls)")
-
-    fam = {}
     op_ms = {"fwd": 0.0, "bwd_data": 0.0, "bwd_weight": 0.0}
+    xflops_step = 0.0
     for (op, li), ts in per.items():
-        f = fam.setdefault(family(op, li), dict(ms=0.0, xflops=0.0, dflops=0.0, calls=0))
-        f["ms"] += sum(ts)
-        f["xflops"] += recs[li]["xflops"][op] * len(ts)
-        f["dflops"] += recs[li]["flops"] * len(ts)
-        f["calls"] += len(ts)
         op_ms[op] += sum(ts)
+        xflops_step += recs[li]["xflops"][op]
+
+    # ---- per-kernel durations: the library's own events around every main-kernel launch
+    # of the timed region, on the launch stream (conv2d_profile_*), with the algorithmic
+    # flops / minimal bytes each launch stated ----
+    kern = {}
+    for i in range(nrec):
+        kid, fl, by, ms = B.conv2d_profile_record(i)
+        k = kern.setdefault(B.conv2d_profile_kernel_name(kid), dict(ms=[], flops=0.0, bytes=0.0))
+        k["ms"].append(ms)
+        k["flops"] += fl
+        k["bytes"] += by
+
+    def kernel_line(name, k):
+        tot = sum(k["ms"])
+        # (the taps forms serve both first layers, bound by their output, and small 5x5 banks,
+        # bound by the matrix pipe: by their arithmetic intensity against the ridge)
+        hbm = name in HBM_BOUND_KERNELS or ("TAPS" in name and k["flops"] / max(k["bytes"], 1.0)
+                                            < PEAK_MFMA_FP32_TFLOPS * 1e3 / PEAK_HBM_GBS)
+        if hbm:
+            ach, peak, unit = k["bytes"] / (tot * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        else:
+            ach, peak, unit = k["flops"] / (tot * 1e-3) / 1e12, PEAK_MFMA_FP32_TFLOPS, "TFLOP/s"
+        return {"bound": "hbm" if hbm else "mfma", "kernel": name, "achieved": round(ach, 3), "peak": peak,
+                "unit": unit, "frac": round(ach / peak, 4), "avg_launch_ms": round(tot / len(k["ms"]), 4),
+                "launches": len(k["ms"]), "ms_per_step": round(tot / args.steps, 3)}
+
     if args.detail:
-        print("%-12s %-10s %-5s %9s %10s %8s %10s" % ("layer", "op", "algo", "ms(avg)", "TF/s(dir)", "%peak", "TF/s(exec)"),
-              file=sys.stderr)
+        print("%-12s %-10s %-5s %9s %9s %9s %10s %8s %10s" % ("layer", "op", "algo", "ms(avg)", "ms(med)", "ms(min)",
+                                                            "TF/s(dir)", "%peak", "TF/s(exec)"), file=sys.stderr)
         for li, r in enumerate(recs):
             for op in ("fwd", "bwd_data", "bwd_weight"):
-                ts = per[(op, li)]
+                ts = sorted(per[(op, li)])
                 ms = sum(ts) / len(ts)
+                med = ts[len(ts) // 2] if len(ts) % 2 else 0.5 * (ts[len(ts) // 2 - 1] + ts[len(ts) // 2])
                 tf = r["flops"] / (ms * 1e-3) / 1e12
                 xtf = r["xflops"][op] / (ms * 1e-3) / 1e12
-                print("%-12s %-10s %-5s %9.3f %10.2f %8.1f %10.2f" % (
-                    r["L"].name, op, {2: "wino", 3: "wino4"}.get(r["algo"][op], "igemm"), ms, tf,
+                print("%-12s %-10s %-5s %9.3f %9.3f %9.3f %10.2f %8.1f %10.2f" % (
+                    r["L"].name, op, {2: "wino", 3: "wino4"}.get(r["algo"][op], "igemm"), ms, med, ts[0], tf,
                     100 * tf / PEAK_MFMA_FP32_TFLOPS, xtf), file=sys.stderr)
         for op in op_ms:
             print("total %-10s %9.3f ms/step" % (op, op_ms[op] / args.steps), file=sys.stderr)
-        for k, f in fam.items():
-            print("family %-100s %8.3f ms/step  exec %.1f TF/s" % (k, f["ms"] / args.steps,
-                                                                 f["xflops"] / f["ms"] / 1e9), file=sys.stderr)
-        print("wall %.3f ms/step, %.2f TFLOP/s direct-equivalent (%.1f%% of fp32 MFMA peak)" % (
-            ms_per_step, tflops, 100 * tflops / PEAK_MFMA_FP32_TFLOPS), file=sys.stderr)
+        for name, k in sorted(kern.items(), key=lambda kv: -sum(kv[1]["ms"])):
+            kl = kernel_line(name, k)
+            print("kernel %-24s %8.3f ms/step %5d launches  %9.1f %s = %.3f of %s peak" % (
+                name, kl["ms_per_step"], kl["launches"], kl["achieved"], kl["unit"], kl["frac"], kl["bound"]),
+                file=sys.stderr)
+        print("wall %.3f ms/step, %.2f TFLOP/s direct-equivalent (%.1f%% of fp32 MFMA peak); executed %.2f TFLOP/s" % (
+            ms_per_step, tflops, 100 * tflops / PEAK_MFMA_FP32_TFLOPS, xflops_step / (ms_per_step * 1e-3) / 1e12),
+            file=sys.stderr)
         # training skips the input gradient of the first layer: the same totals without it
         first_bd = sum(per[("bwd_data", 0)]) / args.steps
         ev_ms = sum(op_ms.values()) / args.steps
@@ -227,36 +262,54 @@ def main() -> int:
         if args.workload == "inception":
             grouped_1x1(recs, per, ws, stream)
 
-    # roofline of the dominant kernel family: MFMA flops the algorithm executes
-    # (not the direct-equivalent count) over the summed event durations of its calls
-    kname, kf = max(fam.items(), key=lambda kv: kv[1]["ms"])
-    achieved = kf["xflops"] / (kf["ms"] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 3),
-                "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_MFMA_FP32_TFLOPS, 4), "traffic": None,
-                "avg_launch_ms": round(kf["ms"] / kf["calls"], 4), "launches": kf["calls"],
-                "direct_equivalent_tflops": round(kf["dflops"] / (kf["ms"] * 1e-3) / 1e12, 3)}
-
-    # HBM traffic of that kernel family per launch, from the committed rocprofv3
-    # counter summary of this workload (null if none has been taken)
+    # roofline of the dominant kernel: the one with the largest summed duration in the
+    # timed region; the next ones follow in "others"
+    ranked = sorted(kern.items(), key=lambda kv: -sum(kv[1]["ms"]))
+    roofline = kernel_line(*ranked[0])
+    roofline["traffic"] = None
+    # HBM traffic of that kernel per launch as rocprofv3 counted it in an earlier profiling
+    # run of this command (the summary is committed; null if none has been taken)
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
     if os.path.exists(tpath):
         try:
             with open(tpath) as fh:
                 tr = json.load(fh)
-            key = kname.split(" ")[0]
-            if key in tr.get("bytes_per_launch", {}):
-                roofline["traffic"] = tr["bytes_per_launch"][key]
+            if roofline["kernel"] in tr.get("bytes_per_launch", {}):
+                roofline["traffic"] = tr["bytes_per_launch"][roofline["kernel"]]
+                roofline["traffic_source"] = "profiles/traffic_%s.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, %s)" % (
+                    args.workload, tr.get("date", "undated"))
         except (OSError, ValueError):
             pass
+    if calib:
+        roofline["measured_peak"] = calib
+        ref = calib["hbm_copy_GBps"] if roofline["bound"] == "hbm" else calib["mfma_f32_TFLOPs"]
+        roofline["frac_of_measured_peak"] = round(roofline["achieved"] / ref, 4)
+    roofline["others"] = [kernel_line(n, k) for n, k in ranked[1:4]]
+    roofline["measured_in"] = ("%d further steps of the same loop right after the timed region, HIP events of the library "
+                               "around every main-kernel launch on the launch stream (%.3f ms/step with them on)"
+                               % (args.steps, ms_per_step_profiled))
+    # cross-check from the timed region itself: the calls this kernel serves, events around the calls
+    fam_ms = fam_x = 0.0
+    fam_calls = 0
+    for (op, li), ts in per.items():
+        if CALL_KERNEL.get((recs[li]["algo"][op], op)) == roofline["kernel"]:
+            fam_ms += sum(ts)
+            fam_x += recs[li]["xflops"][op] * len(ts)
+            fam_calls += len(ts)
+    if fam_calls:
+        roofline["timed_region_calls"] = {"calls": fam_calls, "avg_call_ms": round(fam_ms / fam_calls, 4),
+                                          "executed_tflops": round(fam_x / (fam_ms * 1e-3) / 1e12, 3),
+                                          "note": "whole calls (main kernel + its transform / reduction kernels)"}
 
     out = {
-        "metric": "fp32 conv TFLOP/s fwd+bwd (%s conv stack)" % args.workload,
+        "metric": "fp32 conv TFLOP/s fwd+bwd, direct-equivalent flops (%s conv stack)" % args.workload,
         "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "pct_mfma_peak": round(100 * tflops / PEAK_MFMA_FP32_TFLOPS, 2),
+        "pct_mfma_peak_direct_equivalent": round(100 * tflops / PEAK_MFMA_FP32_TFLOPS, 2),
+        "executed_tflops_step": round(xflops_step / (ms_per_step * 1e-3) / 1e12, 3),
+        "executed_frac_step": round(xflops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_FP32_TFLOPS, 4),
         "config": {"workload": "%s conv stack, N=%d, %d layers, fwd+bwd_data+bwd_weight, fp32 NCHW"
                    % (args.workload, layers[0].N, len(layers)), "algo": args.algo},
         "roofline": roofline,
@@ -266,6 +319,41 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(cfg, layers)
     print(json.dumps(out))
     return 0
+
+
+def calibrate(dev, stream):
+    """What this chip sustains, outside the timed region: a pure v_mfma_f32_32x32x2_f32 loop
+    and a 16-byte-vector copy / fill of 1 GiB (the library's probe kernels), best of three."""
+    import torch
+    from paper_1606_04884_amd import binding as B
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    sink = torch.zeros(4, device=dev)
+    n = 1 << 28
+    src, dst = torch.ones(n, device=dev), torch.empty(n, device=dev)
+
+    def best(fn, reps=3):
+        fn()
+        ts = []
+        for _ in range(reps):
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return min(ts) * 1e-3
+
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = B.conv2d_probe_mfma_f32(sink, 4000, stream=stream)
+
+    t_m = best(mfma)
+    t_c = best(lambda: B.conv2d_probe_copy(src, dst, stream=stream))
+    t_f = best(lambda: B.conv2d_probe_copy(None, dst, stream=stream))
+    return {"mfma_f32_TFLOPs": round(flops[0] / t_m / 1e12, 2), "hbm_copy_GBps": round(8.0 * n / t_c / 1e9, 1),
+            "hbm_fill_GBps": round(4.0 * n / t_f / 1e9, 1),
+            "how": "library probes: 512x4 waves of v_mfma_f32_32x32x2_f32 only (%.0f ms); float4 copy and fill of 1 GiB"
+                   % (t_m * 1e3)}
 
 
 def bench_apply(args, dev):

@@ -30,10 +30,12 @@
  * Ownership: the caller owns every buffer, including the workspace.  The library
  * allocates no device memory and keeps no state between calls; it only enqueues
  * kernels on the caller's stream and returns without synchronising.  Concurrent
- * calls on different streams are safe if their buffers (and workspaces) differ.
+ * calls from several threads on different streams are safe if their buffers (and
+ * workspaces) differ (one-time kernel attribute set-up is guarded).
  *
- * Errors: every function returns CONV2D_OK (0) or a negative code; on error
- * nothing has been enqueued.  No exceptions cross this boundary.
+ * Errors: every function returns CONV2D_OK (0) or a negative code.  On an argument,
+ * algorithm or workspace error nothing has been enqueued; CONV2D_ERR_LAUNCH (HIP refused a
+ * launch) may follow earlier launches of the same call.  No exceptions cross this boundary.
  */
 #ifndef MI355CONV_H
 #define MI355CONV_H
@@ -107,9 +109,9 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
 
 /* Forward (Torch's updateOutput; Sec. 4.1/4.2).  Overwrites all of y.
  * bias may be NULL (no bias); it is added in the kernel's epilogue, before the
- * only store of y ("fully fused kernels", Sec. 4.2 "Neon").
+ * only store of y (Sec. 4.2 "Neon": transforms and epilogue belong in the product's kernel).
  * ws: device pointer to >= conv2d_workspace_bytes(d, CONV2D_FWD, algo) bytes,
- * 256-byte aligned; contents are scratch.  hip_stream: a hipStream_t (NULL = the
+ * 256-byte aligned (checked: CONV2D_ERR_WORKSPACE otherwise); contents are scratch.  hip_stream: a hipStream_t (NULL = the
  * default stream). */
 int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias,
                float *y, void *ws, size_t ws_bytes, conv2d_algo algo, void *hip_stream);
@@ -136,7 +138,7 @@ int conv2d_fwd_static(const conv2d_desc *d, const float *x, const float *w, cons
 /* Forward followed by the rectifier of the layer after it, in the same epilogue:
  * y = max(0, conv(x, w) + bias), stored once.  (Sec. 4.1 lists the RELU layers as the
  * small remainder of the per-layer time next to the convolutions; fusing them is the
- * "fully fused kernels" item of Sec. 4.2 "Neon" taken one step further: the separate
+ * fusion item of Sec. 4.2 "Neon" taken one step further: the separate
  * layer would read and write y once more.)  Same arguments, workspace, algorithm choice
  * and errors as conv2d_fwd; the sum is the one conv2d_fwd forms, max(., 0) is applied to
  * it in fp32 (a NaN sum gives 0). */
@@ -194,6 +196,32 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy,
  * x.  n == 0 is a no-op; n < 0 returns CONV2D_ERR_GEOMETRY.  Enqueues on hip_stream
  * and returns. */
 int apply_mul_add(const float *x, float *y, int64_t n, float a, float b, void *hip_stream);
+
+/* ---- measurement helpers (not part of the convolution path) ------------------------
+ * Opt-in timing of the library's main kernels, for roofline figures: between
+ * conv2d_profile_begin(capacity) and conv2d_profile_end() every launch of a main kernel
+ * (the GEMM / Winograd / streaming kernels and the transform kernels of the unfused
+ * Winograd path; not the small preparation and reduction kernels) is bracketed by two HIP
+ * events on its stream, up to `capacity` launches.  begin creates the host-side event
+ * objects (kept for reuse until the library is unloaded) and returns CONV2D_OK or an
+ * error; end returns the number of launches recorded.  After the caller has synchronised
+ * the streams, conv2d_profile_record(i, ...) returns launch i's kernel id, the algorithmic
+ * flops and minimal HBM bytes the launcher stated for it, and its duration in ms.
+ * Process-wide host state, not thread-safe: one measuring thread at a time. */
+int conv2d_profile_begin(int capacity);
+int conv2d_profile_end(void);
+int conv2d_profile_record(int i, int32_t *kernel, double *flops, double *bytes, float *ms);
+const char *conv2d_profile_kernel_name(int kernel);
+
+/* What the chip sustains, for calibrating roofline fractions (Sec. 3.3 measures the
+ * bandwidth of trivial kernels in the same spirit).  conv2d_probe_mfma_f32 enqueues a
+ * kernel that does nothing but v_mfma_f32_32x32x2_f32 (512 workgroups x 4 waves x iters x
+ * 32 instructions) and stores the flops it executes in *flops (host); sink: 4 bytes of
+ * device memory, never written.  conv2d_probe_copy enqueues a 16-byte-vector copy of n
+ * floats from src to dst (device, 16-byte aligned, n % 4 == 0), or a fill of dst when src
+ * is NULL.  The caller times them with events. */
+int conv2d_probe_mfma_f32(float *sink, int32_t iters, double *flops, void *hip_stream);
+int conv2d_probe_copy(const float *src, float *dst, int64_t n, void *hip_stream);
 
 /* Static, never-NULL description of a status code. */
 const char *conv2d_status_string(int status);

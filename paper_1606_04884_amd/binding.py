@@ -21,7 +21,8 @@ STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = ("conv2d_output_dims", "conv2d_pick_algo", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_fwd_static",
            "conv2d_fwd_relu", "conv2d_fwd_relu_pool2",
            "conv2d_fwd_1x1_group", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_status_string", "conv2d_version",
-           "apply_mul_add")
+           "apply_mul_add", "conv2d_profile_begin", "conv2d_profile_end", "conv2d_profile_record",
+           "conv2d_profile_kernel_name", "conv2d_probe_mfma_f32", "conv2d_probe_copy")
 
 
 class conv2d_desc(C.Structure):
@@ -73,6 +74,19 @@ def load() -> C.CDLL:
     lib.conv2d_bwd_weight.restype = C.c_int
     lib.apply_mul_add.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_float, vp]
     lib.apply_mul_add.restype = C.c_int
+    lib.conv2d_profile_begin.argtypes = [C.c_int]
+    lib.conv2d_profile_begin.restype = C.c_int
+    lib.conv2d_profile_end.argtypes = []
+    lib.conv2d_profile_end.restype = C.c_int
+    lib.conv2d_profile_record.argtypes = [C.c_int, i32p, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                          C.POINTER(C.c_float)]
+    lib.conv2d_profile_record.restype = C.c_int
+    lib.conv2d_profile_kernel_name.argtypes = [C.c_int]
+    lib.conv2d_profile_kernel_name.restype = C.c_char_p
+    lib.conv2d_probe_mfma_f32.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), vp]
+    lib.conv2d_probe_mfma_f32.restype = C.c_int
+    lib.conv2d_probe_copy.argtypes = [vp, vp, C.c_int64, vp]
+    lib.conv2d_probe_copy.restype = C.c_int
     lib.conv2d_status_string.argtypes = [C.c_int]
     lib.conv2d_status_string.restype = C.c_char_p
     lib.conv2d_version.argtypes = []
@@ -153,16 +167,23 @@ def alloc_workspace(nbytes: int, device="cuda"):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
-def _ws(ws, need: int):
+def _ws(ws, need: int, stream=None):
+    """Caller's workspace, or a temporary one.  A temporary is released when the Python call
+    returns while the kernels are only enqueued: it is recorded on the stream they run on, so
+    that torch's allocator does not hand the block out again before they have finished."""
     if ws is None:
+        import torch
         ws = alloc_workspace(need)
+        s = _stream(stream)
+        if s != torch.cuda.current_stream().cuda_stream:
+            ws.record_stream(torch.cuda.ExternalStream(s))
     return ws, ws.data_ptr(), ws.numel() * ws.element_size()
 
 
 def conv2d_fwd(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=None) -> None:
     dd = _desc(d)
     P, Q = conv2d_output_dims(dd)
-    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, algo))
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, algo), stream)
     rc = load().conv2d_fwd(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"),
                            _ptr(w, (dd.K, dd.C, dd.R, dd.S), "w"), _ptr(bias, (dd.K,), "bias"),
                            _ptr(y, (dd.N, dd.K, P, Q), "y"), wptr, wbytes, int(algo),
@@ -186,7 +207,7 @@ def conv2d_fwd_static(d, x, w, bias, y, algo: int = ALGO_AUTO, stream=None) -> N
 def conv2d_fwd_relu(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=None) -> None:
     dd = _desc(d)
     P, Q = conv2d_output_dims(dd)
-    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, algo))
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, algo), stream)
     rc = load().conv2d_fwd_relu(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"),
                                 _ptr(w, (dd.K, dd.C, dd.R, dd.S), "w"), _ptr(bias, (dd.K,), "bias"),
                                 _ptr(y, (dd.N, dd.K, P, Q), "y"), wptr, wbytes, int(algo),
@@ -198,7 +219,7 @@ def conv2d_fwd_relu(d, x, w, bias, y, ws=None, algo: int = ALGO_AUTO, stream=Non
 def conv2d_fwd_relu_pool2(d, x, w, bias, y_pooled, ws=None, stream=None) -> None:
     dd = _desc(d)
     P, Q = conv2d_output_dims(dd)
-    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, ALGO_WINOGRAD))
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, ALGO_WINOGRAD), stream)
     rc = load().conv2d_fwd_relu_pool2(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"),
                                       _ptr(w, (dd.K, dd.C, dd.R, dd.S), "w"), _ptr(bias, (dd.K,), "bias"),
                                       _ptr(y_pooled, (dd.N, dd.K, P // 2, Q // 2), "y_pooled"), wptr, wbytes,
@@ -221,7 +242,7 @@ def conv2d_fwd_1x1_group(d, x, ws_list, bias_list, ys, ws=None, stream=None) -> 
     barr = None
     if bias_list is not None:
         barr = (C.c_void_p * n)(*[_ptr(b, (k,), "bias[%d]" % i) or None for i, (b, k) in enumerate(zip(bias_list, Ks))])
-    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, ALGO_IGEMM))
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_FWD, ALGO_IGEMM), stream)
     rc = load().conv2d_fwd_1x1_group(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"), n, karr, warr,
                                      barr, yarr, wptr, wbytes, _stream(stream))
     if rc:
@@ -231,7 +252,7 @@ def conv2d_fwd_1x1_group(d, x, ws_list, bias_list, ys, ws=None, stream=None) -> 
 def conv2d_bwd_data(d, dy, w, dx, ws=None, algo: int = ALGO_AUTO, stream=None) -> None:
     dd = _desc(d)
     P, Q = conv2d_output_dims(dd)
-    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_BWD_DATA, algo))
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_BWD_DATA, algo), stream)
     rc = load().conv2d_bwd_data(C.byref(dd), _ptr(dy, (dd.N, dd.K, P, Q), "dy"),
                                 _ptr(w, (dd.K, dd.C, dd.R, dd.S), "w"),
                                 _ptr(dx, (dd.N, dd.C, dd.H, dd.W), "dx"), wptr, wbytes, int(algo),
@@ -244,7 +265,7 @@ def conv2d_bwd_weight(d, x, dy, dw, dbias=None, scale: float = 1.0, accumulate: 
                       ws=None, algo: int = ALGO_AUTO, stream=None) -> None:
     dd = _desc(d)
     P, Q = conv2d_output_dims(dd)
-    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_BWD_WEIGHT, algo))
+    wsb, wptr, wbytes = _ws(ws, conv2d_workspace_bytes(dd, OP_BWD_WEIGHT, algo), stream)
     rc = load().conv2d_bwd_weight(C.byref(dd), _ptr(x, (dd.N, dd.C, dd.H, dd.W), "x"),
                                   _ptr(dy, (dd.N, dd.K, P, Q), "dy"),
                                   _ptr(dw, (dd.K, dd.C, dd.R, dd.S), "dw"),
@@ -262,3 +283,43 @@ def apply_mul_add(x, y, a: float, b: float, stream=None) -> None:
     rc = load().apply_mul_add(_ptr(x, None, "x"), _ptr(y, None, "y"), n, float(a), float(b), _stream(stream))
     if rc:
         raise Conv2dError(rc, "apply_mul_add")
+
+
+# ---- measurement helpers ---------------------------------------------------
+def conv2d_profile_begin(capacity: int) -> None:
+    rc = load().conv2d_profile_begin(int(capacity))
+    if rc:
+        raise Conv2dError(rc, "conv2d_profile_begin")
+
+
+def conv2d_profile_end() -> int:
+    return int(load().conv2d_profile_end())
+
+
+def conv2d_profile_record(i: int):
+    """(kernel id, flops, bytes, ms) of recorded launch i; the streams must be synchronised."""
+    k, fl, by, ms = C.c_int32(), C.c_double(), C.c_double(), C.c_float()
+    rc = load().conv2d_profile_record(int(i), C.byref(k), C.byref(fl), C.byref(by), C.byref(ms))
+    if rc:
+        raise Conv2dError(rc, "conv2d_profile_record")
+    return k.value, fl.value, by.value, ms.value
+
+
+def conv2d_profile_kernel_name(kernel: int) -> str:
+    return load().conv2d_profile_kernel_name(int(kernel)).decode()
+
+
+def conv2d_probe_mfma_f32(sink, iters: int, stream=None) -> float:
+    """Enqueues the pure-MFMA probe; returns the flops it executes."""
+    fl = C.c_double()
+    rc = load().conv2d_probe_mfma_f32(_ptr(sink, None, "sink"), int(iters), C.byref(fl), _stream(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_probe_mfma_f32")
+    return fl.value
+
+
+def conv2d_probe_copy(src, dst, stream=None) -> None:
+    """16-byte-vector copy of src to dst (equal sizes), or a fill of dst when src is None."""
+    rc = load().conv2d_probe_copy(_ptr(src, None, "src"), _ptr(dst, None, "dst"), dst.numel(), _stream(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_probe_copy")

@@ -361,6 +361,9 @@ WinoWgradPlan plan_wino_wgrad(const Geom &g)
 
 int launch_status(hipError_t e) { return e == hipSuccess ? CONV2D_OK : CONV2D_ERR_LAUNCH; }
 
+// the workspace contract: present, large enough, 256-byte aligned
+bool ws_ok(const void *ws, size_t ws_bytes, size_t need) { return ws && ws_bytes >= need && ((uintptr_t)ws & 255) == 0; }
+
 // ---- Winograd F(4x4,3x3), unfused (wino4.hip) --------------------------------
 struct W4Plan {
     bool ok;
@@ -431,7 +434,7 @@ int run_wino4(const Geom &g, conv2d_op op, const float *in, const float *w, cons
 {
     const W4Plan p = plan_wino4(g, op);
     if (!p.ok) return CONV2D_ERR_ALGO;
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     W4Args a = {};
     a.in = in; a.w = w; a.bias = bias; a.out = out; a.relu = relu;
     a.U = (float *)ws;
@@ -501,7 +504,7 @@ int run_wino4_wgrad(const Geom &g, const float *x, const float *dy, float *dw, f
 {
     const W4WgradPlan p = plan_wino4_wgrad(g);
     if (!p.ok) return CONV2D_ERR_ALGO;
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     W4WgradArgs a = {};
     a.x = x; a.dy = dy; a.dw = dw; a.db = dbias;
     a.Wm = (float *)ws;
@@ -518,6 +521,15 @@ int run_wino4_wgrad(const Geom &g, const float *x, const float *dy, float *dw, f
     a.div_THW = make_fastdiv((uint32_t)(p.TH * p.TW));
     a.div_TW = make_fastdiv((uint32_t)p.TW);
     return launch_status(launch_wino4_wgrad(a, s));
+}
+
+// the gather kernel's launch, timed when profiling is on (`share`: this launch's part of the pass)
+int run_gemmconv(const GemmConvArgs &a, int tile, int nphases, const Geom &g, double share, hipStream_t s)
+{
+    const double flops = 2.0 * g.N * (double)g.K * g.P * g.Q * g.C * g.R * g.S * share;
+    const double bytes = 4.0 * ((double)g.N * g.C * g.H * g.W + (double)g.N * g.K * g.P * g.Q + (double)g.K * g.C * g.R * g.S) * share;
+    const ProfScope ps(KID_GEMMCONV, flops, bytes, s);
+    return launch_status(launch_gemmconv(a, tile, nphases, s));
 }
 
 bool s2d_applicable(const Geom &g, conv2d_op op);     // strided layer as a stride-1 3x3 layer, below
@@ -793,7 +805,7 @@ int run_wino(const Geom &g, conv2d_op op, const float *in, const float *w, const
              float *out, void *ws, size_t ws_bytes, hipStream_t s, int relu = 0, int pool = 0)
 {
     const WinoPlan p = plan_wino(g, op);
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     float *U = (float *)ws;
     int rc = launch_status(launch_wino_filter(w, U, g.K, g.C, g.R, g.S, p.Cin, p.Kout, p.Cpad, p.Kpad,
                                               op == CONV2D_FWD ? 0 : 1, p.mode != 0, s));
@@ -826,7 +838,7 @@ int run_wino_wgrad(const Geom &g, const float *x, const float *dy, float *dw, fl
                    int acc_w, int acc_b, void *ws, size_t ws_bytes, hipStream_t s)
 {
     const WinoWgradPlan p = plan_wino_wgrad(g);
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     float *part = (float *)ws;
     float *bias_part = (float *)((char *)ws + p.part_bytes);
     WinoWgradArgs a = {};
@@ -913,7 +925,7 @@ int run_s2d(const Geom &g, conv2d_op op, const float *in, const float *w, const 
 {
     const S2dPlan p = plan_s2d(g, op);
     if (!p.ok) return CONV2D_ERR_ALGO;
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     float *x2 = (float *)ws;
     float *w2 = (float *)((char *)ws + p.x2_bytes);
     void *inner = (char *)ws + p.x2_bytes + p.w2_bytes;
@@ -939,7 +951,7 @@ int run_s2d_wgrad(const Geom &g, const float *x, const float *dy, float *dw, flo
 {
     const S2dPlan p = plan_s2d(g, CONV2D_BWD_WEIGHT);
     if (!p.ok) return CONV2D_ERR_ALGO;
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     float *x2 = (float *)ws;
     float *dw2 = (float *)((char *)ws + p.x2_bytes + p.w2_bytes);
     void *inner = (char *)ws + p.x2_bytes + p.w2_bytes + p.dw2_bytes;
@@ -1019,7 +1031,7 @@ static int fwd_impl(const conv2d_desc *d, const float *x, const float *w, const 
                                               : run_s2d(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
 
     const GatherPlan p = plan_fwd(g);
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     if (pw_stream_ok(g, CONV2D_FWD)) {
         PwArgs pa = {};
         fill_pw_args(pa, g, CONV2D_FWD, x);
@@ -1064,7 +1076,7 @@ static int fwd_impl(const conv2d_desc *d, const float *x, const float *w, const 
         a.pw_depth = g.C;
         a.in_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
     }
-    return launch_status(launch_gemmconv(a, p.tile, 1, s));
+    return run_gemmconv(a, p.tile, 1, g, 1.0, s);
 }
 
 int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float *bias, float *y,
@@ -1138,7 +1150,7 @@ int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, c
     hipStream_t s = (hipStream_t)hip_stream;
 
     const GatherPlan p = plan_fwd(g);
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     if (pw_stream_ok(g, CONV2D_FWD)) {
         PwArgs sa = {};
         fill_pw_args(sa, g, CONV2D_FWD, x);
@@ -1201,7 +1213,7 @@ int conv2d_fwd_1x1_group(const conv2d_desc *d, const float *x, int32_t ngroup, c
         a.pw_depth = g.C;
         a.in_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
     }
-    return launch_status(launch_gemmconv(a, p.tile, 1, s));
+    return run_gemmconv(a, p.tile, 1, g, 1.0, s);
 }
 
 int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float *dx, void *ws,
@@ -1228,7 +1240,7 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
                    : run_s2d(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
 
     const GatherPlan p = plan_bwd_data(g);
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     if (pw_stream_ok(g, CONV2D_BWD_DATA)) {
         PwArgs pa = {};
         fill_pw_args(pa, g, CONV2D_BWD_DATA, dy);
@@ -1277,7 +1289,7 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
         a.phase[0].in_base_h = 0; a.phase[0].in_base_w = 0;
         a.phase[0].out_base_h = 0; a.phase[0].out_base_w = 0;
         a.phase[0].Hs = Hs; a.phase[0].Ws = Ws;
-        return launch_status(launch_gemmconv(a, p.tile, 1, s));
+        return run_gemmconv(a, p.tile, 1, g, 1.0, s);
     }
 
     // phases are prepared and launched in groups of at most kMaxPhases
@@ -1316,7 +1328,7 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
             a.pw_depth = g.K;
             a.in_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
         }
-        rc = launch_status(launch_gemmconv(a, p.tile, cnt, s));
+        rc = run_gemmconv(a, p.tile, cnt, g, (double)cnt / p.nphases, s);
         if (rc) return rc;
         row_cursor += group_rows;
     }
@@ -1344,7 +1356,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
 
     const PwWgradPlan pw = plan_pw_wgrad(g);
     if (pw.ok && (((uintptr_t)x | (uintptr_t)dy) & 15) == 0) {
-        if (!ws || ws_bytes < pw.total_bytes) return CONV2D_ERR_WORKSPACE;
+        if (!ws_ok(ws, ws_bytes, pw.total_bytes)) return CONV2D_ERR_WORKSPACE;
         float *part = (float *)ws;
         float *bias_part = (float *)((char *)ws + pw.part_bytes);
         PwWgradArgs a = {};
@@ -1363,7 +1375,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
 
     const PwWgradPlan tw = plan_tap_wgrad(g);
     if (tw.ok && ((uintptr_t)dy & 15) == 0) {
-        if (!ws || ws_bytes < tw.total_bytes) return CONV2D_ERR_WORKSPACE;
+        if (!ws_ok(ws, ws_bytes, tw.total_bytes)) return CONV2D_ERR_WORKSPACE;
         float *part = (float *)ws;
         float *bias_part = (float *)((char *)ws + tw.part_bytes);
         const int taps = g.C * g.R * g.S, PQ = g.P * g.Q;
@@ -1386,7 +1398,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     }
 
     const WgradPlan p = plan_wgrad(g);
-    if (!ws || ws_bytes < p.total_bytes) return CONV2D_ERR_WORKSPACE;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
     float *part = (float *)ws;
     float *bias_part = (float *)((char *)ws + p.part_bytes);
 

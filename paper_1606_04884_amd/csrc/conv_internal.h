@@ -360,6 +360,26 @@ hipError_t launch_filter_d2s(const float *dw2, float *dw, int K, int C, int R, i
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Opt-in kernel timing (see prof.hip): a ProfScope around the launch of a main kernel
+// records a start and a stop event on the launch stream while conv2d_profile_begin is in
+// effect, with the algorithmic flops and minimal bytes of the launch; otherwise it does
+// nothing.
+enum KernelId {
+    KID_WINO4_GEMM = 0, KID_WINO4_INPUT, KID_WINO4_OUTPUT, KID_WINO4_WG_INPUT, KID_WINO4_WG_DY,
+    KID_WINO_PAIR, KID_WINO_FUSED, KID_WINO_WGRAD_VEC, KID_WINO_WGRAD, KID_GEMMCONV, KID_WGRAD,
+    KID_PW_STREAM, KID_PW_WGRAD, KID_SMALLC, KID_TAP_STREAM, KID_TAP_WGRAD, KID_COUNT
+};
+class ProfScope {
+public:
+    ProfScope(int kernel, double flops, double bytes, hipStream_t s);
+    ~ProfScope();
+    ProfScope(const ProfScope &) = delete;
+    ProfScope &operator=(const ProfScope &) = delete;
+private:
+    int slot_;
+    hipStream_t stream_;
+};
+
 // Per-element operation y = fl(fl(a*x) + b) over n floats (see apply.hip).
 hipError_t launch_apply_mul_add(const float *x, float *y, int64_t n, float a, float b, hipStream_t s);
 

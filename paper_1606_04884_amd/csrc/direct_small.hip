@@ -109,6 +109,8 @@ hipError_t launch_bwd_data_smallc(const SmallCArgs &a, hipStream_t s)
 {
     const int64_t total = (int64_t)a.N * a.H * (a.W >> 2);
     const dim3 grid((unsigned)((total + 255) / 256));
+    const ProfScope ps(KID_SMALLC, 18.0 * a.N * (double)a.K * a.P * a.Q * a.C,
+                       (double)a.dy_bytes + 4.0 * a.N * (double)a.C * a.H * a.W, s);
     switch (a.C) {
     case 1: hipLaunchKernelGGL(bwd_data_smallc_kernel<1>, grid, dim3(256), 0, s, a); break;
     case 2: hipLaunchKernelGGL(bwd_data_smallc_kernel<2>, grid, dim3(256), 0, s, a); break;

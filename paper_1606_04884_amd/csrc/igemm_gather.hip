@@ -12,7 +12,7 @@
 //   * the filter matrix is pre-transposed to [depth][Kpad] so its tiles are
 //     plain 16-byte row reads;
 //   * bias (and, on request, the ReLU that follows the layer) is applied in the epilogue
-//     before the only store ("fully fused").
+//     before the only store (the fused epilogue of Sec. 4.2 "Neon").
 // 256 threads = 4 waves; LDS tiles are double buffered, one barrier per step.
 
 #include "conv_internal.h"

@@ -296,6 +296,8 @@ int wgrad_col_tile(int tile) { return kWColTile[tile]; }
 hipError_t launch_wgrad(const WgradArgs &a, int tile, hipStream_t s)
 {
     const dim3 grid((unsigned)(a.tiles_k * a.tiles_j * a.splits));
+    const ProfScope ps(KID_WGRAD, 2.0 * a.M * (double)a.K * a.CRS,
+                       4.0 * ((double)a.N * a.C * a.H * a.W + (double)a.M * a.K + (double)a.K * a.CRS), s);
     switch (tile) {
     case 0:
         hipLaunchKernelGGL((wgrad_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, a);

@@ -20,6 +20,8 @@
 
 #include "conv_internal.h"
 
+#include <mutex>
+
 namespace mi355conv {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -487,13 +489,15 @@ __global__ __launch_bounds__(kPwThreads) void pw_stream_kernel(PwArgs a)
 template <int MI, bool GROUPED, bool TAPS = false, int RING = kPwRing>
 static hipError_t launch_pw_stream_t(const PwArgs &a, size_t lds_bytes, int grid, hipStream_t s)
 {
-    static size_t configured = 0;
-    if (lds_bytes > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_stream_kernel<MI, GROUPED, TAPS, RING>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwLdsMax);
-        if (e != hipSuccess) return e;
-        configured = kPwLdsMax;
-    }
+    static std::once_flag once;
+    static hipError_t cfg = hipSuccess;
+    std::call_once(once, [] {
+        cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_stream_kernel<MI, GROUPED, TAPS, RING>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwLdsMax);
+    });
+    if (cfg != hipSuccess) return cfg;
+    const ProfScope ps(TAPS ? KID_TAP_STREAM : KID_PW_STREAM, 2.0 * a.M * (double)a.D * a.Rout,
+                       (double)a.in_bytes + 4.0 * a.M * (double)a.Rout + 4.0 * a.D * (double)a.Rout, s);
     hipLaunchKernelGGL((pw_stream_kernel<MI, GROUPED, TAPS, RING>), dim3((unsigned)grid), dim3(kPwThreads), lds_bytes, s, a);
     return hipGetLastError();
 }
@@ -826,13 +830,15 @@ void pw_wgrad_shape(int C, int K, int HW, int *NJ, int *BT, int *PH)
 template <int AT, int BT, bool TAPS = false>
 static hipError_t launch_pw_wgrad_t(const PwWgradArgs &a, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s)
 {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_wgrad_kernel<AT, BT, TAPS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwWgradLdsMax);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::once_flag once;
+    static hipError_t cfg = hipSuccess;
+    std::call_once(once, [] {
+        cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(pw_wgrad_kernel<AT, BT, TAPS>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwWgradLdsMax);
+    });
+    if (cfg != hipSuccess) return cfg;
+    const ProfScope ps(TAPS ? KID_TAP_WGRAD : KID_PW_WGRAD, 2.0 * a.N * (double)a.HW * a.C * a.K,
+                       (double)a.x_bytes + (double)a.dy_bytes + 4.0 * a.K * (double)a.C, s);
     hipLaunchKernelGGL((pw_wgrad_kernel<AT, BT, TAPS>), grid, block, lds_bytes, s, a);
     return hipGetLastError();
 }

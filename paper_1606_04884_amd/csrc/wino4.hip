@@ -606,8 +606,16 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(wino4_input_kernel, dim3((unsigned)((a.Tpad + 255) / 256), (unsigned)(a.chunks * 2)), dim3(256), 0, s, a);
-    hipError_t e = hipGetLastError();
+    const double in_b = (double)a.in_bytes, out_b = 4.0 * a.N * (double)a.Kout * a.Hout * a.Wout;
+    const double v_b = 4.0 * 36.0 * a.chunks * 8 * (double)a.Tpad, m_b = 4.0 * 36.0 * a.Kpad * (double)a.Tpad;
+    const double u_b = 4.0 * 36.0 * a.chunks * 8 * (double)a.Kpad;
+    const double gemm_flops = 72.0 * a.T * (double)a.Cin * a.Kout;
+    hipError_t e;
+    {
+        const ProfScope ps(KID_WINO4_INPUT, 0.0, in_b + v_b, s);
+        hipLaunchKernelGGL(wino4_input_kernel, dim3((unsigned)((a.Tpad + 255) / 256), (unsigned)(a.chunks * 2)), dim3(256), 0, s, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
     W4GemmArgs g = {};
     g.A = a.U; g.B = a.V; g.C = a.M;
@@ -619,6 +627,7 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
     const int full = a.split > 1 ? tiles - a.split_tiles : tiles;
     if (full > 0) {
         g.tile_base = 0; g.nsplit = 1;
+        const ProfScope ps(KID_WINO4_GEMM, gemm_flops * full / tiles, (u_b + v_b + m_b) * full / tiles, s);
         if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3((unsigned)full), dim3(256), 0, s, g);
         else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3((unsigned)full), dim3(256), 0, s, g);
         e = hipGetLastError();
@@ -629,9 +638,12 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
     if (full < tiles) {
         g.tile_base = full; g.nsplit = a.split; g.slots = a.slots;
         const unsigned grid = (unsigned)((tiles - full) * a.split);
-        if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
-        e = hipGetLastError();
+        {
+            const ProfScope ps(KID_WINO4_GEMM, gemm_flops * (tiles - full) / tiles, (u_b + v_b + m_b) * (tiles - full) / tiles, s);
+            if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
+            else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+            e = hipGetLastError();
+        }
         if (e != hipSuccess) return e;
         if (a.tile_cfg == 0)
             hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), dim3((unsigned)(tiles - full), 8), dim3(256), 0, s, g);
@@ -640,19 +652,28 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    const ProfScope ps(KID_WINO4_OUTPUT, 0.0, m_b + out_b, s);
     hipLaunchKernelGGL(wino4_output_kernel, dim3((unsigned)((a.T + 255) / 256), (unsigned)a.Kout), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s)
 {
-    const dim3 gx((unsigned)((a.Cpad + 31) / 32), (unsigned)a.chunks);
-    hipLaunchKernelGGL(wino4_wg_input_kernel, gx, dim3(256), 0, s, a);
-    hipError_t e = hipGetLastError();
+    const double vm_b = 4.0 * 36.0 * a.chunks * 8 * (double)a.Cpad, wm_b = 4.0 * 36.0 * a.chunks * 8 * (double)a.Kpad;
+    hipError_t e;
+    {
+        const ProfScope ps(KID_WINO4_WG_INPUT, 0.0, (double)a.x_bytes + vm_b, s);
+        const dim3 gx((unsigned)((a.Cpad + 31) / 32), (unsigned)a.chunks);
+        hipLaunchKernelGGL(wino4_wg_input_kernel, gx, dim3(256), 0, s, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
-    const dim3 gy((unsigned)((a.Kpad + 31) / 32), (unsigned)a.chunks);
-    hipLaunchKernelGGL(wino4_wg_dy_kernel, gy, dim3(256), 0, s, a);
-    e = hipGetLastError();
+    {
+        const ProfScope ps(KID_WINO4_WG_DY, 0.0, (double)a.dy_bytes + wm_b, s);
+        const dim3 gy((unsigned)((a.Kpad + 31) / 32), (unsigned)a.chunks);
+        hipLaunchKernelGGL(wino4_wg_dy_kernel, gy, dim3(256), 0, s, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
     W4GemmArgs g = {};
     g.A = a.Wm; g.B = a.Vm; g.C = a.D; g.slots = a.slots;
@@ -661,9 +682,13 @@ hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s)
     g.tiles_n = a.Cpad / wino4_tile_n(a.tile_cfg);
     g.tile_base = 0; g.nsplit = a.split;                // >= 2: every share goes to its slot
     const unsigned grid = (unsigned)(36 * g.tiles_m * g.tiles_n * a.split);
-    if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
-    e = hipGetLastError();
+    {
+        const double slot_b = 4.0 * grid * (double)wino4_tile_m(a.tile_cfg) * wino4_tile_n(a.tile_cfg);
+        const ProfScope ps(KID_WINO4_GEMM, 72.0 * a.T * (double)a.C * a.K, vm_b + wm_b + slot_b, s);
+        if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
     // the depth shares of every tile added in order into D, then the filter transform
     const dim3 gf((unsigned)(36 * g.tiles_m * g.tiles_n), 8);

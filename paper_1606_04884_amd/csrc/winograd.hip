@@ -2,8 +2,8 @@
 // backward-data of 3x3 stride-1 layers, fused into one kernel per call.
 //
 // Sec. 4.2 "Winograd" of the paper: minimal filtering cuts the multiplications
-// of a 3x3 convolution by 2.25 but "still relies on GEMM"; Sec. 4.2 "Neon" adds
-// that the fast implementations fuse the transforms into that GEMM.  The paper
+// of a 3x3 convolution by 2.25 while the bulk of the work remains matrix products;
+// Sec. 4.2 "Neon": the fast implementations fuse the transforms into those products.  The paper
 // prints no transform matrices; the standard ones for the points {0,1,-1,inf}
 // are used:
 //   B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1]     (input tile d, 4x4)
@@ -26,6 +26,8 @@
 // LDS-only barrier hidden under the last position pair.
 
 #include "conv_internal.h"
+
+#include <mutex>
 
 namespace mi355conv {
 
@@ -1026,29 +1028,33 @@ int wino_partial_slot_floats() { return kWinoKB * kWinoTB * 4; }
 template <bool VEC>
 static hipError_t launch_wino_variant(const WinoArgs &a, int G, hipStream_t s)
 {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel<VEC>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWinoLdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::once_flag once;
+    static hipError_t cfg = hipSuccess;
+    std::call_once(once, [] {
+        cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_fused_kernel<VEC>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWinoLdsBytes);
+    });
+    if (cfg != hipSuccess) return cfg;
+    const ProfScope ps(KID_WINO_FUSED, 32.0 * a.T * (double)a.Cin * a.nsub * a.Kout,
+                       (double)a.in_bytes + 4.0 * a.N * (double)a.Kout * a.Hout * a.Wout + 36.0 * a.Cin * (double)a.nsub * a.Kout, s);
     hipLaunchKernelGGL((wino_fused_kernel<VEC>), dim3((unsigned)G), dim3(256), kWinoLdsBytes, s, a);
     return hipGetLastError();
 }
 
 static hipError_t launch_wino_pair(const WinoArgs &a, int G, hipStream_t s)
 {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_ragged_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::once_flag once;
+    static hipError_t cfg = hipSuccess;
+    std::call_once(once, [] {
+        cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
+        if (cfg == hipSuccess)
+            cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_pair_ragged_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kWinoPairLdsBytes);
+    });
+    if (cfg != hipSuccess) return cfg;
+    const ProfScope ps(KID_WINO_PAIR, 32.0 * a.T * (double)a.Cin * a.Kout,
+                       (double)a.in_bytes + 4.0 * a.N * (double)a.Kout * a.Hout * a.Wout + 36.0 * a.Cin * (double)a.Kout, s);
     if (a.Cin % kWinoCB != 0)
         hipLaunchKernelGGL(wino_pair_ragged_kernel, dim3((unsigned)G), dim3(512), kWinoPairLdsBytes, s, a);
     else

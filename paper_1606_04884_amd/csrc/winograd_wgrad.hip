@@ -20,6 +20,8 @@
 
 #include "conv_internal.h"
 
+#include <mutex>
+
 namespace mi355conv {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -627,20 +629,22 @@ int wino_wgrad_step() { return kWwTS; }
 
 hipError_t launch_wino_wgrad(const WinoWgradArgs &a, hipStream_t s)
 {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWwLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_vec_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kWvLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_vec_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kWvLdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::once_flag once;
+    static hipError_t cfg = hipSuccess;
+    std::call_once(once, [] {
+        cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWwLdsBytes);
+        if (cfg == hipSuccess)
+            cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_vec_kernel<false>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kWvLdsBytes);
+        if (cfg == hipSuccess)
+            cfg = hipFuncSetAttribute(reinterpret_cast<const void *>(wino_wgrad_vec_kernel<true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kWvLdsBytes);
+    });
+    if (cfg != hipSuccess) return cfg;
     const dim3 grid((unsigned)(a.tiles_k * a.tiles_c * a.splits));
+    const ProfScope ps(a.mode == 0 ? KID_WINO_WGRAD : KID_WINO_WGRAD_VEC, 32.0 * a.T * (double)a.C * a.K * a.nsub,
+                       (double)a.x_bytes + (double)a.dy_bytes + 36.0 * a.K * (double)a.C * a.nsub, s);
     if (a.mode == 0)
         hipLaunchKernelGGL(wino_wgrad_kernel, grid, dim3(256), kWwLdsBytes, s, a);
     else if (a.mode == 1)

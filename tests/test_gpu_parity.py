@@ -273,6 +273,11 @@ def test_grouped_1x1_forward(case):
         got = ys[i].cpu().numpy()
         assert np.isfinite(got).all()
         assert max_err_ratio(got, ref) <= TOL_IGEMM, "group %d" % i
+        # the header's claim: the same summation order as the group's own conv2d_fwd call
+        y1 = torch.full((N, k, H, W), float("nan"), device=dev)
+        B.conv2d_fwd(g1, tx, tws[i], tbs[i], y1, algo=B.ALGO_IGEMM)
+        torch.cuda.synchronize()
+        assert torch.equal(ys[i], y1), "group %d differs from the single-layer call" % i
 
 
 WINO_LARGE_FILTER_SHAPES = [
