@@ -78,16 +78,59 @@ def kernel_stats(stats_csv: str, bench_line: str, workload: str, out_dir: str) -
         fh.write("\nbench.py line of the same run:\n%s\n" % bench_line.strip())
 
 
+def mfma_util(counter_csv: str, workload: str, out_dir: str) -> None:
+    """profiles/mfma_util_<workload>.txt from one counter run with SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_MFMA
+    SQ_INSTS_VALU SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE (and others, ignored) collected together."""
+    import collections
+    per = collections.defaultdict(lambda: collections.defaultdict(float))
+    launches = collections.Counter()
+    seen = set()
+    with open(counter_csv, newline="") as fh:
+        for row in csv.DictReader(fh):
+            name = short_name(row["Kernel_Name"])
+            if not name:
+                continue
+            per[name][row["Counter_Name"]] += float(row["Counter_Value"])
+            if row["Dispatch_Id"] not in seen:
+                seen.add(row["Dispatch_Id"])
+                launches[name] += 1
+    with open(os.path.join(out_dir, "mfma_util_%s.txt" % workload), "w") as fh:
+        fh.write("MFMA utilisation per kernel, %s workload, %s (rocprofv3 counters, two passes of the stack)\n" % (
+            workload, time.strftime("%Y-%m-%d")))
+        fh.write("command: rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_MFMA SQ_BUSY_CYCLES SQ_INSTS_VALU "
+                 "SQ_ACTIVE_INST_VALU SQ_WAIT_INST_ANY SQ_WAVE_CYCLES GRBM_GUI_ACTIVE --output-format csv -d out -o u -- "
+                 "python3 bench.py --workload %s --steps 1 --warmup 0 --no-cpu-baseline --no-calib\n" % workload)
+        fh.write("summarised by: python -m paper_1606_04884_amd.profsum --util <out>/u_counter_collection.csv\n\n")
+        fh.write("util = SQ_VALU_MFMA_BUSY_CYCLES / (cycles x 256 compute units x 4 SIMDs), cycles = GRBM_GUI_ACTIVE / 8 (the\n"
+                 "counter comes back summed over the 8 XCDs); SQ_VALU_MFMA_BUSY_CYCLES is 64 per v_mfma_f32_32x32x2_f32, so util\n"
+                 "is the share of the fp32 matrix pipe's cycles the kernel's MFMAs fill at the clock it actually ran at.\n"
+                 "INSTS_VALU counts the MFMAs too: (INSTS_VALU - INSTS_MFMA) / INSTS_MFMA = other vector instructions per MFMA.\n\n")
+        fh.write("%-28s %8s %12s %12s %12s %7s %12s %14s\n" % ("kernel", "launches", "GUI_ACTIVE", "MFMA_BUSY", "INSTS_MFMA",
+                                                              "util %", "INSTS_VALU", "other per MFMA"))
+        for name, c in sorted(per.items(), key=lambda kv: -kv[1]["GRBM_GUI_ACTIVE"]):
+            cyc = c["GRBM_GUI_ACTIVE"] / 8.0
+            util = 100.0 * c["SQ_VALU_MFMA_BUSY_CYCLES"] / (cyc * 256 * 4) if cyc else 0.0
+            other = (c["SQ_INSTS_VALU"] - c["SQ_INSTS_MFMA"]) / c["SQ_INSTS_MFMA"] if c["SQ_INSTS_MFMA"] else float("nan")
+            fh.write("%-28s %8d %12.4g %12.4g %12.4g %7.1f %12.4g %14.2f\n" % (
+                name, launches[name], c["GRBM_GUI_ACTIVE"], c["SQ_VALU_MFMA_BUSY_CYCLES"], c["SQ_INSTS_MFMA"], util,
+                c["SQ_INSTS_VALU"], other))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--stats", help="s_kernel_stats.csv of a --kernel-trace --stats run: write kernel_stats_<workload>.txt")
     ap.add_argument("--bench-line", help="file holding the JSON line that run printed")
+    ap.add_argument("--util", help="counter_collection.csv of an MFMA-utilisation counter run: write mfma_util_<workload>.txt")
     ap.add_argument("--fetch")
     ap.add_argument("--write")
     ap.add_argument("--workload", required=True)
     ap.add_argument("--calib-mib", type=int, default=1024)
     ap.add_argument("--out-dir", default="profiles")
     args = ap.parse_args()
+    if args.util:
+        os.makedirs(args.out_dir, exist_ok=True)
+        mfma_util(args.util, args.workload, args.out_dir)
+        return 0
     if args.stats:
         line = open(args.bench_line).read() if args.bench_line else ""
         os.makedirs(args.out_dir, exist_ok=True)
