@@ -54,7 +54,7 @@ def executed_flops(L, P, Q, op, algo):
     if algo == 3:
         # F(4x4,3x3): 36 GEMMs, 2*36*K*C per 4x4 tile of the pass's output
         th, tw = (-(-L.H // 4), -(-L.W // 4)) if op == "bwd_data" else (-(-P // 4), -(-Q // 4))
-        return 72.0 * L.N * th * tw * L.K * L.C
+        return 72.0 * L.N * th * tw * L.K * L.C * (-(-L.R // 3) * -(-L.S // 3))
     if algo != 2:
         return layer_flops(L, P, Q)
     if L.stride > 1:

@@ -367,7 +367,7 @@ bool ws_ok(const void *ws, size_t ws_bytes, size_t need) { return ws && ws_bytes
 // ---- Winograd F(4x4,3x3), unfused (wino4.hip) --------------------------------
 struct W4Plan {
     bool ok;
-    int Cin, Kout, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, Tpad, Kpad, chunks, cfg, split, split_tiles;
+    int Cin, Kout, Hin, Win, Hout, Wout, pad_h, pad_w, TH, TW, T, Tpad, Kpad, chunks, csub, nsub, cfg, split, split_tiles;
     size_t u_bytes, v_bytes, m_bytes, slot_bytes, total_bytes;
 };
 
@@ -375,25 +375,27 @@ W4Plan plan_wino4(const Geom &g, conv2d_op op)
 {
     W4Plan p = {};
     if (op == CONV2D_BWD_WEIGHT) return p;
-    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph > 2 || g.pw > 2) return p;
+    if (g.R < 3 || g.S < 3 || g.R > 6 || g.S > 6 || g.sh != 1 || g.sw != 1 || g.ph > g.R - 1 || g.pw > g.S - 1) return p;
     const bool fwd = op == CONV2D_FWD;
+    p.nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);
     p.Cin = fwd ? g.C : g.K;
     p.Kout = fwd ? g.K : g.C;
     p.Hin = fwd ? g.H : g.P;
     p.Win = fwd ? g.W : g.Q;
     p.Hout = fwd ? g.P : g.H;
     p.Wout = fwd ? g.Q : g.W;
-    p.pad_h = fwd ? g.ph : 2 - g.ph;
-    p.pad_w = fwd ? g.pw : 2 - g.pw;
+    p.pad_h = fwd ? g.ph : g.R - 1 - g.ph;
+    p.pad_w = fwd ? g.pw : g.S - 1 - g.pw;
     p.TH = ceil_div(p.Hout, 4);
     p.TW = ceil_div(p.Wout, 4);
     const int64_t T = (int64_t)g.N * p.TH * p.TW;
     if (T > (int64_t(1) << 24) || p.Kout > 65535) return p;
     p.T = (int)T;
-    p.chunks = ceil_div(p.Cin, 8);
+    p.csub = ceil_div(p.Cin, 8);
+    p.chunks = p.nsub * p.csub;
     // the workgroup tile that pads the product least (ties: the wider column tile)
     int64_t best = -1;
-    for (int cfg = 0; cfg < 2; ++cfg) {
+    for (int cfg = 0; cfg < 3; ++cfg) {
         const int64_t cost = (int64_t)round_up(p.Kout, wino4_tile_m(cfg)) * round_up(p.T, wino4_tile_n(cfg));
         if (best < 0 || cost < best) { best = cost; p.cfg = cfg; }
     }
@@ -447,6 +449,7 @@ int run_wino4(const Geom &g, conv2d_op op, const float *in, const float *w, cons
     a.N = g.N; a.Cin = p.Cin; a.Hin = p.Hin; a.Win = p.Win; a.Kout = p.Kout; a.Kpad = p.Kpad;
     a.Hout = p.Hout; a.Wout = p.Wout; a.pad_h = p.pad_h; a.pad_w = p.pad_w;
     a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.Tpad = p.Tpad; a.chunks = p.chunks;
+    a.R = g.R; a.S = g.S; a.csub = p.csub; a.nsw = ceil_div(g.S, 3);
     a.in_bytes = (int32_t)((int64_t)g.N * p.Cin * p.Hin * p.Win * 4);
     a.tile_cfg = p.cfg;
     return launch_status(launch_wino4(a, s));
@@ -454,14 +457,15 @@ int run_wino4(const Geom &g, conv2d_op op, const float *in, const float *w, cons
 
 struct W4WgradPlan {
     bool ok;
-    int TH, TW, T, chunks, Kpad, Cpad, cfg, split, tiles;
+    int TH, TW, T, chunks, Kpad, Cpad, cfg, split, tiles, nsub;
     size_t wm_bytes, vm_bytes, slot_bytes, d_bytes, bias_bytes, total_bytes;
 };
 
 W4WgradPlan plan_wino4_wgrad(const Geom &g)
 {
     W4WgradPlan p = {};
-    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph > 2 || g.pw > 2) return p;
+    if (g.R < 3 || g.S < 3 || g.R > 6 || g.S > 6 || g.sh != 1 || g.sw != 1 || g.ph > g.R - 1 || g.pw > g.S - 1) return p;
+    p.nsub = ceil_div(g.R, 3) * ceil_div(g.S, 3);
     if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31) || (int64_t)g.N * g.K * g.P * g.Q * 4 >= (int64_t(1) << 31))
         return p;
     p.TH = ceil_div(g.P, 4);
@@ -471,12 +475,12 @@ W4WgradPlan plan_wino4_wgrad(const Geom &g)
     p.T = (int)T;
     p.chunks = ceil_div(p.T, 8);
     int64_t best = -1;
-    for (int cfg = 0; cfg < 2; ++cfg) {
-        const int64_t cost = (int64_t)round_up(g.K, wino4_tile_m(cfg)) * round_up(g.C, wino4_tile_n(cfg));
+    for (int cfg = 0; cfg < 3; ++cfg) {
+        const int64_t cost = (int64_t)round_up(g.K, wino4_tile_m(cfg)) * round_up(p.nsub * g.C, wino4_tile_n(cfg));
         if (best < 0 || cost < best) { best = cost; p.cfg = cfg; }
     }
     p.Kpad = round_up(g.K, wino4_tile_m(p.cfg));
-    p.Cpad = round_up(g.C, wino4_tile_n(p.cfg));
+    p.Cpad = round_up(p.nsub * g.C, wino4_tile_n(p.cfg));
     if ((int64_t)p.chunks * 2 * p.Kpad * 16 >= (int64_t(1) << 31) || (int64_t)p.chunks * 2 * p.Cpad * 16 >= (int64_t(1) << 31))
         return p;
     p.tiles = 36 * (p.Kpad / wino4_tile_m(p.cfg)) * (p.Cpad / wino4_tile_n(p.cfg));
@@ -515,6 +519,7 @@ int run_wino4_wgrad(const Geom &g, const float *x, const float *dy, float *dw, f
     a.scale = scale; a.accumulate = accumulate;
     a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q; a.pad_h = g.ph; a.pad_w = g.pw;
     a.TH = p.TH; a.TW = p.TW; a.T = p.T; a.chunks = p.chunks; a.Kpad = p.Kpad; a.Cpad = p.Cpad;
+    a.R = g.R; a.S = g.S; a.nsub = p.nsub; a.nsw = ceil_div(g.S, 3);
     a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
     a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
     a.tile_cfg = p.cfg; a.split = p.split;
@@ -559,15 +564,17 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
             // the partial products written and read once, ~40 us of small launches) beats the
             // fused F(3x3,2x2) kernels' (~108 TFLOP/s executed with vector loads, ~85 without)
             const W4WgradPlan w4 = plan_wino4_wgrad(g);
-            if (w4.ok && g.R == 3 && g.S == 3 && g.C >= 64 && g.K >= 64) {
+            if (w4.ok && g.C >= 64 && g.K >= 64) {
                 const WinoWgradPlan f2 = plan_wino_wgrad(g);
-                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K / (f2.mode != 0 ? 108e12 : 85e12);
+                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K * f2.nsub / (f2.mode != 0 ? 108e12 : 80e12);
                 const double tile_b = 4.0 * wino4_tile_m(w4.cfg) * wino4_tile_n(w4.cfg);
-                const double bytes = 4.0 * ((double)g.N * g.C * g.H * g.W + (double)g.N * g.K * g.P * g.Q) +
-                                     4.0 * 36.0 * w4.chunks * 8 * ((double)w4.Kpad + w4.Cpad) +
-                                     2.0 * w4.tiles * (double)w4.split * tile_b;
+                const double x_b = 4.0 * g.N * (double)g.C * g.H * g.W, dy_b = 4.0 * g.N * (double)g.K * g.P * g.Q;
+                const double vm_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Cpad, wm_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Kpad;
                 const double eff = (double)w4.tiles * w4.split / (512.0 * ceil_div(w4.tiles * w4.split, 512));
-                const double t_w4 = 72.0 * w4.chunks * 8.0 * w4.Kpad * w4.Cpad / (130e12 * eff) + bytes / 4.0e12 + 40e-6;
+                double t_gemm = 72.0 * w4.chunks * 8.0 * w4.Kpad * w4.Cpad / (130e12 * eff);
+                if (t_gemm < (vm_b + wm_b) / 3.5e12) t_gemm = (vm_b + wm_b) / 3.5e12;      // operands streamed from HBM
+                const double t_w4 = t_gemm + (x_b + vm_b) / 3.6e12 + (dy_b + wm_b) / 4.4e12 +
+                                    2.0 * w4.tiles * (double)w4.split * tile_b / 5e12 + 40e-6;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
             return CONV2D_ALGO_WINOGRAD;
@@ -594,16 +601,19 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         if (wino_ok && cin >= 32 && pays) {
             // 3x3 with many channels on a small map: the unfused F(4x4,3x3) path when its
             // estimate beats the fused F(2x2,3x3) kernels' (measured rates on this chip:
-            // 36 GEMMs at ~125 TFLOP/s, transforms at ~4.5 TB/s over input + V and M + output,
+            // 36 GEMMs at ~125 TFLOP/s unless streaming V and M at 3.5 TB/s takes longer, input
+            // transform at 3.5 TB/s over input + V, output transform at 4.5 TB/s over M + output,
             // ~25 us of small launches; fused: ~105 TFLOP/s executed for the tile-pair kernel,
-            // ~80 for the one-tile-per-lane kernel)
+            // ~82 for the one-tile-per-lane kernel)
             const W4Plan w4 = plan_wino4(g, op);
             if (w4.ok && cin >= 64) {
                 const WinoPlan f2 = plan_wino(g, op);
-                const double t_f2 = 32.0 * f2.T * f2.Cin * (double)f2.Kpad / (f2.mode != 0 ? 105e12 : 80e12);
-                const double bytes = 4.0 * ((double)g.N * w4.Cin * w4.Hin * w4.Win + 36.0 * w4.chunks * 8 * w4.Tpad +
-                                            36.0 * w4.Kpad * w4.Tpad + (double)g.N * w4.Kout * w4.Hout * w4.Wout);
-                const double t_w4 = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / 125e12 + bytes / 4.5e12 + 25e-6;
+                const double t_f2 = 32.0 * f2.T * f2.Cin * (double)f2.nsub * f2.Kpad / (f2.mode != 0 ? 105e12 : 82e12);
+                const double in_b = 4.0 * g.N * (double)w4.Cin * w4.Hin * w4.Win, out_b = 4.0 * g.N * (double)w4.Kout * w4.Hout * w4.Wout;
+                const double v_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Tpad, m_b = 4.0 * 36.0 * w4.Kpad * (double)w4.Tpad;
+                double t_gemm = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / 125e12;
+                if (t_gemm < (v_b + m_b) / 3.5e12) t_gemm = (v_b + m_b) / 3.5e12;          // operands streamed from HBM
+                const double t_w4 = t_gemm + (in_b + v_b) / 3.5e12 + (m_b + out_b) / 4.5e12 + 25e-6;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
             return CONV2D_ALGO_WINOGRAD;

@@ -215,7 +215,9 @@ struct W4Args {
     int32_t C;                 // channel count of w (its second axis)
     int32_t N, Cin, Hin, Win, Kout, Kpad, Hout, Wout, pad_h, pad_w;
     int32_t TH, TW, T, Tpad;   // 4x4 output tiles per image (rows, cols), in total, padded to the GEMM tile
-    int32_t chunks;            // 8-channel chunks of the reduction (Cin rounded up)
+    int32_t chunks;            // 8-channel chunks of the reduction: nsub * csub
+    int32_t R, S;              // filter size (3..6); nsub = ceil(R/3)*ceil(S/3) sub-filters of 3x3
+    int32_t csub, nsw;         // chunks per sub-filter (Cin rounded up to 8); sub-filters per filter row
     int32_t in_bytes;          // size of `in` (below 2^31)
     int32_t tile_cfg;          // workgroup tile of the GEMM, see wino4_tile_m / _n
 };
@@ -231,8 +233,9 @@ struct W4WgradArgs {
     float scale;
     int32_t accumulate;
     int32_t N, C, H, W, K, P, Q, pad_h, pad_w;
+    int32_t R, S, nsub, nsw;   // filter size (3..6), its 3x3 sub-filters, sub-filters per filter row
     int32_t TH, TW, T, chunks; // 4x4 output tiles per image (rows, cols), in total; 8-tile chunks of the depth
-    int32_t Kpad, Cpad;        // rows of the two operands, multiples of the GEMM tile
+    int32_t Kpad, Cpad;        // rows of the two operands (Cpad: nsub * C rows q*C + c), multiples of the GEMM tile
     int32_t x_bytes, dy_bytes; // both below 2^31
     int32_t tile_cfg, split;
     FastDiv div_THW, div_TW;

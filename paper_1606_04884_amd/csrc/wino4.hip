@@ -38,39 +38,42 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ filters
-// U[pos][chunk][half][ko][j]: reduction channel ci = 8*chunk + 2*j + half, output channel
-// ko < Kpad; zero where ci >= Cin or ko >= Kout.  mode 0: g = w[ko][ci]; mode 1
-// (backward-data: the layer mapping dy to dx): g = w[ci][ko] rotated by 180 degrees.
+// U[pos][chunk][half][ko][j]: output channel ko < Kpad, reduction channel
+// ci = 8*(chunk % csub) + 2*j + half of sub-filter q = chunk / csub (csub = chunks per
+// sub-filter); zero where ci >= Cin or ko >= Kout.  A filter larger than 3x3 is the sum of
+// its 3x3 sub-filters q = (a, b), taps (3a + r, 3b + s), zero where the R x S filter ends,
+// applied to the input shifted by (3a, 3b); R = S = 3: one sub-filter, the filter itself.
+// mode 0: g = w[ko][ci]; mode 1 (backward-data: the layer mapping dy to dx): g = w[ci][ko]
+// rotated by 180 degrees.
 __global__ __launch_bounds__(256) void wino4_filter_kernel(const float *__restrict__ w, float *__restrict__ U,
-                                                           int C, int Cin, int Kout, int chunks, int Kpad, int mode)
+                                                           int C, int Cin, int Kout, int chunks, int Kpad, int mode,
+                                                           int R, int S, int csub)
 {
+    const int nsw = (S + 2) / 3, RS = R * S;
     const int64_t nvec = (int64_t)chunks * 2 * Kpad;           // 16-byte vectors per position
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * blockDim.x) {
         const int ko = (int)(v % Kpad);
         const int ch = (int)(v / Kpad);                         // chunk * 2 + half
         floatx4 u[36];
+        const int q = (ch >> 1) / csub, cchunk = (ch >> 1) - q * csub;
+        const int r0 = 3 * (q / nsw), s0 = 3 * (q - (q / nsw) * nsw);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int ci = (ch >> 1) * 8 + (ch & 1) + 2 * j;
+            const int ci = cchunk * 8 + (ch & 1) + 2 * j;
             float g[3][3];
 #pragma unroll
             for (int r = 0; r < 3; ++r)
 #pragma unroll
                 for (int s = 0; s < 3; ++s) g[r][s] = 0.f;
             if (ci < Cin && ko < Kout) {
-                if (mode == 0) {
-                    const float *p = w + ((int64_t)ko * C + ci) * 9;
+                const float *p = mode == 0 ? w + ((int64_t)ko * C + ci) * RS : w + ((int64_t)ci * C + ko) * RS;
 #pragma unroll
-                    for (int r = 0; r < 3; ++r)
+                for (int r = 0; r < 3; ++r)
 #pragma unroll
-                        for (int s = 0; s < 3; ++s) g[r][s] = p[r * 3 + s];
-                } else {
-                    const float *p = w + ((int64_t)ci * C + ko) * 9;
-#pragma unroll
-                    for (int r = 0; r < 3; ++r)
-#pragma unroll
-                        for (int s = 0; s < 3; ++s) g[r][s] = p[(2 - r) * 3 + (2 - s)];
-                }
+                    for (int s = 0; s < 3; ++s) {
+                        const int rr = r0 + r, ss = s0 + s;
+                        if (rr < R && ss < S) g[r][s] = mode == 0 ? p[rr * S + ss] : p[(R - 1 - rr) * S + (S - 1 - ss)];
+                    }
             }
             float t[6][3];
 #pragma unroll
@@ -116,7 +119,8 @@ __device__ __forceinline__ void w4_bt(const float d0, const float d1, const floa
 
 // ------------------------------------------------------------------- input
 // V[pos][chunk][half][t][j], t < Tpad (tiles past T are written as zeros), channel
-// ci = 8*chunk + 2*j + half.  A thread owns one tile and the four channels of one
+// ci = 8*(chunk % csub) + 2*j + half of sub-filter chunk / csub, whose patches are shifted
+// by three pixels per sub-filter row / column.  A thread owns one tile and the four channels of one
 // (chunk, half): it fetches their 6x6 patches (origin 4*tile - pad; elements outside the
 // image carry an offset beyond the buffer, for which the buffer load returns 0),
 // transforms them and stores each position as one 16-byte vector; the 64 lanes of a wave
@@ -131,7 +135,9 @@ __global__ __launch_bounds__(256) void wino4_input_kernel(W4Args a)
     const int THW = a.TH * a.TW;
     const int n = tl / THW, rem = tl - n * THW;
     const int th = rem / a.TW, tw = rem - th * a.TW;
-    const int ih0 = 4 * th - a.pad_h, iw0 = 4 * tw - a.pad_w;
+    // (chunk -> sub-filter q and its chunk of real channels; the block is uniform in both)
+    const int q = (ch >> 1) / a.csub, cchunk = (ch >> 1) - q * a.csub;
+    const int ih0 = 4 * th - a.pad_h + 3 * (q / a.nsw), iw0 = 4 * tw - a.pad_w + 3 * (q % a.nsw);
     const int HW = a.Hin * a.Win;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
     uint32_t rowoff[6];
@@ -145,7 +151,7 @@ __global__ __launch_bounds__(256) void wino4_input_kernel(W4Args a)
     floatx4 v[36];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int ci = (ch >> 1) * 8 + (ch & 1) + 2 * j;
+        const int ci = cchunk * 8 + (ch & 1) + 2 * j;
         const uint32_t cbad = ci < a.Cin ? 0u : 0x80000000u;
         const int so = (ci < a.Cin ? ci : 0) * HW * 4;
         float d[6][6];
@@ -422,18 +428,19 @@ __global__ __launch_bounds__(256) void wino4_wg_input_kernel(W4WgradArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 3, h = (lane >> 2) & 1;
-    const int c = blockIdx.x * 32 + wave * 8 + (lane >> 3);
+    const int c = blockIdx.x * 32 + wave * 8 + (lane >> 3);       // row: sub-filter q, channel cr
     const int tc = blockIdx.y;
     if (c >= a.Cpad) return;
+    const int q = c / a.C, cr = c - q * a.C;
     const int t = tc * 8 + 2 * j + h;
-    const bool tv = t < a.T && c < a.C;
+    const bool tv = t < a.T && q < a.nsub;
     const int tl = t < a.T ? t : 0;
     const int HW = a.H * a.W;
     const int n = (int)fast_div((uint32_t)tl, a.div_THW), rem = tl - n * (a.TH * a.TW);
     const int th = (int)fast_div((uint32_t)rem, a.div_TW), tw = rem - th * a.TW;
-    const int ih0 = 4 * th - a.pad_h, iw0 = 4 * tw - a.pad_w;
+    const int ih0 = 4 * th - a.pad_h + 3 * (q / a.nsw), iw0 = 4 * tw - a.pad_w + 3 * (q % a.nsw);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
-    const int cl = c < a.C ? c : 0;
+    const int cl = q < a.nsub ? cr : 0;
     uint32_t colbad = 0;
 #pragma unroll
     for (int i = 0; i < 6; ++i)
@@ -535,13 +542,14 @@ __device__ __forceinline__ void w4_gt(const float m0, const float m1, const floa
     o[2] = (1.f / 6.f) * (s34 - s12) + m5;
 }
 
-// dw[k][c] = scale * G^T D[.][k][c] G (+ dw[k][c]) from the reduced products D[pos][Kpad][Cpad];
-// a thread takes one filter and four consecutive channels (lanes along c).
+// dw[k][c] = scale * G^T D[.][k][c'] G (+ dw[k][c]) from the reduced products D[pos][Kpad][Cpad];
+// a thread takes one filter and four consecutive rows c' = q*C + c (lanes along c'); the 3x3
+// block of sub-filter q = (a, b) lands on taps (3a.., 3b..) of the R x S gradient.
 __global__ __launch_bounds__(256) void wino4_wg_output_kernel(W4WgradArgs a)
 {
     const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
     const int k = blockIdx.y;
-    if (c0 >= a.C) return;
+    if (c0 >= a.nsub * a.C) return;
     const int64_t pos_stride = (int64_t)a.Kpad * a.Cpad;
     const float *p = a.D + (int64_t)k * a.Cpad + c0;
     floatx4 m[6][6];
@@ -549,7 +557,9 @@ __global__ __launch_bounds__(256) void wino4_wg_output_kernel(W4WgradArgs a)
     for (int pos = 0; pos < 36; ++pos) m[pos / 6][pos % 6] = *reinterpret_cast<const floatx4 *>(p + pos * pos_stride);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        if (c0 + e >= a.C) break;
+        if (c0 + e >= a.nsub * a.C) break;
+        const int q = (c0 + e) / a.C, cr = (c0 + e) - q * a.C;
+        const int r0 = 3 * (q / a.nsw), s0 = 3 * (q % a.nsw);
         float tc[3][6];
 #pragma unroll
         for (int j = 0; j < 6; ++j) {
@@ -558,15 +568,18 @@ __global__ __launch_bounds__(256) void wino4_wg_output_kernel(W4WgradArgs a)
 #pragma unroll
             for (int i = 0; i < 3; ++i) tc[i][j] = o[i];
         }
-        float *dst = a.dw + ((int64_t)k * a.C + c0 + e) * 9;
+        float *dst = a.dw + ((int64_t)k * a.C + cr) * (a.R * a.S);
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
             float o[3];
             w4_gt(tc[i][0], tc[i][1], tc[i][2], tc[i][3], tc[i][4], tc[i][5], o);
 #pragma unroll
             for (int j = 0; j < 3; ++j) {
-                const float g = a.scale * o[j];
-                dst[3 * i + j] = a.accumulate ? dst[3 * i + j] + g : g;
+                if (r0 + i < a.R && s0 + j < a.S) {
+                    float *d1 = dst + (r0 + i) * a.S + s0 + j;
+                    const float g = a.scale * o[j];
+                    *d1 = a.accumulate ? *d1 + g : g;
+                }
             }
         }
     }
@@ -593,8 +606,23 @@ __global__ __launch_bounds__(256) void wino4_wg_bias_kernel(W4WgradArgs a)
 }
 
 // ---------------------------------------------------------------- launchers
-int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : 256; }     // 2 x 2 or 4 x 1 wave tiles of 64 x 128
-int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : 128; }
+// workgroup tile: 2 x 2, 4 x 1 or 1 x 4 wave tiles of 64 rows x 128 columns
+int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : cfg == 1 ? 256 : 64; }
+int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : cfg == 1 ? 128 : 512; }
+
+static void launch_w4_gemm(const W4GemmArgs &g, int cfg, unsigned grid, hipStream_t s)
+{
+    if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
+    else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((wino4_gemm_kernel<1, 4>), dim3(grid), dim3(256), 0, s, g);
+}
+
+static void launch_w4_fixup(const W4GemmArgs &g, int cfg, unsigned tiles, hipStream_t s)
+{
+    if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), dim3(tiles, 8), dim3(256), 0, s, g);
+    else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128>), dim3(tiles, 8), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<64, 512>), dim3(tiles, 8), dim3(256), 0, s, g);
+}
 
 hipError_t launch_wino4(const W4Args &a, hipStream_t s)
 {
@@ -602,14 +630,14 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
         int64_t blocks = ((int64_t)a.chunks * 2 * a.Kpad + 255) / 256;
         if (blocks > 8192) blocks = 8192;
         hipLaunchKernelGGL(wino4_filter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a.w, a.U, a.C, a.Cin, a.Kout,
-                           a.chunks, a.Kpad, a.mode);
+                           a.chunks, a.Kpad, a.mode, a.R, a.S, a.csub);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     const double in_b = (double)a.in_bytes, out_b = 4.0 * a.N * (double)a.Kout * a.Hout * a.Wout;
     const double v_b = 4.0 * 36.0 * a.chunks * 8 * (double)a.Tpad, m_b = 4.0 * 36.0 * a.Kpad * (double)a.Tpad;
     const double u_b = 4.0 * 36.0 * a.chunks * 8 * (double)a.Kpad;
-    const double gemm_flops = 72.0 * a.T * (double)a.Cin * a.Kout;
+    const double gemm_flops = 72.0 * a.T * (double)a.Cin * a.Kout * (a.chunks / a.csub);
     hipError_t e;
     {
         const ProfScope ps(KID_WINO4_INPUT, 0.0, in_b + v_b, s);
@@ -628,8 +656,7 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
     if (full > 0) {
         g.tile_base = 0; g.nsplit = 1;
         const ProfScope ps(KID_WINO4_GEMM, gemm_flops * full / tiles, (u_b + v_b + m_b) * full / tiles, s);
-        if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3((unsigned)full), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3((unsigned)full), dim3(256), 0, s, g);
+        launch_w4_gemm(g, a.tile_cfg, (unsigned)full, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -640,15 +667,11 @@ hipError_t launch_wino4(const W4Args &a, hipStream_t s)
         const unsigned grid = (unsigned)((tiles - full) * a.split);
         {
             const ProfScope ps(KID_WINO4_GEMM, gemm_flops * (tiles - full) / tiles, (u_b + v_b + m_b) * (tiles - full) / tiles, s);
-            if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
-            else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+            launch_w4_gemm(g, a.tile_cfg, grid, s);
             e = hipGetLastError();
         }
         if (e != hipSuccess) return e;
-        if (a.tile_cfg == 0)
-            hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), dim3((unsigned)(tiles - full), 8), dim3(256), 0, s, g);
-        else
-            hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128>), dim3((unsigned)(tiles - full), 8), dim3(256), 0, s, g);
+        launch_w4_fixup(g, a.tile_cfg, (unsigned)(tiles - full), s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -684,19 +707,16 @@ hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s)
     const unsigned grid = (unsigned)(36 * g.tiles_m * g.tiles_n * a.split);
     {
         const double slot_b = 4.0 * grid * (double)wino4_tile_m(a.tile_cfg) * wino4_tile_n(a.tile_cfg);
-        const ProfScope ps(KID_WINO4_GEMM, 72.0 * a.T * (double)a.C * a.K, vm_b + wm_b + slot_b, s);
-        if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
+        const ProfScope ps(KID_WINO4_GEMM, 72.0 * a.T * (double)a.C * a.K * a.nsub, vm_b + wm_b + slot_b, s);
+        launch_w4_gemm(g, a.tile_cfg, grid, s);
         e = hipGetLastError();
     }
     if (e != hipSuccess) return e;
     // the depth shares of every tile added in order into D, then the filter transform
-    const dim3 gf((unsigned)(36 * g.tiles_m * g.tiles_n), 8);
-    if (a.tile_cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), gf, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128>), gf, dim3(256), 0, s, g);
+    launch_w4_fixup(g, a.tile_cfg, (unsigned)(36 * g.tiles_m * g.tiles_n), s);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 go((unsigned)((a.C + 1023) / 1024), (unsigned)a.K);
+    const dim3 go((unsigned)((a.nsub * a.C + 1023) / 1024), (unsigned)a.K);
     hipLaunchKernelGGL(wino4_wg_output_kernel, go, dim3(256), 0, s, a);
     e = hipGetLastError();
     if (e != hipSuccess || !a.db) return e;

@@ -25,6 +25,15 @@ SHAPES = [
     (1, 136, 6, 5, 64, 3, 3, 1, 1, 1, 1),         # map smaller than two tiles
     (32, 64, 32, 32, 256, 3, 3, 1, 1, 1, 1),      # 576 GEMM tiles for 512 resident workgroups: the last 64 in 8 depth shares
     (36, 40, 30, 30, 200, 3, 3, 1, 1, 1, 1),      # 648 tiles, the last 136 in 3 unequal shares of 5 chunks
+    (32, 16, 32, 32, 192, 3, 3, 1, 1, 1, 1),      # 192 filters: the 64-row x 512-column workgroup tile
+    # filters beyond 3x3 as sums of 3x3 sub-filters of shifted inputs
+    (2, 16, 12, 12, 24, 5, 5, 1, 1, 2, 2),
+    (3, 8, 9, 11, 16, 5, 5, 1, 1, 0, 0),
+    (2, 24, 13, 10, 40, 5, 5, 1, 1, 4, 1),
+    (2, 8, 9, 9, 8, 4, 4, 1, 1, 1, 2),
+    (2, 12, 10, 12, 16, 6, 6, 1, 1, 3, 2),
+    (2, 16, 8, 9, 8, 3, 5, 1, 1, 1, 2),
+    (4, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2),       # AlexNet conv2 at a small batch
 ]
 
 
@@ -49,6 +58,12 @@ WG_SHAPES = [
     (2, 24, 7, 10, 72, 3, 3, 1, 1, 2, 2),
     (2, 3, 12, 12, 8, 3, 3, 1, 1, 1, 0),
     (37, 48, 12, 12, 136, 3, 3, 1, 1, 1, 1),      # 333 tiles: last chunk ragged, unequal depth shares
+    (4, 512, 12, 12, 192, 3, 3, 1, 1, 1, 1),      # 192 filters x 512 channels: the 64 x 512 workgroup tile
+    (2, 16, 12, 12, 24, 5, 5, 1, 1, 2, 2),        # sub-filter gradients scattered into the 5x5 gradient
+    (5, 8, 9, 11, 16, 5, 5, 1, 1, 0, 0),
+    (2, 24, 13, 10, 40, 5, 4, 1, 1, 4, 1),
+    (2, 12, 10, 12, 16, 6, 6, 1, 1, 3, 2),
+    (4, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2),
 ]
 
 
@@ -100,7 +115,7 @@ def test_wino4_relu_and_no_bias():
 
 
 def test_wino4_refuses_what_it_cannot_do():
-    for geom, op in (((2, 8, 16, 16, 8, 5, 5, 1, 1, 2, 2), B.OP_FWD),
+    for geom, op in (((2, 8, 16, 16, 8, 7, 7, 1, 1, 3, 3), B.OP_FWD),
                      ((2, 8, 16, 16, 8, 3, 3, 2, 2, 1, 1), B.OP_FWD),
                      ((1, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1), B.OP_BWD_WEIGHT)):        # 4 tiles: too few to split
         assert B.conv2d_workspace_bytes(geom, op, B.ALGO_WINOGRAD4) == 0

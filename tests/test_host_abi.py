@@ -149,10 +149,13 @@ def test_algo_choice_rules():
     assert pick((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # odd width: no pairs
     assert pick((64, 3, 224, 224, 16, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # few filters
     assert B.conv2d_workspace_bytes((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD, B.ALGO_WINOGRAD) == 0
-    five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5: four 3x3 sub-filters
-    assert pick(five, B.OP_FWD) == B.ALGO_WINOGRAD
-    assert pick(five, B.OP_BWD_DATA) == B.ALGO_WINOGRAD
-    assert pick(five, B.OP_BWD_WEIGHT) == B.ALGO_WINOGRAD
+    five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5: four 3x3 sub-filters, fused or unfused
+    for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+        assert pick(five, op) in (B.ALGO_WINOGRAD, B.ALGO_WINOGRAD4)
+        assert B.conv2d_workspace_bytes(five, op, B.ALGO_WINOGRAD) > 0
+        assert B.conv2d_workspace_bytes(five, op, B.ALGO_WINOGRAD4) > 0
+    small5 = (128, 32, 27, 27, 64, 5, 5, 1, 1, 2, 2)           # few channels: the fused kernels
+    assert pick(small5, B.OP_FWD) == B.ALGO_WINOGRAD
     assert pick((8, 64, 20, 20, 64, 4, 4, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # 4x4: no saving
     assert pick((8, 64, 20, 20, 64, 7, 7, 1, 1, 3, 3), B.OP_FWD) == B.ALGO_IGEMM          # above 6x6
     assert pick((8, 64, 56, 56, 64, 3, 3, 2, 2, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # stride 2
