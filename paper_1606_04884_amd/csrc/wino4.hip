@@ -117,6 +117,26 @@ __device__ __forceinline__ void w4_bt(const float d0, const float d1, const floa
     o[5] = 4.f * d1 - 5.f * d3 + d5;
 }
 
+// Six consecutive floats of a patch row as dword + 16 bytes + dword (buffer loads work at any
+// 4-byte-aligned offset and range-check every component on its own).  `off` is the byte
+// offset of the row's first element, or 0x80000000 for a row outside the image (all zeros);
+// bit jj of `colbad` marks a column outside the image row: the end dwords then carry an
+// out-of-range offset, the middle components are replaced by 0 (they may have read the
+// neighbouring row).  Needs pad_w <= 1, so that the 16 bytes start inside the row.
+__device__ __forceinline__ void w4_load_row6(const __amdgpu_buffer_rsrc_t rs, uint32_t off, int so, uint32_t colbad,
+                                             float (&d)[6])
+{
+    const uint32_t o0 = (colbad & 1u) ? 0x80000000u : off;
+    const uint32_t o5 = (colbad & 32u) ? 0x80000000u : off + 20u;
+    d[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, o0, so, 0));
+    const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs, off + 4u, so, 0));
+    d[5] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, o5, so, 0));
+    d[1] = (colbad & 2u) ? 0.f : m[0];
+    d[2] = (colbad & 4u) ? 0.f : m[1];
+    d[3] = (colbad & 8u) ? 0.f : m[2];
+    d[4] = (colbad & 16u) ? 0.f : m[3];
+}
+
 // ------------------------------------------------------------------- input
 // V[pos][chunk][half][t][j], t < Tpad (tiles past T are written as zeros), channel
 // ci = 8*(chunk % csub) + 2*j + half of sub-filter chunk / csub, whose patches are shifted
@@ -155,13 +175,18 @@ __global__ __launch_bounds__(256) void wino4_input_kernel(W4Args a)
         const uint32_t cbad = ci < a.Cin ? 0u : 0x80000000u;
         const int so = (ci < a.Cin ? ci : 0) * HW * 4;
         float d[6][6];
+        if (a.pad_w <= 1) {
 #pragma unroll
-        for (int i = 0; i < 6; ++i)
+            for (int i = 0; i < 6; ++i) w4_load_row6(rs, rowoff[i] | cbad, so, colbad, d[i]);
+        } else {
 #pragma unroll
-            for (int jj = 0; jj < 6; ++jj) {
-                const uint32_t off = ((colbad >> jj) & 1u) ? 0x80000000u : (rowoff[i] + 4u * jj);
-                d[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off | cbad, so, 0));
-            }
+            for (int i = 0; i < 6; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 6; ++jj) {
+                    const uint32_t off = ((colbad >> jj) & 1u) ? 0x80000000u : (rowoff[i] + 4u * jj);
+                    d[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off | cbad, so, 0));
+                }
+        }
         float tcol[6][6];       // B^T d: column pass
 #pragma unroll
         for (int jj = 0; jj < 6; ++jj) {
@@ -450,10 +475,14 @@ __global__ __launch_bounds__(256) void wino4_wg_input_kernel(W4WgradArgs a)
     for (int i = 0; i < 6; ++i) {
         const bool ok = tv && (unsigned)(ih0 + i) < (unsigned)a.H;
         const uint32_t rowoff = ok ? (uint32_t)(((n * a.C + cl) * HW + (ih0 + i) * a.W + iw0) * 4) : 0x80000000u;
+        if (a.pad_w <= 1) {
+            w4_load_row6(rs, rowoff, 0, colbad, d[i]);
+        } else {
 #pragma unroll
-        for (int jj = 0; jj < 6; ++jj) {
-            const uint32_t off = ((colbad >> jj) & 1u) ? 0x80000000u : (rowoff + 4u * jj);
-            d[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+            for (int jj = 0; jj < 6; ++jj) {
+                const uint32_t off = ((colbad >> jj) & 1u) ? 0x80000000u : (rowoff + 4u * jj);
+                d[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+            }
         }
     }
     float tcol[6][6];
@@ -464,14 +493,28 @@ __global__ __launch_bounds__(256) void wino4_wg_input_kernel(W4WgradArgs a)
 #pragma unroll
         for (int i = 0; i < 6; ++i) tcol[i][jj] = o[i];
     }
-    const int64_t pos_stride = (int64_t)a.chunks * 2 * a.Cpad * 4;
-    float *dst = a.Vm + ((int64_t)(tc * 2 + h) * a.Cpad + c) * 4 + j;
+    // The 36 results of a lane go through a wave-private LDS area [pos][lane] (the four j of a
+    // (row, half) are neighbouring lanes, i.e. 16 contiguous bytes) and leave as 16-byte
+    // vectors: lane (ps, v) stores positions 4*g + ps of vector v = (row, half), so a store
+    // instruction writes 8 runs of 128 bytes instead of 2 (dword stores held this kernel at
+    // 3.6 TB/s).  LDS operations of a wave execute in order: no barrier.
+    __shared__ float sm[4][36 * 64];
+    float *my = sm[wave];
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
         float o[6];
         w4_bt(tcol[i][0], tcol[i][1], tcol[i][2], tcol[i][3], tcol[i][4], tcol[i][5], o);
 #pragma unroll
-        for (int jj = 0; jj < 6; ++jj) dst[(6 * i + jj) * pos_stride] = o[jj];
+        for (int jj = 0; jj < 6; ++jj) my[(6 * i + jj) * 64 + lane] = o[jj];
+    }
+    const int64_t pos_stride = (int64_t)a.chunks * 2 * a.Cpad * 4;
+    const int ps = lane >> 4, v = lane & 15;
+    const int crow = blockIdx.x * 32 + wave * 8 + (v >> 1);
+    float *dst = a.Vm + ((int64_t)(tc * 2 + (v & 1)) * a.Cpad + crow) * 4;
+#pragma unroll
+    for (int g = 0; g < 9; ++g) {
+        const floatx4 val = *reinterpret_cast<const floatx4 *>(my + (4 * g + ps) * 64 + v * 4);
+        *reinterpret_cast<floatx4 *>(dst + (4 * g + ps) * pos_stride) = val;
     }
 }
 
@@ -499,11 +542,10 @@ __global__ __launch_bounds__(256) void wino4_wg_dy_kernel(W4WgradArgs a)
     for (int i = 0; i < 4; ++i) {
         const bool ok = tv && oh + i < a.P;
         const uint32_t rowoff = ok ? (uint32_t)(((n * a.K + kl) * PQ + (oh + i) * a.Q + ow) * 4) : 0x80000000u;
+        // (16 bytes at any 4-byte-aligned offset; components past the row end are dropped)
+        const floatx4 m = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs, rowoff, 0, 0));
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const uint32_t off = ow + jj < a.Q ? rowoff + 4u * jj : 0x80000000u;
-            y[i][jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
-        }
+        for (int jj = 0; jj < 4; ++jj) y[i][jj] = ow + jj < a.Q ? m[jj] : 0.f;
     }
     float tcol[6][4];
 #pragma unroll
