@@ -604,14 +604,18 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
             // 36 GEMMs at ~125 TFLOP/s unless streaming V and M at 3.5 TB/s takes longer, input
             // transform at 3.5 TB/s over input + V, output transform at 4.5 TB/s over M + output,
             // ~25 us of small launches; fused: ~105 TFLOP/s executed for the tile-pair kernel,
-            // ~82 for the one-tile-per-lane kernel)
+            // ~76 for the one-tile-per-lane kernel)
             const W4Plan w4 = plan_wino4(g, op);
             if (w4.ok && cin >= 64) {
                 const WinoPlan f2 = plan_wino(g, op);
-                const double t_f2 = 32.0 * f2.T * f2.Cin * (double)f2.nsub * f2.Kpad / (f2.mode != 0 ? 105e12 : 82e12);
+                const double t_f2 = 32.0 * f2.T * f2.Cin * (double)f2.nsub * f2.Kpad / (f2.mode != 0 ? 105e12 : 76e12);
                 const double in_b = 4.0 * g.N * (double)w4.Cin * w4.Hin * w4.Win, out_b = 4.0 * g.N * (double)w4.Kout * w4.Hout * w4.Wout;
                 const double v_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Tpad, m_b = 4.0 * 36.0 * w4.Kpad * (double)w4.Tpad;
-                double t_gemm = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / 125e12;
+                // (the GEMM runs in rounds of 512 workgroups: a small layer leaves most of a round empty)
+                const int64_t tiles = (int64_t)36 * (w4.Kpad / wino4_tile_m(w4.cfg)) * (w4.Tpad / wino4_tile_n(w4.cfg));
+                const int64_t pieces = tiles - w4.split_tiles + (int64_t)w4.split_tiles * w4.split;
+                const double fill = (double)pieces / (512.0 * (double)((pieces + 511) / 512));
+                double t_gemm = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / (135e12 * fill);
                 if (t_gemm < (v_b + m_b) / 3.5e12) t_gemm = (v_b + m_b) / 3.5e12;          // operands streamed from HBM
                 const double t_w4 = t_gemm + (in_b + v_b) / 3.5e12 + (m_b + out_b) / 4.5e12 + 25e-6;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
