@@ -560,20 +560,21 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         if (op == CONV2D_BWD_WEIGHT) {
             if (!(wino_ok && pays_f)) return CONV2D_ALGO_IGEMM;
             // many channels and filters on a small map: the unfused F(4x4,3x3) form when its
-            // estimate (36 GEMMs at ~130 TFLOP/s, transforms at ~4 TB/s over x + V and dy + W,
+            // estimate (36 GEMMs at ~130 TFLOP/s, transforms at 4.3 / 4.9 TB/s over x + V and dy + W,
             // the partial products written and read once, ~40 us of small launches) beats the
-            // fused F(3x3,2x2) kernels' (~108 TFLOP/s executed with vector loads, ~85 without)
+            // fused F(3x3,2x2) kernels' (~108 TFLOP/s executed with vector loads, ~88 on odd tile rows,
+            // ~80 with per-element loads)
             const W4WgradPlan w4 = plan_wino4_wgrad(g);
             if (w4.ok && g.C >= 64 && g.K >= 64) {
                 const WinoWgradPlan f2 = plan_wino_wgrad(g);
-                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K * f2.nsub / (f2.mode != 0 ? 108e12 : 80e12);
+                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K * f2.nsub / (f2.mode == 1 ? 108e12 : f2.mode == 2 ? 88e12 : 80e12);
                 const double tile_b = 4.0 * wino4_tile_m(w4.cfg) * wino4_tile_n(w4.cfg);
                 const double x_b = 4.0 * g.N * (double)g.C * g.H * g.W, dy_b = 4.0 * g.N * (double)g.K * g.P * g.Q;
                 const double vm_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Cpad, wm_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Kpad;
                 const double eff = (double)w4.tiles * w4.split / (512.0 * ceil_div(w4.tiles * w4.split, 512));
                 double t_gemm = 72.0 * w4.chunks * 8.0 * w4.Kpad * w4.Cpad / (130e12 * eff);
                 if (t_gemm < (vm_b + wm_b) / 3.5e12) t_gemm = (vm_b + wm_b) / 3.5e12;      // operands streamed from HBM
-                const double t_w4 = t_gemm + (x_b + vm_b) / 3.6e12 + (dy_b + wm_b) / 4.4e12 +
+                const double t_w4 = t_gemm + (x_b + vm_b) / 4.3e12 + (dy_b + wm_b) / 4.9e12 +
                                     2.0 * w4.tiles * (double)w4.split * tile_b / 5e12 + 40e-6;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
@@ -602,7 +603,8 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
             // 3x3 with many channels on a small map: the unfused F(4x4,3x3) path when its
             // estimate beats the fused F(2x2,3x3) kernels' (measured rates on this chip:
             // 36 GEMMs at ~125 TFLOP/s unless streaming V and M at 3.5 TB/s takes longer, input
-            // transform at 3.5 TB/s over input + V, output transform at 4.5 TB/s over M + output,
+            // transform at 4.8 TB/s over input + V (3.5 without the wide row loads), output transform
+            // at 4.5 TB/s over M + output,
             // ~25 us of small launches; fused: ~105 TFLOP/s executed for the tile-pair kernel,
             // ~76 for the one-tile-per-lane kernel)
             const W4Plan w4 = plan_wino4(g, op);
@@ -617,7 +619,7 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
                 const double fill = (double)pieces / (512.0 * (double)((pieces + 511) / 512));
                 double t_gemm = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / (135e12 * fill);
                 if (t_gemm < (v_b + m_b) / 3.5e12) t_gemm = (v_b + m_b) / 3.5e12;          // operands streamed from HBM
-                const double t_w4 = t_gemm + (in_b + v_b) / 3.5e12 + (m_b + out_b) / 4.5e12 + 25e-6;
+                const double t_w4 = t_gemm + (in_b + v_b) / (w4.pad_w <= 1 ? 4.8e12 : 3.5e12) + (m_b + out_b) / 4.5e12 + 25e-6;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
             return CONV2D_ALGO_WINOGRAD;
