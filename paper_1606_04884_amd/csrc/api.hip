@@ -560,22 +560,23 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
         if (op == CONV2D_BWD_WEIGHT) {
             if (!(wino_ok && pays_f)) return CONV2D_ALGO_IGEMM;
             // many channels and filters on a small map: the unfused F(4x4,3x3) form when its
-            // estimate (36 GEMMs at ~130 TFLOP/s, transforms at 4.3 / 4.9 TB/s over x + V and dy + W,
-            // the partial products written and read once, ~40 us of small launches) beats the
-            // fused F(3x3,2x2) kernels' (~108 TFLOP/s executed with vector loads, ~88 on odd tile rows,
-            // ~80 with per-element loads)
+            // estimate (36 GEMMs at ~140 TFLOP/s, the last round of workgroups charged half of what it
+            // leaves empty, transforms at 4.3 / 4.9 TB/s over x + V and dy + W, the partial products
+            // written and read once, ~25 us of small launches; within 5% of the measured times of the
+            // VGG-16, AlexNet and Overfeat layers) beats the fused F(3x3,2x2) kernels' (~108 TFLOP/s
+            // executed with vector loads, ~88 on odd tile rows, ~73 with per-element loads)
             const W4WgradPlan w4 = plan_wino4_wgrad(g);
             if (w4.ok && g.C >= 64 && g.K >= 64) {
                 const WinoWgradPlan f2 = plan_wino_wgrad(g);
-                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K * f2.nsub / (f2.mode == 1 ? 108e12 : f2.mode == 2 ? 88e12 : 80e12);
+                const double t_f2 = 32.0 * f2.T * g.C * (double)g.K * f2.nsub / (f2.mode == 1 ? 108e12 : f2.mode == 2 ? 88e12 : 73e12);
                 const double tile_b = 4.0 * wino4_tile_m(w4.cfg) * wino4_tile_n(w4.cfg);
                 const double x_b = 4.0 * g.N * (double)g.C * g.H * g.W, dy_b = 4.0 * g.N * (double)g.K * g.P * g.Q;
                 const double vm_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Cpad, wm_b = 4.0 * 36.0 * w4.chunks * 8 * (double)w4.Kpad;
-                const double eff = (double)w4.tiles * w4.split / (512.0 * ceil_div(w4.tiles * w4.split, 512));
-                double t_gemm = 72.0 * w4.chunks * 8.0 * w4.Kpad * w4.Cpad / (130e12 * eff);
+                const double fill = (double)w4.tiles * w4.split / (512.0 * ceil_div(w4.tiles * w4.split, 512));
+                double t_gemm = 72.0 * w4.chunks * 8.0 * w4.Kpad * w4.Cpad / (140e12 * (0.5 + 0.5 * fill));
                 if (t_gemm < (vm_b + wm_b) / 3.5e12) t_gemm = (vm_b + wm_b) / 3.5e12;      // operands streamed from HBM
                 const double t_w4 = t_gemm + (x_b + vm_b) / 4.3e12 + (dy_b + wm_b) / 4.9e12 +
-                                    2.0 * w4.tiles * (double)w4.split * tile_b / 5e12 + 40e-6;
+                                    2.0 * w4.tiles * (double)w4.split * tile_b / 5e12 + 25e-6;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
             return CONV2D_ALGO_WINOGRAD;
