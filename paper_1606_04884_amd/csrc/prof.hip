@@ -71,15 +71,35 @@ __global__ __launch_bounds__(256, 2) void probe_mfma_kernel(float *sink, int ite
     if (r == 12345.678f) sink[0] = r;       // never true: keeps the accumulators live
 }
 
+// Copy / fill in the form that moved the most bytes in a sweep over grid sizes, loads in flight
+// and cache hints on this chip: a workgroup takes spans of 4 x 256 vectors, all four loads issued
+// before the first store, nontemporal hint on both sides (1 GiB: 6.0-6.2 TB/s read + write against
+// 4.5-5.7 for one vector per thread and step; fill 5.9-6.0 TB/s when a workgroup writes one span).
+// The vectors past the last whole span go one per thread.
 __global__ __launch_bounds__(256) void probe_copy_kernel(const floatx4 *__restrict__ src, floatx4 *__restrict__ dst, int64_t n4)
 {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+    const int64_t spans = n4 / 1024;
+    for (int64_t sp = blockIdx.x; sp < spans; sp += gridDim.x) {
+        const int64_t i = sp * 1024 + threadIdx.x;
+        const floatx4 v0 = __builtin_nontemporal_load(src + i), v1 = __builtin_nontemporal_load(src + i + 256);
+        const floatx4 v2 = __builtin_nontemporal_load(src + i + 512), v3 = __builtin_nontemporal_load(src + i + 768);
+        __builtin_nontemporal_store(v0, dst + i);
+        __builtin_nontemporal_store(v1, dst + i + 256);
+        __builtin_nontemporal_store(v2, dst + i + 512);
+        __builtin_nontemporal_store(v3, dst + i + 768);
+    }
+    for (int64_t i = spans * 1024 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
 }
 
 __global__ __launch_bounds__(256) void probe_fill_kernel(floatx4 *__restrict__ dst, int64_t n4, float v)
 {
     const floatx4 x = {v, v, v, v};
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = x;
+    const int64_t spans = n4 / 1024;
+    for (int64_t sp = blockIdx.x; sp < spans; sp += gridDim.x) {
+        const int64_t i = sp * 1024 + threadIdx.x;
+        dst[i] = x; dst[i + 256] = x; dst[i + 512] = x; dst[i + 768] = x;
+    }
+    for (int64_t i = spans * 1024 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = x;
 }
 
 }  // namespace mi355conv
@@ -142,7 +162,11 @@ int conv2d_probe_copy(const float *src, float *dst, int64_t n, void *hip_stream)
 {
     if (!dst) return CONV2D_ERR_NULL;
     if (n < 4 || (n & 3) != 0 || (((uintptr_t)src | (uintptr_t)dst) & 15) != 0) return CONV2D_ERR_GEOMETRY;
-    const int blocks = 256 * 8;
+    // grids the sweep found best: 16384 workgroups for the copy, one span per workgroup (up to
+    // 65536) for the fill; at least one workgroup for the tail loop
+    const int64_t spans = n / 4 / 1024;
+    const int64_t cap = src ? 16384 : 65536;
+    const int blocks = (int)(spans < 1 ? 1 : spans < cap ? spans : cap);
     if (src)
         hipLaunchKernelGGL(probe_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream,
                            reinterpret_cast<const floatx4 *>(src), reinterpret_cast<floatx4 *>(dst), n / 4);
