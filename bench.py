@@ -31,7 +31,8 @@ PEAK_HBM_GBS = 8000.0
 # kernels whose roofline is HBM bandwidth over their minimal bytes (streaming and transform
 # kernels); every other main kernel is a dense contraction on fp32 MFMA
 HBM_BOUND_KERNELS = {"pw_stream_kernel", "pw_wgrad_kernel", "bwd_data_smallc_kernel", "wino4_input_kernel",
-                     "wino4_output_kernel", "wino4_wg_input_kernel", "wino4_wg_dy_kernel"}
+                     "wino4_output_kernel", "wino4_wg_input_kernel", "wino4_wg_dy_kernel", "fft_filter_kernel",
+                     "fft_wg_output_kernel"}
 
 # main kernel of a call by (resolved algorithm, pass), for the call-level cross-check of the
 # roofline block (3x3 layers with even maps; other shapes take sibling kernels)
@@ -51,6 +52,9 @@ def executed_flops(L, P, Q, op, algo):
     direct count for the implicit GEMM; for Winograd F(2x2,3x3) the 16 GEMMs,
     2*16*K*C per 2x2 tile (tiles of the pass's output: y for fwd/bwd_weight, dx for
     bwd_data)."""
+    if algo == 4:
+        # product of spectra: one complex K x C x N product (8 real flops per term) per kept frequency
+        return 8.0 * 544 * L.K * L.C * L.N
     if algo == 3:
         # F(4x4,3x3): 36 GEMMs, 2*36*K*C per 4x4 tile of the pass's output
         th, tw = (-(-L.H // 4), -(-L.W // 4)) if op == "bwd_data" else (-(-P // 4), -(-Q // 4))
@@ -78,7 +82,7 @@ def main() -> int:
     ap.add_argument("--workload", default="vgg16", choices=sorted(WORKLOADS))
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--algo", type=int, default=0,
-                    help="0 auto, 1 implicit GEMM, 2 Winograd F(2x2,3x3) fused, 3 Winograd F(4x4,3x3) unfused; "
+                    help="0 auto, 1 implicit GEMM, 2 Winograd F(2x2,3x3) fused, 3 Winograd F(4x4,3x3) unfused, 4 product of spectra; "
                          "calls the algorithm cannot serve use auto")
     ap.add_argument("--detail", action="store_true", help="per-layer table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -239,7 +243,7 @@ def main() -> int:
                 tf = r["flops"] / (ms * 1e-3) / 1e12
                 xtf = r["xflops"][op] / (ms * 1e-3) / 1e12
                 print("%-12s %-10s %-5s %9.3f %9.3f %9.3f %10.2f %8.1f %10.2f" % (
-                    r["L"].name, op, {2: "wino", 3: "wino4"}.get(r["algo"][op], "igemm"), ms, med, ts[0], tf,
+                    r["L"].name, op, {2: "wino", 3: "wino4", 4: "fft"}.get(r["algo"][op], "igemm"), ms, med, ts[0], tf,
                     100 * tf / PEAK_MFMA_FP32_TFLOPS, xtf), file=sys.stderr)
         for op in op_ms:
             print("total %-10s %9.3f ms/step" % (op, op_ms[op] / args.steps), file=sys.stderr)

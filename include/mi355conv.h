@@ -64,11 +64,18 @@ typedef enum {
                                   * 5x5/2, ...): as the stride-1 3x3 layer over the
                                   * space-to-depth rearrangement of the input, which
                                   * the workspace then holds a copy of              */
-    CONV2D_ALGO_WINOGRAD4 = 3    /* F(4x4,3x3), 3x3 stride-1 filters: filter, input and
-                                  * output transforms as separate kernels around 36
-                                  * batched GEMMs; the workspace holds the transformed
-                                  * input and the products (2.25 x the layer's input and
-                                  * output each).  Forward and backward-data             */
+    CONV2D_ALGO_WINOGRAD4 = 3,   /* F(4x4,3x3), stride-1 filters of 3x3 up to 6x6 (the
+                                  * larger ones as sums of 3x3 sub-filters): filter,
+                                  * input and output transforms as separate kernels
+                                  * around 36 batched GEMMs; the workspace holds the
+                                  * transformed input and the products (2.25 x the
+                                  * layer's input and output each).  All three passes */
+    CONV2D_ALGO_FFT = 4          /* product of spectra (Sec. 4.2 "fft": the choice for
+                                  * large filters): stride 1, any filter size, padded
+                                  * input at most 32 x 32 (one tile per image);
+                                  * 544 complex GEMMs between transform kernels, the
+                                  * workspace holds the spectra of filters, images and
+                                  * products.  All three passes                        */
 } conv2d_algo;
 
 typedef enum {

@@ -13,7 +13,7 @@ from typing import Optional, Sequence, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmi355conv.so")
 
-ALGO_AUTO, ALGO_IGEMM, ALGO_WINOGRAD, ALGO_WINOGRAD4 = 0, 1, 2, 3
+ALGO_AUTO, ALGO_IGEMM, ALGO_WINOGRAD, ALGO_WINOGRAD4, ALGO_FFT = 0, 1, 2, 3, 4
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 
 STATIC_SCRATCH_BYTES = 64 << 20

@@ -542,6 +542,130 @@ bool tap_stream_ok(const Geom &g);                    // forward pass with the f
 bool tap_stream_bwd_ok(const Geom &g);                // the same for a stride-1 backward-data pass
 constexpr int kTapBwdMinRows = 12;                 // below that the 32-row MFMA tiles are mostly empty
 
+// ---- frequency-domain path (fft.hip): one 32 x 32 tile per image ---------------------------
+struct FftPlan {
+    bool ok;
+    int rows, cols, depth;      // of the complex product per frequency
+    int chunks, Mpad, Npad, cfg, split, split_tiles;
+    size_t a_bytes, b_bytes, m_bytes, slot_bytes, total_bytes;
+};
+
+// per frequency a complex (rows x depth) . (depth x cols) product.  forward: rows = images,
+// depth = channels, columns = filters; backward-data: columns = channels, depth = filters;
+// backward-weight: rows = filters, depth = images, columns = channels.  The column side is
+// stored in 2 x 2 block form (2 * cols real columns)
+FftPlan plan_fft(const Geom &g, conv2d_op op)
+{
+    FftPlan p = {};
+    if (g.sh != 1 || g.sw != 1 || g.H + 2 * g.ph > 32 || g.W + 2 * g.pw > 32 || g.P < 1 || g.Q < 1) return p;
+    if ((int64_t)g.N * g.C * g.H * g.W * 4 >= (int64_t(1) << 31) || (int64_t)g.N * g.K * g.P * g.Q * 4 >= (int64_t(1) << 31) ||
+        (int64_t)g.K * g.C * g.R * g.S * 4 >= (int64_t(1) << 31))
+        return p;
+    p.rows = op == CONV2D_BWD_WEIGHT ? g.K : g.N;
+    p.depth = op == CONV2D_FWD ? g.C : op == CONV2D_BWD_DATA ? g.K : g.N;
+    p.cols = op == CONV2D_FWD ? g.K : g.C;
+    if (p.rows > 65535 || p.cols > 32767) return p;          // grid dimensions of the transform kernels
+    p.chunks = ceil_div(p.depth, 4);
+    if (p.chunks > 65535) return p;
+    int64_t best = -1;
+    for (int cfg = 0; cfg < 3; ++cfg) {
+        const int64_t cost = (int64_t)round_up(p.rows, wino4_tile_m(cfg)) * round_up(2 * p.cols, wino4_tile_n(cfg));
+        if (best < 0 || cost < best) { best = cost; p.cfg = cfg; }
+    }
+    p.Mpad = round_up(p.rows, wino4_tile_m(p.cfg));
+    p.Npad = round_up(2 * p.cols, wino4_tile_n(p.cfg));
+    // 32-bit byte offsets inside each operand (the chunk is the slowest index)
+    if ((int64_t)p.chunks * 2 * kFftFreqs * p.Mpad * 16 >= (int64_t(1) << 31) ||
+        (int64_t)p.chunks * 2 * kFftFreqs * p.Npad * 16 >= (int64_t(1) << 31))
+        return p;
+    const int64_t tiles = (int64_t)kFftFreqs * (p.Mpad / wino4_tile_m(p.cfg)) * (p.Npad / wino4_tile_n(p.cfg));
+    if (tiles >= (int64_t(1) << 22)) return p;
+    // the last, partly filled round of the 512 resident workgroups as depth shares (as in plan_wino4)
+    const int rem = (int)(tiles % 512);
+    p.split = 1;
+    p.split_tiles = 0;
+    if (rem > 0) {
+        double best_t = (double)p.chunks + 4.0;
+        for (int sp = 2; sp <= 8 && sp <= p.chunks && rem * sp <= 1024; ++sp) {
+            const double t = (double)ceil_div(rem * sp, 512) * ((double)ceil_div(p.chunks, sp) + 4.0) + 2.0;
+            if (t < best_t) { best_t = t; p.split = sp; }
+        }
+        if (p.split > 1) p.split_tiles = rem;
+    }
+    p.a_bytes = align_up((size_t)kFftFreqs * p.chunks * 8 * p.Mpad * sizeof(float), 256);
+    p.b_bytes = align_up((size_t)kFftFreqs * p.chunks * 8 * p.Npad * sizeof(float), 256);
+    p.m_bytes = align_up((size_t)kFftFreqs * p.Mpad * p.Npad * sizeof(float), 256);
+    p.slot_bytes = align_up((size_t)p.split_tiles * p.split * wino4_tile_m(p.cfg) * wino4_tile_n(p.cfg) * sizeof(float), 256);
+    p.total_bytes = p.a_bytes + p.b_bytes + p.m_bytes + p.slot_bytes;
+    p.ok = true;
+    return p;
+}
+
+int run_fft(const Geom &g, conv2d_op op, const float *in, const float *w, const float *bias, float *out,
+            void *ws, size_t ws_bytes, hipStream_t s, int relu = 0)
+{
+    const FftPlan p = plan_fft(g, op);
+    if (!p.ok || op == CONV2D_BWD_WEIGHT) return CONV2D_ERR_ALGO;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
+    const bool fwd = op == CONV2D_FWD;
+    FftArgs a = {};
+    a.in = in; a.w = w; a.bias = bias; a.out = out; a.relu = relu;
+    a.A = (float *)ws;
+    a.B = (float *)((char *)ws + p.a_bytes);
+    a.M = (float *)((char *)ws + p.a_bytes + p.b_bytes);
+    a.slots = (float *)((char *)ws + p.a_bytes + p.b_bytes + p.m_bytes);
+    a.split = p.split; a.split_tiles = p.split_tiles; a.tile_cfg = p.cfg;
+    a.mode = fwd ? 0 : 1;
+    a.C = g.C; a.N = g.N;
+    a.Cin = p.depth; a.Kout = p.cols;
+    a.Hin = fwd ? g.H : g.P; a.Win = fwd ? g.W : g.Q;
+    a.Hout = fwd ? g.P : g.H; a.Wout = fwd ? g.Q : g.W;
+    a.in_off_h = fwd ? g.ph : 0; a.in_off_w = fwd ? g.pw : 0;
+    a.out_off_h = fwd ? 0 : g.ph; a.out_off_w = fwd ? 0 : g.pw;
+    a.R = g.R; a.S = g.S;
+    a.chunks = p.chunks; a.Mpad = p.Mpad; a.Npad = p.Npad;
+    a.in_bytes = (int32_t)((int64_t)g.N * a.Cin * a.Hin * a.Win * 4);
+    a.w_bytes = (int32_t)((int64_t)g.K * g.C * g.R * g.S * 4);
+    return launch_status(launch_fft_conv(a, s));
+}
+
+int run_fft_wgrad(const Geom &g, const float *x, const float *dy, float *dw, float *dbias, float scale, int accumulate,
+                  void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const FftPlan p = plan_fft(g, CONV2D_BWD_WEIGHT);
+    if (!p.ok) return CONV2D_ERR_ALGO;
+    if (!ws_ok(ws, ws_bytes, p.total_bytes)) return CONV2D_ERR_WORKSPACE;
+    FftWgradArgs a = {};
+    a.x = x; a.dy = dy; a.dw = dw; a.db = dbias;
+    a.A = (float *)ws;
+    a.B = (float *)((char *)ws + p.a_bytes);
+    a.M = (float *)((char *)ws + p.a_bytes + p.b_bytes);
+    a.slots = (float *)((char *)ws + p.a_bytes + p.b_bytes + p.m_bytes);
+    a.split = p.split; a.split_tiles = p.split_tiles; a.tile_cfg = p.cfg;
+    a.scale = scale; a.accumulate = accumulate;
+    a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.K = g.K; a.P = g.P; a.Q = g.Q; a.R = g.R; a.S = g.S;
+    a.pad_h = g.ph; a.pad_w = g.pw;
+    a.chunks = p.chunks; a.Mpad = p.Mpad; a.Npad = p.Npad;
+    a.x_bytes = (int32_t)((int64_t)g.N * g.C * g.H * g.W * 4);
+    a.dy_bytes = (int32_t)((int64_t)g.N * g.K * g.P * g.Q * 4);
+    return launch_status(launch_fft_wgrad(a, s));
+}
+
+// Estimated time of the frequency-domain path, seconds; huge where it does not apply or is
+// not worth trying (3x3 and smaller filters, a handful of channels).  Fitted to its kernels'
+// measured times on the 5x5 layers of the AlexNet and Overfeat configurations: ~4.8 ns per
+// transformed image or filter, ~4.4 ns per inverse, the GEMM at ~120 TFLOP/s over its padded
+// size plus ~30 us for its short depth and the fix-up, ~5 us per launch.
+double fft_estimate(const Geom &g, conv2d_op op)
+{
+    const FftPlan p = plan_fft(g, op);
+    if (!p.ok || g.R * g.S < 16 || p.rows < 32 || p.cols < 32 || p.depth < 32) return 1e30;
+    const double n_in = op == CONV2D_BWD_WEIGHT ? (double)g.N * (g.K + g.C) : (double)g.K * g.C + (double)g.N * p.depth;
+    const double n_out = op == CONV2D_BWD_WEIGHT ? (double)g.K * g.C : (double)g.N * p.cols;
+    const double gemm = 2.0 * kFftFreqs * p.Mpad * (double)p.Npad * p.chunks * 8.0 / 120e12 + 30e-6;
+    return 4.8e-9 * n_in + 4.4e-9 * n_out + gemm + 15e-6;
+}
+
 int resolve_algo(const Geom &g, conv2d_op op, int algo)
 {
     const bool s2d_ok = s2d_applicable(g, op);
@@ -577,6 +701,10 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
                 if (t_gemm < (vm_b + wm_b) / 3.5e12) t_gemm = (vm_b + wm_b) / 3.5e12;      // operands streamed from HBM
                 const double t_w4 = t_gemm + (x_b + vm_b) / 4.3e12 + (dy_b + wm_b) / 4.9e12 +
                                     2.0 * w4.tiles * (double)w4.split * tile_b / 5e12 + 25e-6;
+                // filters beyond 3x3 on maps of at most 32 x 32: the product of spectra, when its
+                // estimate is clearly below both
+                const double t_best = t_w4 < 0.95 * t_f2 ? t_w4 : t_f2;
+                if (fft_estimate(g, op) < 0.92 * t_best) return CONV2D_ALGO_FFT;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
             return CONV2D_ALGO_WINOGRAD;
@@ -621,10 +749,15 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
                 double t_gemm = 72.0 * w4.Tpad * (w4.chunks * 8.0) * w4.Kpad / (135e12 * fill);
                 if (t_gemm < (v_b + m_b) / 3.5e12) t_gemm = (v_b + m_b) / 3.5e12;          // operands streamed from HBM
                 const double t_w4 = t_gemm + (in_b + v_b) / (w4.pad_w <= 1 ? 4.8e12 : 3.5e12) + (m_b + out_b) / 4.5e12 + 25e-6;
+                const double t_best = t_w4 < 0.95 * t_f2 ? t_w4 : t_f2;
+                if (fft_estimate(g, op) < 0.92 * t_best) return CONV2D_ALGO_FFT;
                 if (t_w4 < 0.95 * t_f2) return CONV2D_ALGO_WINOGRAD4;
             }
             return CONV2D_ALGO_WINOGRAD;
         }
+        // filters the Winograd forms do not take (7x7 and up at stride 1), many channels: the
+        // product of spectra against the implicit GEMM at ~85 TFLOP/s over the direct flops
+        if (fft_estimate(g, op) < 0.8 * (2.0 * g.N * (double)g.K * g.C * g.P * g.Q * g.R * g.S / 85e12)) return CONV2D_ALGO_FFT;
         return CONV2D_ALGO_IGEMM;
     }
     case CONV2D_ALGO_IGEMM: return CONV2D_ALGO_IGEMM;
@@ -632,6 +765,7 @@ int resolve_algo(const Geom &g, conv2d_op op, int algo)
     case CONV2D_ALGO_WINOGRAD4:
         return (op == CONV2D_BWD_WEIGHT ? plan_wino4_wgrad(g).ok : plan_wino4(g, op).ok) ? CONV2D_ALGO_WINOGRAD4
                                                                                        : CONV2D_ERR_ALGO;
+    case CONV2D_ALGO_FFT: return plan_fft(g, op).ok ? CONV2D_ALGO_FFT : CONV2D_ERR_ALGO;
     default: return CONV2D_ERR_ALGO;
     }
 }
@@ -1017,6 +1151,7 @@ size_t conv2d_workspace_bytes(const conv2d_desc *d, conv2d_op op, conv2d_algo al
         return wino_applicable(g, op) ? wino_ws_bytes(g, op) : plan_s2d(g, op).total_bytes;
     if (al == CONV2D_ALGO_WINOGRAD4)
         return op == CONV2D_BWD_WEIGHT ? plan_wino4_wgrad(g).total_bytes : plan_wino4(g, op).total_bytes;
+    if (al == CONV2D_ALGO_FFT) return plan_fft(g, op).total_bytes;
     switch (op) {
     case CONV2D_FWD: return plan_fwd(g).total_bytes;
     case CONV2D_BWD_DATA: return plan_bwd_data(g).total_bytes;
@@ -1043,6 +1178,7 @@ static int fwd_impl(const conv2d_desc *d, const float *x, const float *w, const 
     if (al < 0) return al;
     hipStream_t s = (hipStream_t)hip_stream;
     if (al == CONV2D_ALGO_WINOGRAD4) return run_wino4(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
+    if (al == CONV2D_ALGO_FFT) return run_fft(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
     if (al == CONV2D_ALGO_WINOGRAD)
         return wino_applicable(g, CONV2D_FWD) ? run_wino(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu)
                                               : run_s2d(g, CONV2D_FWD, x, w, bias, y, ws, ws_bytes, s, relu);
@@ -1124,7 +1260,7 @@ int conv2d_fwd_static(const conv2d_desc *d, const float *x, const float *w, cons
     if (need == 0) return CONV2D_ERR_ALGO;
     // AUTO may pick the unfused Winograd path, whose workspace holds whole transformed
     // tensors: where that does not fit, take the fused kernels, which need far less
-    if (need > (size_t)CONV2D_STATIC_SCRATCH_BYTES && algo == CONV2D_ALGO_AUTO && al == CONV2D_ALGO_WINOGRAD4) {
+    if (need > (size_t)CONV2D_STATIC_SCRATCH_BYTES && algo == CONV2D_ALGO_AUTO && (al == CONV2D_ALGO_WINOGRAD4 || al == CONV2D_ALGO_FFT)) {
         algo = CONV2D_ALGO_WINOGRAD;
         need = conv2d_workspace_bytes(d, CONV2D_FWD, algo);
         if (need == 0) return CONV2D_ERR_ALGO;
@@ -1251,6 +1387,7 @@ int conv2d_bwd_data(const conv2d_desc *d, const float *dy, const float *w, float
         return launch_status(launch_bwd_data_smallc(sa, s));
     }
     if (al == CONV2D_ALGO_WINOGRAD4) return run_wino4(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
+    if (al == CONV2D_ALGO_FFT) return run_fft(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s);
     if (al == CONV2D_ALGO_WINOGRAD)
         return wino_applicable(g, CONV2D_BWD_DATA)
                    ? run_wino(g, CONV2D_BWD_DATA, dy, w, nullptr, dx, ws, ws_bytes, s)
@@ -1365,6 +1502,7 @@ int conv2d_bwd_weight(const conv2d_desc *d, const float *x, const float *dy, flo
     hipStream_t s = (hipStream_t)hip_stream;
 
     if (al == CONV2D_ALGO_WINOGRAD4) return run_wino4_wgrad(g, x, dy, dw, dbias, scale, accumulate, ws, ws_bytes, s);
+    if (al == CONV2D_ALGO_FFT) return run_fft_wgrad(g, x, dy, dw, dbias, scale, accumulate, ws, ws_bytes, s);
     if (al == CONV2D_ALGO_WINOGRAD) {
         if (!wino_applicable(g, CONV2D_BWD_WEIGHT))
             return run_s2d_wgrad(g, x, dy, dw, dbias, scale, accumulate, ws, ws_bytes, s);

@@ -244,6 +244,62 @@ hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s);
 int wino4_tile_m(int cfg);
 int wino4_tile_n(int cfg);
 hipError_t launch_wino4(const W4Args &a, hipStream_t s);
+// The batched GEMM of that path on its own: C[b][m][n] = sum_d A[b][d][m] * B[b][d][n], A and
+// B in MFMA order (depth/8, depth%2, row, (depth%8)/2, the last one contiguous), any number of
+// batches b: the batch is the slowest part of the tile index.  `grid` workgroups take the tiles tile_base ...;
+// with nsplit > 1 every tile is computed as nsplit depth shares into `slots`, which
+// launch_w4_fixup adds up into C in a fixed order.
+constexpr int kFftFreqs = 32 * 17;      // frequencies kept by the frequency-domain path: f = v * 17 + u, u < 17, v < 32
+struct W4GemmArgs {
+    const float *A, *B;
+    float *C;
+    float *slots;              // [tile][split] partial workgroup tiles of a launch with nsplit > 1
+    int32_t chunks, Mpad, Npad, tiles_m, tiles_n;
+    int32_t tile_base;         // first tile of this launch (tile order: row tile fastest, column tile, batch)
+    int32_t nsplit;            // workgroups per tile, each taking an equal share of the chunks
+    int32_t batch_inner;       // 0: A[b][chunk][half][row][4], C[b][row][col]; 1: A[chunk][half][b][row][4],
+                               // C[row][b][col] with kFftFreqs batches (chunks * 2 * kFftFreqs * rows * 16 below 2^31)
+};
+void launch_w4_gemm(const W4GemmArgs &g, int cfg, unsigned grid, hipStream_t s);
+void launch_w4_fixup(const W4GemmArgs &g, int cfg, unsigned tiles, hipStream_t s);
+
+// Frequency-domain path for stride-1 layers whose padded input fits one 32 x 32 tile (see
+// fft.hip): spectra of the images and filters, one complex product per frequency as a real
+// GEMM with 2 x 2 blocks, inverse transform of the products.
+struct FftArgs {                        // forward (mode 0) and backward-data (mode 1)
+    const float *in;           // x, or dy
+    const float *w;            // [K][C][R][S]
+    const float *bias;         // nullable
+    float *out;                // y, or dx
+    float *A, *B, *M;          // workspace: image spectra (rows n), filter spectra (block form, columns
+                               // 2 ch + po), products [f][Mpad][Npad]
+    float *slots;
+    int32_t split, split_tiles, tile_cfg;
+    int32_t relu, mode;
+    int32_t C;                 // channel count of w (its second axis)
+    int32_t N, Cin, Hin, Win, Kout, Hout, Wout;
+    int32_t in_off_h, in_off_w;    // where the image sits in its tile (the padding, or 0)
+    int32_t out_off_h, out_off_w;  // where the output starts in the inverse tile (0, or the padding)
+    int32_t R, S;
+    int32_t chunks;            // 8-deep chunks of the 2*Cin-deep real product: ceil(Cin / 4)
+    int32_t Mpad, Npad;        // N rows and 2*Kout columns, padded to the GEMM's workgroup tile
+    int32_t in_bytes, w_bytes; // sizes of `in` and `w` (below 2^31)
+};
+hipError_t launch_fft_conv(const FftArgs &a, hipStream_t s);
+struct FftWgradArgs {
+    const float *x, *dy;
+    float *dw, *db;            // db nullable
+    float *A, *B, *M;          // workspace: spectra of dy (rows k), of x (conjugate block form, columns 2c+po), products
+    float *slots;
+    int32_t split, split_tiles, tile_cfg;
+    float scale;
+    int32_t accumulate;
+    int32_t N, C, H, W, K, P, Q, R, S, pad_h, pad_w;
+    int32_t chunks;            // ceil(N / 4): the images are the depth
+    int32_t Mpad, Npad;        // K rows, 2*C columns, padded
+    int32_t x_bytes, dy_bytes; // both below 2^31
+};
+hipError_t launch_fft_wgrad(const FftWgradArgs &a, hipStream_t s);
 
 // Winograd backward-weight F(3x3,2x2) (see winograd_wgrad.hip).
 struct WinoWgradArgs {
@@ -370,7 +426,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 enum KernelId {
     KID_WINO4_GEMM = 0, KID_WINO4_INPUT, KID_WINO4_OUTPUT, KID_WINO4_WG_INPUT, KID_WINO4_WG_DY,
     KID_WINO_PAIR, KID_WINO_FUSED, KID_WINO_WGRAD_VEC, KID_WINO_WGRAD, KID_GEMMCONV, KID_WGRAD,
-    KID_PW_STREAM, KID_PW_WGRAD, KID_SMALLC, KID_TAP_STREAM, KID_TAP_WGRAD, KID_COUNT
+    KID_PW_STREAM, KID_PW_WGRAD, KID_SMALLC, KID_TAP_STREAM, KID_TAP_WGRAD, KID_FFT_IMAGE, KID_FFT_INVERSE, KID_FFT_FILTER, KID_COUNT
 };
 class ProfScope {
 public:

@@ -29,6 +29,7 @@ const char *const kKernelNames[KID_COUNT] = {
     "wino4_wg_dy_kernel", "wino_pair_kernel", "wino_fused_kernel", "wino_wgrad_vec_kernel",
     "wino_wgrad_kernel", "gemmconv_kernel", "wgrad_kernel", "pw_stream_kernel",
     "pw_wgrad_kernel", "bwd_data_smallc_kernel", "pw_stream_kernel<TAPS>", "pw_wgrad_kernel<TAPS>",
+    "fft_image_kernel", "fft_inverse_kernel", "fft_image_kernel<filters>",
 };
 
 }  // namespace

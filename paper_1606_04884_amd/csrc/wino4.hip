@@ -220,15 +220,6 @@ __global__ __launch_bounds__(256) void wino4_input_kernel(W4Args a)
 // overlap the MFMAs of the other).  Workgroup ids are remapped so that each XCD walks a
 // contiguous range of tiles in the order (position, column tile, row tile): the B tile
 // column is then reused from its L2 across the row tiles, and one position's A stays there.
-struct W4GemmArgs {
-    const float *A, *B;
-    float *C;
-    float *slots;              // [tile][split] partial workgroup tiles of a launch with nsplit > 1
-    int32_t chunks, Mpad, Npad, tiles_m, tiles_n;
-    int32_t tile_base;         // first tile of this launch (tile order: row tile fastest, column tile, position)
-    int32_t nsplit;            // workgroups per tile, each taking an equal share of the chunks
-};
-
 __device__ __forceinline__ int w4_xcd_remap(int id, int nb)
 {
     const int per = nb >> 3, rem = nb & 7;
@@ -236,7 +227,7 @@ __device__ __forceinline__ int w4_xcd_remap(int id, int nb)
     return xcd * per + (xcd < rem ? xcd : rem) + local;
 }
 
-template <int WGM, int WGN>
+template <int WGM, int WGN, bool BATCH_INNER, int NB>
 __global__ __launch_bounds__(256, 2) void wino4_gemm_kernel(W4GemmArgs a)
 {
     const int lane = threadIdx.x & 63;
@@ -256,13 +247,20 @@ __global__ __launch_bounds__(256, 2) void wino4_gemm_kernel(W4GemmArgs a)
     const int c_first = (int)((int64_t)split * a.chunks / a.nsplit);
     const int c_end = (int)((int64_t)(split + 1) * a.chunks / a.nsplit);
 
-    const int a_chunk = 2 * a.Mpad * 16, b_chunk = 2 * a.Npad * 16;          // bytes per chunk
-    const float *Ap = a.A + (int64_t)pos * a.chunks * 2 * a.Mpad * 4;
-    const float *Bp = a.B + (int64_t)pos * a.chunks * 2 * a.Npad * 4;
-    const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void *)Ap, 0, a.chunks * a_chunk, 0x00020000);
-    const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc((void *)Bp, 0, a.chunks * b_chunk, 0x00020000);
-    const uint32_t aoff = (uint32_t)(lhi * a.Mpad + m0 + l32) * 16u;
-    const uint32_t boff = (uint32_t)(lhi * a.Npad + n0 + l32) * 16u;
+    // BATCH_INNER = false: A[b][chunk][half][row][4], C[b][row][col] (the Winograd transforms'
+    // layout).  true: A[chunk][half][b][row][4], C[row][b][col] with NB batches (the frequency-
+    // domain path: what one of its transform waves touches then lies close together)
+    const int a_half = BATCH_INNER ? NB * a.Mpad * 16 : a.Mpad * 16, b_half = BATCH_INNER ? NB * a.Npad * 16 : a.Npad * 16;
+    const int a_chunk = 2 * a_half, b_chunk = 2 * b_half;                     // bytes per chunk
+    const float *Ap = a.A + (BATCH_INNER ? (int64_t)pos * a.Mpad * 4 : (int64_t)pos * a.chunks * 2 * a.Mpad * 4);
+    const float *Bp = a.B + (BATCH_INNER ? (int64_t)pos * a.Npad * 4 : (int64_t)pos * a.chunks * 2 * a.Npad * 4);
+    // exactly this batch's extent: the last chunk's second half ends the buffer
+    const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)Ap, 0, BATCH_INNER ? (a.chunks - 1) * a_chunk + a_half + a.Mpad * 16 : a.chunks * a_chunk, 0x00020000);
+    const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)Bp, 0, BATCH_INNER ? (a.chunks - 1) * b_chunk + b_half + a.Npad * 16 : a.chunks * b_chunk, 0x00020000);
+    const uint32_t aoff = BATCH_INNER ? (uint32_t)(lhi * a_half) + (uint32_t)(m0 + l32) * 16u : (uint32_t)(lhi * a.Mpad + m0 + l32) * 16u;
+    const uint32_t boff = BATCH_INNER ? (uint32_t)(lhi * b_half) + (uint32_t)(n0 + l32) * 16u : (uint32_t)(lhi * a.Npad + n0 + l32) * 16u;
 
     // three register sets: the loads of chunk i+2 are issued during the MFMAs of chunk i
     floatx4 ra[3][2], rb[3][4];
@@ -325,8 +323,9 @@ __global__ __launch_bounds__(256, 2) void wino4_gemm_kernel(W4GemmArgs a)
     // accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
     // (a split tile goes to its slot, a dense TM x TN block)
     float *Cp = a.nsplit > 1 ? a.slots + (int64_t)lb * (TM * TN) + (wm * 64 + 4 * lhi) * TN + wn * 128 + l32
-                             : a.C + (int64_t)pos * a.Mpad * a.Npad + (int64_t)(m0 + 4 * lhi) * a.Npad + n0 + l32;
-    const int64_t pitch = a.nsplit > 1 ? TN : a.Npad;
+                             : BATCH_INNER ? a.C + (int64_t)pos * a.Npad + (int64_t)(m0 + 4 * lhi) * NB * a.Npad + n0 + l32
+                                           : a.C + (int64_t)pos * a.Mpad * a.Npad + (int64_t)(m0 + 4 * lhi) * a.Npad + n0 + l32;
+    const int64_t pitch = a.nsplit > 1 ? TN : BATCH_INNER ? (int64_t)NB * a.Npad : a.Npad;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -339,14 +338,15 @@ __global__ __launch_bounds__(256, 2) void wino4_gemm_kernel(W4GemmArgs a)
 // Sum of the depth splits of the tiles that were cut (see launch_wino4): C tile j of the
 // split group = slot[j*S] + slot[j*S+1] + ... in that order.  Grid (tiles, 8): block
 // (j, part) adds an eighth of the tile, 16 bytes per thread and step.
-template <int TM, int TN>
+template <int TM, int TN, bool BATCH_INNER, int NB>
 __global__ __launch_bounds__(256) void wino4_gemm_fixup_kernel(W4GemmArgs a)
 {
     const int tile = a.tile_base + blockIdx.x;
     const int tm = tile % a.tiles_m, r1 = tile / a.tiles_m;
     const int tn = r1 % a.tiles_n, pos = r1 / a.tiles_n;
     const float *src = a.slots + (int64_t)blockIdx.x * a.nsplit * (TM * TN);
-    float *dst = a.C + (int64_t)pos * a.Mpad * a.Npad + (int64_t)tm * TM * a.Npad + tn * TN;
+    const int64_t pitch = BATCH_INNER ? (int64_t)NB * a.Npad : a.Npad;
+    float *dst = a.C + (BATCH_INNER ? (int64_t)pos * a.Npad : (int64_t)pos * a.Mpad * a.Npad) + (int64_t)tm * TM * pitch + tn * TN;
     constexpr int NV = TM * TN / 4 / 8;                 // 16-byte vectors per part
     for (int iv = threadIdx.x; iv < NV; iv += 256) {
         const int e = (blockIdx.y * NV + iv) * 4;
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void wino4_gemm_fixup_kernel(W4GemmArgs a)
             const floatx4 q = *reinterpret_cast<const floatx4 *>(src + (int64_t)sp * (TM * TN) + e);
             r[0] += q[0]; r[1] += q[1]; r[2] += q[2]; r[3] += q[3];
         }
-        *reinterpret_cast<floatx4 *>(dst + (int64_t)row * a.Npad + col) = r;
+        *reinterpret_cast<floatx4 *>(dst + (int64_t)row * pitch + col) = r;
     }
 }
 
@@ -652,18 +652,30 @@ __global__ __launch_bounds__(256) void wino4_wg_bias_kernel(W4WgradArgs a)
 int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : cfg == 1 ? 256 : 64; }
 int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : cfg == 1 ? 128 : 512; }
 
-static void launch_w4_gemm(const W4GemmArgs &g, int cfg, unsigned grid, hipStream_t s)
+void launch_w4_gemm(const W4GemmArgs &g, int cfg, unsigned grid, hipStream_t s)
 {
-    if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2>), dim3(grid), dim3(256), 0, s, g);
-    else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_kernel<4, 1>), dim3(grid), dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((wino4_gemm_kernel<1, 4>), dim3(grid), dim3(256), 0, s, g);
+    if (g.batch_inner) {
+        if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
+        else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_kernel<4, 1, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_kernel<1, 4, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
+        return;
+    }
+    if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2, false, 0>), dim3(grid), dim3(256), 0, s, g);
+    else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_kernel<4, 1, false, 0>), dim3(grid), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((wino4_gemm_kernel<1, 4, false, 0>), dim3(grid), dim3(256), 0, s, g);
 }
 
-static void launch_w4_fixup(const W4GemmArgs &g, int cfg, unsigned tiles, hipStream_t s)
+void launch_w4_fixup(const W4GemmArgs &g, int cfg, unsigned tiles, hipStream_t s)
 {
-    if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256>), dim3(tiles, 8), dim3(256), 0, s, g);
-    else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128>), dim3(tiles, 8), dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<64, 512>), dim3(tiles, 8), dim3(256), 0, s, g);
+    if (g.batch_inner) {
+        if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
+        else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<64, 512, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
+        return;
+    }
+    if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256, false, 0>), dim3(tiles, 8), dim3(256), 0, s, g);
+    else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128, false, 0>), dim3(tiles, 8), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<64, 512, false, 0>), dim3(tiles, 8), dim3(256), 0, s, g);
 }
 
 hipError_t launch_wino4(const W4Args &a, hipStream_t s)

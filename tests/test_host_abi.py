@@ -149,11 +149,17 @@ def test_algo_choice_rules():
     assert pick((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # odd width: no pairs
     assert pick((64, 3, 224, 224, 16, 3, 3, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM      # few filters
     assert B.conv2d_workspace_bytes((64, 3, 225, 225, 64, 3, 3, 1, 1, 1, 1), B.OP_FWD, B.ALGO_WINOGRAD) == 0
-    five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5: four 3x3 sub-filters, fused or unfused
-    for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
-        assert pick(five, op) in (B.ALGO_WINOGRAD, B.ALGO_WINOGRAD4)
+    five = (128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2)            # 5x5 on a map that fits one 32x32 tile: four 3x3
+    for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):      # sub-filters, fused or unfused, or the product of spectra
+        assert pick(five, op) in (B.ALGO_WINOGRAD, B.ALGO_WINOGRAD4, B.ALGO_FFT)
         assert B.conv2d_workspace_bytes(five, op, B.ALGO_WINOGRAD) > 0
         assert B.conv2d_workspace_bytes(five, op, B.ALGO_WINOGRAD4) > 0
+        assert B.conv2d_workspace_bytes(five, op, B.ALGO_FFT) > 0
+    big5 = (16, 64, 56, 56, 64, 5, 5, 1, 1, 2, 2)              # the same filter on a larger map: never the spectra
+    for op in (B.OP_FWD, B.OP_BWD_DATA, B.OP_BWD_WEIGHT):
+        assert pick(big5, op) in (B.ALGO_WINOGRAD, B.ALGO_WINOGRAD4)
+        assert B.conv2d_workspace_bytes(big5, op, B.ALGO_FFT) == 0
+    assert pick((128, 16, 28, 28, 32, 5, 5, 1, 1, 2, 2), B.OP_FWD) != B.ALGO_FFT          # a handful of channels
     small5 = (128, 32, 27, 27, 64, 5, 5, 1, 1, 2, 2)           # few channels: the fused kernels
     assert pick(small5, B.OP_FWD) == B.ALGO_WINOGRAD
     assert pick((8, 64, 20, 20, 64, 4, 4, 1, 1, 1, 1), B.OP_FWD) == B.ALGO_IGEMM          # 4x4: no saving
