@@ -653,7 +653,7 @@ int run_fft_wgrad(const Geom &g, const float *x, const float *dy, float *dw, flo
 
 // Estimated time of the frequency-domain path, seconds; huge where it does not apply or is
 // not worth trying (3x3 and smaller filters, a handful of channels).  Fitted to its kernels'
-// measured times on the 5x5 layers of the AlexNet and Overfeat configurations: ~4.8 ns per
+// measured times on the 5x5 layers of the AlexNet and Overfeat configurations: ~3.2 ns per
 // transformed image or filter, ~4.4 ns per inverse, the GEMM at ~120 TFLOP/s over its padded
 // size plus ~30 us for its short depth and the fix-up, ~5 us per launch.
 double fft_estimate(const Geom &g, conv2d_op op)
@@ -663,7 +663,7 @@ double fft_estimate(const Geom &g, conv2d_op op)
     const double n_in = op == CONV2D_BWD_WEIGHT ? (double)g.N * (g.K + g.C) : (double)g.K * g.C + (double)g.N * p.depth;
     const double n_out = op == CONV2D_BWD_WEIGHT ? (double)g.K * g.C : (double)g.N * p.cols;
     const double gemm = 2.0 * kFftFreqs * p.Mpad * (double)p.Npad * p.chunks * 8.0 / 120e12 + 30e-6;
-    return 4.8e-9 * n_in + 4.4e-9 * n_out + gemm + 15e-6;
+    return 3.2e-9 * n_in + 4.4e-9 * n_out + gemm + 15e-6;
 }
 
 int resolve_algo(const Geom &g, conv2d_op op, int algo)

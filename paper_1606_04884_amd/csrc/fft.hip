@@ -24,7 +24,7 @@
 // the inverse kernel gathers as whole 128-byte lines.
 //
 // The transforms are dense 32-point DFT matrices on the matrix cores, not butterflies: a
-// 32 x 32 tile takes 96 v_mfma_f32_32x32x2_f32 (82 for the inverse), a wave per image, and the
+// 32 x 32 tile takes 48 v_mfma_f32_32x32x2_f32 (82 for the inverse), a wave per image, and the
 // data never leaves the registers between the two passes: the accumulator layout of the
 // first product (lane = column, registers = rows) is the B-operand layout of the second, whose
 // reduction runs over those rows in the order the registers hold them (the constant A operand
@@ -84,44 +84,67 @@ struct FftImgArgs {
     int32_t chunks, pitch, mode;
 };
 
-__global__ __launch_bounds__(256, 2) void fft_image_kernel(FftImgArgs a)
+// Staging area of a workgroup: per frequency one 128-byte line of the operand (8 rows of 16
+// bytes) + 16 bytes so that the lanes of a wave, which hold neighbouring frequencies, hit
+// different banks; then the 64-float sine / cosine table.
+constexpr int kStageF = 36;                                  // floats per frequency
+constexpr int kImgLds = (kF * kStageF + 64) * 4;
+
+// ROWS operand rows per image b: 1 (mode 0: a workgroup of 8 waves takes 8 images b, so that a
+// compute unit holds two waves per SIMD in ONE workgroup and the launch splits into many short
+// rounds) or 2 (block form: 4 waves, 4 images b, columns 2b and 2b + 1).  Every
+// half-chunk is staged in LDS and leaves as whole 128-byte lines: a compute unit completes
+// about one line-sized store per ~20 cycles, and a wave storing its own 16-byte pieces asks for
+// 34 different lines per instruction (the kernel's time was then set by the number of its stores).
+template <int ROWS, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 512 / (64 * WAVES)) void fft_image_kernel(FftImgArgs a)
 {
-    __shared__ float tab[64];
+    extern __shared__ float sm[];
+    float *tab = sm + kF * kStageF;
     cs32_fill(tab);
-    const int lane = threadIdx.x & 63;
-    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    constexpr int NB = 8 / ROWS, ROUNDS = NB / WAVES;        // images b per workgroup; per wave
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b0 = blockIdx.x * NB;
     const int chunk = blockIdx.y;
-    if (b >= a.nb) return;                                   // the whole wave; no barrier below
     const int l32 = lane & 31, hi = lane >> 5;
-    // first pass: Z^T[w][u] = sum_h X[h][w] exp(-2 pi i h u / 32); B operand [k = h][col = u]
-    // second pass: Y^T[v][u] = sum_w exp(-2 pi i w v / 32) Z^T[w][u]; A operand [row = v][k = w],
-    // w in the order the accumulators of the first pass hold their rows
-    float c1[16], s1[16], c2[16], s2[16];
+    // first pass: Z^T[w][u] = sum_h X[h][w] exp(-2 pi i h u / 32); B operand [k = h][col].  The
+    // input is real, so Z[0] and Z[16] are real: Re Z[u], u = 0..16, and Im Z[u], u = 1..15, are
+    // exactly 32 columns, col = u and col = 16 + u, and ONE product gives both.
+    // second pass: sum_w exp(-2 pi i w v / 32) Z^T[w][u] = (C - iS)(Zr + iZi); A operand [row = v]
+    // [k = w], w in the order the accumulators of the first pass hold their rows; P1 = C . Zp and
+    // P2 = S . Zp on the packed columns, then Yr[u] = P1[u] + P2[16 + u], Yi[u] = P1[16 + u] - P2[u]
+    // with one exchange between the lanes u and 16 + u per register.
+    float c1[16], c2[16], s2[16];
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
         float c, sn;
-        cs32(tab, (2 * s + hi) * l32, c, sn);
-        c1[s] = c; s1[s] = -sn;
+        cs32(tab, (2 * s + hi) * (l32 <= 16 ? l32 : l32 - 16), c, sn);
+        c1[s] = l32 <= 16 ? c : -sn;
         cs32(tab, acc_row(s, hi) * l32, c, sn);
         c2[s] = c; s2[s] = sn;
     }
+    const float pm = (l32 >= 1 && l32 <= 15) ? 1.f : 0.f;    // the lanes u that have an imaginary column
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)a.in, 0, a.in_bytes, 0x00020000);
-    // A operand of the first pass: lane = column w of the tile, step s = rows 2s + hi
+    // A operand of the first pass: lane = column w of the tile, step s = rows 2s + hi; the
+    // image's own offset (a, b: uniform in the wave) goes into the scalar offset
     const int col = l32 - a.off_w;
     const bool colok = (unsigned)col < (unsigned)a.W;
     uint32_t off[16];
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
         const int row = 2 * s + hi - a.off_h;
-        off[s] = colok && (unsigned)row < (unsigned)a.H ? (uint32_t)((b * a.stride_b + row * a.W + col) * 4) : 0x80000000u;
+        off[s] = colok && (unsigned)row < (unsigned)a.H ? (uint32_t)((row * a.W + col) * 4) : 0x80000000u;
     }
     const int s_lo = a.off_h >> 1, s_hi = (a.off_h + a.H + 1) >> 1;     // steps 2s, 2s+1 that touch the image's rows
-    // image j = chunk * 4 + j of this wave; rows outside it already carry the out-of-range offset
+    // the wave's images in the order it takes them: (half, round, first / second of the pair);
+    // image a = 4 * chunk + half + 2 * second of b = b0 + WAVES * round + wave
     float x[16];
-    auto load_x = [&](int j) {
-        const int ai = chunk * 4 + j;
-        const uint32_t bad = ai < a.na ? 0u : 0x80000000u;
-        const int so = (ai < a.na ? ai : 0) * a.stride_a * 4;
+    auto load_x = [&](int seq) {
+        const int second = seq & 1, round = (seq >> 1) % ROUNDS, half = (seq >> 1) / ROUNDS;
+        const int ai = chunk * 4 + half + 2 * second, b = b0 + WAVES * round + wave;
+        const bool ok = ai < a.na && b < a.nb;
+        const uint32_t bad = ok ? 0u : 0x80000000u;
+        const int so = ok ? (ai * a.stride_a + b * a.stride_b) * 4 : 0;
 #pragma unroll
         for (int s = 0; s < 16; ++s) x[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off[s] | bad, so, 0));
     };
@@ -129,51 +152,68 @@ __global__ __launch_bounds__(256, 2) void fft_image_kernel(FftImgArgs a)
     const int64_t fstride = (int64_t)a.pitch * 4;            // floats between frequencies
     floatx16 pr, pi;                                         // the first image of a pair
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int j = ((t & 1) << 1) | (t >> 1);             // 0, 2, 1, 3
-        const int jn = (((t + 1) & 1) << 1) | ((t + 1) >> 1);
-        floatx16 zr, zi, yr, yi;
+    for (int seq = 0; seq < 4 * ROUNDS; ++seq) {
+        const int second = seq & 1, round = (seq >> 1) % ROUNDS, half = (seq >> 1) / ROUNDS;
+        floatx16 z, p1, p2, yr, yi;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { zr[e] = 0.f; zi[e] = 0.f; yr[e] = 0.f; yi[e] = 0.f; }
+        for (int e = 0; e < 16; ++e) { z[e] = 0.f; p1[e] = 0.f; p2[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            if (s >= s_lo && s < s_hi) {                     // uniform
-                zr = __builtin_amdgcn_mfma_f32_32x32x2f32(x[s], c1[s], zr, 0, 0, 0);
-                zi = __builtin_amdgcn_mfma_f32_32x32x2f32(x[s], s1[s], zi, 0, 0, 0);
-            }
+            if (s >= s_lo && s < s_hi)                       // uniform
+                z = __builtin_amdgcn_mfma_f32_32x32x2f32(x[s], c1[s], z, 0, 0, 0);
         }
         // the first pass has read x: the next image's loads go out here and are in flight during
-        // the 64 MFMAs of the second pass
+        // the 32 MFMAs of the second pass
         __builtin_amdgcn_sched_barrier(0);
-        if (t < 3) load_x(jn);
+        if (seq + 1 < 4 * ROUNDS) load_x(seq + 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            yr = __builtin_amdgcn_mfma_f32_32x32x2f32(c2[s], zr[s], yr, 0, 0, 0);
-            yr = __builtin_amdgcn_mfma_f32_32x32x2f32(s2[s], zi[s], yr, 0, 0, 0);
-            yi = __builtin_amdgcn_mfma_f32_32x32x2f32(c2[s], zi[s], yi, 0, 0, 0);
-            yi = __builtin_amdgcn_mfma_f32_32x32x2f32(-s2[s], zr[s], yi, 0, 0, 0);
+            p1 = __builtin_amdgcn_mfma_f32_32x32x2f32(c2[s], z[s], p1, 0, 0, 0);
+            p2 = __builtin_amdgcn_mfma_f32_32x32x2f32(s2[s], z[s], p2, 0, 0, 0);
         }
-        if ((t & 1) == 0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float q1 = __shfl_xor(p1[e], 16), q2 = __shfl_xor(p2[e], 16);
+            yr[e] = p1[e] + pm * q2;
+            yi[e] = pm * q1 - p2[e];
+        }
+        if (!second) {
             pr = yr; pi = yi;
-        } else if (l32 < kUH) {
-            // lane = u (kept below 17), element e = row v; images j - 2 (pr, pi) and j (yr, yi): half j % 2
-            float *base = a.dst + ((int64_t)chunk * 2 + (j & 1)) * kF * fstride;
+            continue;
+        }
+        // the pair's spectra into the staging line of their frequency: lane = u (kept below 17),
+        // element e = row v; slot = the operand row inside the workgroup's 8
+        if (l32 < kUH) {
+            const int slot = (WAVES * round + wave) * ROWS;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int f = acc_row(e, hi) * kUH + l32;
-                float *p = base + (int64_t)f * fstride;
-                if (a.mode == 0) {
+                float *q = sm + (acc_row(e, hi) * kUH + l32) * kStageF + slot * 4;
+                if (ROWS == 1) {
                     const floatx4 v = {pr[e], pi[e], yr[e], yi[e]};
-                    *reinterpret_cast<floatx4 *>(p + (int64_t)b * 4) = v;
+                    *reinterpret_cast<floatx4 *>(q) = v;
                 } else {
-                    const float s = a.mode == 1 ? 1.f : -1.f;
-                    const floatx4 v0 = {pr[e], s * pi[e], yr[e], s * yi[e]};
-                    const floatx4 v1 = {-s * pi[e], pr[e], -s * yi[e], yr[e]};
-                    *reinterpret_cast<floatx4 *>(p + (int64_t)(2 * b) * 4) = v0;
-                    *reinterpret_cast<floatx4 *>(p + (int64_t)(2 * b + 1) * 4) = v1;
+                    const float sg = a.mode == 1 ? 1.f : -1.f;
+                    const floatx4 v0 = {pr[e], sg * pi[e], yr[e], sg * yi[e]};
+                    const floatx4 v1 = {-sg * pi[e], pr[e], -sg * yi[e], yr[e]};
+                    *reinterpret_cast<floatx4 *>(q) = v0;
+                    *reinterpret_cast<floatx4 *>(q + 4) = v1;
                 }
             }
+        }
+        if (round == ROUNDS - 1) {
+            // the half-chunk is complete: out as whole lines (thread t: 16 bytes of line f)
+            __syncthreads();
+            const int row0 = b0 * ROWS, nrows = a.nb * ROWS;
+            float *base = a.dst + ((int64_t)chunk * 2 + half) * kF * fstride + (int64_t)row0 * 4;
+#pragma unroll
+            for (int i = 0; i < (kF * 8 + 64 * WAVES - 1) / (64 * WAVES); ++i) {
+                const int idx = threadIdx.x + 64 * WAVES * i, f = idx >> 3, r8 = idx & 7;
+                if (idx < kF * 8 && row0 + r8 < nrows)
+                    *reinterpret_cast<floatx4 *>(base + (int64_t)f * fstride + r8 * 4) =
+                        *reinterpret_cast<const floatx4 *>(sm + f * kStageF + r8 * 4);
+            }
+            __syncthreads();
         }
     }
 }
@@ -332,9 +372,20 @@ hipError_t run_gemm(const float *A, const float *B, float *M, float *slots, int 
 hipError_t launch_image(const FftImgArgs &ia, int kid, hipStream_t s)
 {
     const int steps = ((ia.off_h + ia.H + 1) >> 1) - (ia.off_h >> 1);
-    const ProfScope ps(kid, (2.0 * steps + 64.0) * 4096.0 * ia.nb * (double)ia.chunks * 4,
+    const ProfScope ps(kid, (steps + 32.0) * 4096.0 * ia.nb * (double)ia.chunks * 4,
                        (double)ia.in_bytes + 4.0 * kF * ia.chunks * 8.0 * ia.nb * (ia.mode ? 2 : 1), s);
-    hipLaunchKernelGGL(fft_image_kernel, dim3((unsigned)((ia.nb + 3) / 4), (unsigned)ia.chunks), dim3(256), 0, s, ia);
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(fft_image_kernel<1, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, kImgLds);
+        if (attr == hipSuccess)
+            attr = hipFuncSetAttribute(reinterpret_cast<const void *>(fft_image_kernel<2, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, kImgLds);
+    });
+    if (attr != hipSuccess) return attr;
+    if (ia.mode == 0)
+        hipLaunchKernelGGL((fft_image_kernel<1, 8>), dim3((unsigned)((ia.nb + 7) / 8), (unsigned)ia.chunks), dim3(512), kImgLds, s, ia);
+    else
+        hipLaunchKernelGGL((fft_image_kernel<2, 4>), dim3((unsigned)((ia.nb + 3) / 4), (unsigned)ia.chunks), dim3(256), kImgLds, s, ia);
     return hipGetLastError();
 }
 
