@@ -568,7 +568,7 @@ FftPlan plan_fft(const Geom &g, conv2d_op op)
     p.chunks = ceil_div(p.depth, 4);
     if (p.chunks > 65535) return p;
     int64_t best = -1;
-    for (int cfg = 0; cfg < 3; ++cfg) {
+    for (int cfg = 0; cfg < 4; ++cfg) {          // (the fourth tile, 128 x 128, exists for this path only)
         const int64_t cost = (int64_t)round_up(p.rows, wino4_tile_m(cfg)) * round_up(2 * p.cols, wino4_tile_n(cfg));
         if (best < 0 || cost < best) { best = cost; p.cfg = cfg; }
     }
@@ -580,14 +580,16 @@ FftPlan plan_fft(const Geom &g, conv2d_op op)
         return p;
     const int64_t tiles = (int64_t)kFftFreqs * (p.Mpad / wino4_tile_m(p.cfg)) * (p.Npad / wino4_tile_n(p.cfg));
     if (tiles >= (int64_t(1) << 22)) return p;
-    // the last, partly filled round of the 512 resident workgroups as depth shares (as in plan_wino4)
-    const int rem = (int)(tiles % 512);
+    // the last, partly filled round of the resident workgroups (512 of four waves, 1024 of two)
+    // as depth shares (as in plan_wino4)
+    const int resident = p.cfg == 3 ? 1024 : 512;
+    const int rem = (int)(tiles % resident);
     p.split = 1;
     p.split_tiles = 0;
     if (rem > 0) {
         double best_t = (double)p.chunks + 4.0;
-        for (int sp = 2; sp <= 8 && sp <= p.chunks && rem * sp <= 1024; ++sp) {
-            const double t = (double)ceil_div(rem * sp, 512) * ((double)ceil_div(p.chunks, sp) + 4.0) + 2.0;
+        for (int sp = 2; sp <= 8 && sp <= p.chunks && rem * sp <= 2 * resident; ++sp) {
+            const double t = (double)ceil_div(rem * sp, resident) * ((double)ceil_div(p.chunks, sp) + 4.0) + 2.0;
             if (t < best_t) { best_t = t; p.split = sp; }
         }
         if (p.split > 1) p.split_tiles = rem;

@@ -648,16 +648,18 @@ __global__ __launch_bounds__(256) void wino4_wg_bias_kernel(W4WgradArgs a)
 }
 
 // ---------------------------------------------------------------- launchers
-// workgroup tile: 2 x 2, 4 x 1 or 1 x 4 wave tiles of 64 rows x 128 columns
-int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : cfg == 1 ? 256 : 64; }
-int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : cfg == 1 ? 128 : 512; }
+// workgroup tile: 2 x 2, 4 x 1 or 1 x 4 wave tiles of 64 rows x 128 columns; cfg 3 (the
+// frequency-domain path's small products only): 2 x 1 wave tiles, a workgroup of two waves
+int wino4_tile_m(int cfg) { return cfg == 0 ? 128 : cfg == 1 ? 256 : cfg == 2 ? 64 : 128; }
+int wino4_tile_n(int cfg) { return cfg == 0 ? 256 : cfg == 1 ? 128 : cfg == 2 ? 512 : 128; }
 
 void launch_w4_gemm(const W4GemmArgs &g, int cfg, unsigned grid, hipStream_t s)
 {
     if (g.batch_inner) {
         if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
         else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_kernel<4, 1, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((wino4_gemm_kernel<1, 4, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
+        else if (cfg == 2) hipLaunchKernelGGL((wino4_gemm_kernel<1, 4, true, kFftFreqs>), dim3(grid), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_kernel<2, 1, true, kFftFreqs>), dim3(grid), dim3(128), 0, s, g);
         return;
     }
     if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_kernel<2, 2, false, 0>), dim3(grid), dim3(256), 0, s, g);
@@ -670,7 +672,8 @@ void launch_w4_fixup(const W4GemmArgs &g, int cfg, unsigned tiles, hipStream_t s
     if (g.batch_inner) {
         if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
         else if (cfg == 1) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<256, 128, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<64, 512, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
+        else if (cfg == 2) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<64, 512, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 128, true, kFftFreqs>), dim3(tiles, 8), dim3(256), 0, s, g);
         return;
     }
     if (cfg == 0) hipLaunchKernelGGL((wino4_gemm_fixup_kernel<128, 256, false, 0>), dim3(tiles, 8), dim3(256), 0, s, g);
