@@ -21,6 +21,8 @@ GEOMS = [
     (1, 2, 28, 28, 2, 5, 5, 1, 1, 2, 2),        # the inception module's: 32 padded, no slack at all
     (2, 3, 9, 14, 2, 7, 4, 1, 1, 3, 1),         # rectangular everything
     (1, 1, 5, 5, 1, 5, 5, 1, 1, 0, 0),          # single output pixel
+    (2, 4, 10, 10, 4, 3, 3, 1, 1, 3, 3),        # padding beyond the filter's reach
+    (3, 5, 6, 20, 6, 1, 7, 1, 1, 0, 3),         # one-row filter
 ]
 
 

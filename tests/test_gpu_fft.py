@@ -31,6 +31,9 @@ SHAPES = [
     (2, 4, 8, 8, 4, 1, 1, 1, 1, 0, 0),            # 1x1 filter
     (4, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2),       # AlexNet conv2 at a small batch
     (40, 8, 12, 12, 200, 5, 5, 1, 1, 2, 2),       # 40 rows x 400 columns: the 64-row x 512-column workgroup tile
+    (2, 4, 10, 10, 4, 3, 3, 1, 1, 3, 3),          # padding beyond the filter's reach: output rows that see only zeros
+    (3, 5, 6, 20, 6, 1, 7, 1, 1, 0, 3),           # one-row filter
+    (2, 36, 16, 16, 36, 5, 5, 1, 1, 2, 2),        # 72 product columns, 9 depth chunks: the 128 x 128 workgroup tile
 ]
 
 
