@@ -42,7 +42,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int kL = 32, kUH = 17, kF = kFftFreqs;
+constexpr int kUH = 17, kF = kFftFreqs;      // kept rows of a 32 x 32 spectrum; kept frequencies
 
 // row of accumulator element e in a lane of the upper (hi = 1) or lower half of the wave
 __device__ __forceinline__ int acc_row(int e, int hi) { return 8 * (e >> 2) + 4 * hi + (e & 3); }
@@ -61,14 +61,14 @@ __device__ __forceinline__ void cs32(const float *tab, int m, float &c, float &s
 // One wave per (b, four consecutive a): image (a, b) at in + a * stride_a + b * stride_b.
 // Forward / backward-data: a = reduction channel, b = image; for the filters a = the reduced
 // axis of w, b = the other one.  Backward-weight: a = image, b = channel (x) or filter (dy).
-// Output dst[chunk][half][f][row][4] (the frequency is NOT the slowest index: the 544 values a
-// wave writes for one row then lie a row pitch apart, within a megabyte, instead of a whole
-// operand slice apart; with the frequency slowest every one of them fell into another page and
-// the kernel's time was set by the number of such stores).  Inside an 8-deep chunk the four
-// images a and their two parts sit as [half = a % 2][row][2 * ((a % 4) / 2) + part]: a 16-byte
-// vector holds the (re, im) pairs of the images a and a + 2, so the wave takes its images in
-// the order 0, 2, 1, 3 and stores after every second one, while the next pair's MFMAs run
-// (any order of the depth serves, as long as both operands use the same).
+// Output dst[chunk][half][f][row][4]: the frequency is not the slowest index, so what one
+// workgroup writes (and what an inverse workgroup gathers from the products, laid out the same
+// way) lies a row pitch apart per frequency, within about a megabyte, instead of a whole operand
+// slice apart.  Inside an 8-deep chunk the four images a and their two parts sit as
+// [half = a % 2][row][2 * ((a % 4) / 2) + part]: a 16-byte vector holds the (re, im) pairs of the
+// images a and a + 2, so a wave takes its images in the order 0, 2 (half 0), then 1, 3 (half 1)
+// and hands a finished pair to the staging area (any order of the depth serves, as long as both
+// operands use the same).
 //   mode 0: row b: (re, im)                                    (stacked pairs, b as row)
 //   mode 1: conjugate in block form, columns 2b + po: column 2b: (re, im), column 2b+1: (-im, re)
 //   mode 2: block form of the spectrum itself:        column 2b: (re, -im), column 2b+1: (im, re)
@@ -219,8 +219,8 @@ __global__ __launch_bounds__(64 * WAVES, 512 / (64 * WAVES)) void fft_image_kern
 }
 
 // ------------------------------------------------------------------ inverse
-// "Image" (row, ch) of the products M[row][f][2 ch + po] (a row's frequencies next to each other): forward (n, k), backward-data (n, c),
-// backward-weight (k, c).  A workgroup takes the 16 channels ch0 .. ch0 + 15 of one row: per
+// "Image" (row, ch) of the products M[row][f][2 ch + po] (a row's frequencies next to each
+// other): forward (n, k), backward-data (n, c), backward-weight (k, c).  A workgroup takes the 16 channels ch0 .. ch0 + 15 of one row: per
 // frequency their 32 values are one 128-byte line of M; the 544 lines are gathered into LDS
 // ([channel][part * 544 + f], channel stride 1089 floats), then every wave transforms four
 // images.
