@@ -86,6 +86,10 @@ def main() -> int:
                          "calls the algorithm cannot serve use auto")
     ap.add_argument("--detail", action="store_true", help="per-layer table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (the same calls, in the same order) into a HIP graph after the warm-up and "
+                         "time K replays of it instead of K sequences of stream launches; the per-layer and per-kernel "
+                         "figures then come from K further eager steps")
     ap.add_argument("--no-calib", action="store_true", help="skip the MFMA / copy probes (roofline.measured_peak)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="run the library's probe_copy_kernel once over this many MiB before the warm-up (a kernel "
@@ -141,10 +145,12 @@ def main() -> int:
         recs.append(rec)
     ws = B.alloc_workspace(ws_need, dev)
     stream = torch.cuda.current_stream()
+    launch_on = [stream]     # the stream the step's calls are given (the capturing stream while a graph is recorded)
 
     ev = []          # (op, layer index, start event, end event) for timed steps
 
     def step(record: bool):
+        stream = launch_on[0]
         for li, r in enumerate(recs):
             if record:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -178,11 +184,28 @@ def main() -> int:
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            launch_on[0] = torch.cuda.current_stream()
+            step(False)
+        launch_on[0] = stream
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):      # per-layer events: eager steps outside the timed region
+            step(True)
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     # the same K steps once more with the library's per-kernel events on (two events per
@@ -315,7 +338,8 @@ def main() -> int:
         "executed_tflops_step": round(xflops_step / (ms_per_step * 1e-3) / 1e12, 3),
         "executed_frac_step": round(xflops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_FP32_TFLOPS, 4),
         "config": {"workload": "%s conv stack, N=%d, %d layers, fwd+bwd_data+bwd_weight, fp32 NCHW"
-                   % (args.workload, layers[0].N, len(layers)), "algo": args.algo},
+                   % (args.workload, layers[0].N, len(layers)), "algo": args.algo,
+                   "launch": "one HIP graph replay per step" if args.graph else "stream launches"},
         "roofline": roofline,
     }
 
