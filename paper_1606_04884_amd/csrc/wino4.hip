@@ -627,22 +627,24 @@ __global__ __launch_bounds__(256) void wino4_wg_output_kernel(W4WgradArgs a)
     }
 }
 
-// db[k] = scale * sum_q bias_part[k][q] (+ db[k]), q over the chunk halves: one wave per
-// filter, lane l adds elements l, l+64, ... in order, the 64 lane sums are combined by a
-// fixed tree of lane exchanges: deterministic.
+// db[k] = scale * sum_q bias_part[k][q] (+ db[k]), q over the chunk halves: one workgroup per
+// filter (with one wave per filter a 256-filter layer was 64 workgroups of long serial loops),
+// thread t adds elements t, t+256, ... in order, each wave combines its 64 sums by a fixed tree
+// of lane exchanges and the four wave sums are added in order: deterministic.
 __global__ __launch_bounds__(256) void wino4_wg_bias_kernel(W4WgradArgs a)
 {
-    const int lane = threadIdx.x & 63;
-    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (k >= a.K) return;
+    __shared__ float wsum[4];
+    const int k = blockIdx.x;
     const int n = a.chunks * 2;
     const float *p = a.bias_part + (int64_t)k * n;
     float sacc = 0.f;
-    for (int i = lane; i < n; i += 64) sacc += p[i];
+    for (int i = threadIdx.x; i < n; i += 256) sacc += p[i];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sacc += __shfl_xor(sacc, o);
-    if (lane == 0) {
-        const float g = a.scale * sacc;
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sacc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float g = a.scale * (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]);
         a.db[k] = a.accumulate ? a.db[k] + g : g;
     }
 }
@@ -777,7 +779,7 @@ hipError_t launch_wino4_wgrad(const W4WgradArgs &a, hipStream_t s)
     hipLaunchKernelGGL(wino4_wg_output_kernel, go, dim3(256), 0, s, a);
     e = hipGetLastError();
     if (e != hipSuccess || !a.db) return e;
-    hipLaunchKernelGGL(wino4_wg_bias_kernel, dim3((unsigned)((a.K + 3) / 4)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(wino4_wg_bias_kernel, dim3((unsigned)a.K), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
