@@ -133,8 +133,8 @@ int conv2d_fwd(const conv2d_desc *d, const float *x, const float *w, const float
  * size is refused with CONV2D_ERR_STATIC_LIMIT and nothing is enqueued (every layer of the
  * AlexNet, VGG-16 and inception configurations fits; filter banks beyond about 512 x 512
  * of 3x3 do not).  With CONV2D_ALGO_AUTO, a layer for which AUTO's choice is the unfused
- * F(4x4,3x3) path (whose workspace holds whole transformed tensors) and does not fit is
- * computed by the fused F(2x2,3x3) kernels instead; the result then differs from
+ * F(4x4,3x3) path or the frequency-domain path (whose workspaces hold whole transformed
+ * tensors) and does not fit is computed by the fused F(2x2,3x3) kernels instead; the result then differs from
  * conv2d_fwd's by rounding only.  All calls on one GPU share that one area, which keeps the previous
  * call's contents (nothing in it needs to start at zero): calls that overlap on one GPU,
  * i.e. on different streams without ordering between them, race.  Calls on one stream
@@ -208,7 +208,7 @@ int apply_mul_add(const float *x, float *y, int64_t n, float a, float b, void *h
  * Opt-in timing of the library's main kernels, for roofline figures: between
  * conv2d_profile_begin(capacity) and conv2d_profile_end() every launch of a main kernel
  * (the GEMM / Winograd / streaming kernels and the transform kernels of the unfused
- * Winograd path; not the small preparation and reduction kernels) is bracketed by two HIP
+ * Winograd and frequency-domain paths; not the small preparation and reduction kernels) is bracketed by two HIP
  * events on its stream, up to `capacity` launches.  begin creates the host-side event
  * objects (kept for reuse until the library is unloaded) and returns CONV2D_OK or an
  * error; end returns the number of launches recorded.  After the caller has synchronised

@@ -72,16 +72,20 @@ def test_static_scratch_forward_matches_workspace_forward():
         np.testing.assert_array_equal(got, ref, err_msg=str(geom))
 
 
-def test_static_scratch_auto_falls_back_to_the_fused_kernels():
-    """A layer for which AUTO picks the unfused F(4x4,3x3) path, whose workspace (whole
-    transformed tensors) exceeds the static area: conv2d_fwd_static computes it with the
-    fused kernels instead; same result up to rounding."""
+@pytest.mark.parametrize("geom,picked", [
+    ((16, 512, 28, 28, 512, 3, 3, 1, 1, 1, 1), B.ALGO_WINOGRAD4),
+    ((128, 64, 27, 27, 192, 5, 5, 1, 1, 2, 2), B.ALGO_FFT),
+], ids=["winograd4", "fft"])
+def test_static_scratch_auto_falls_back_to_the_fused_kernels(geom, picked):
+    """A layer for which AUTO picks the unfused F(4x4,3x3) path or the frequency-domain path,
+    whose workspace (whole transformed tensors) exceeds the static area: conv2d_fwd_static
+    computes it with the fused kernels instead; same result up to rounding."""
     import torch
     dev = torch.device("cuda:0")
     lib = B.load()
-    geom = (16, 512, 28, 28, 512, 3, 3, 1, 1, 1, 1)
-    assert B.conv2d_pick_algo(geom, B.OP_FWD) == B.ALGO_WINOGRAD4
+    assert B.conv2d_pick_algo(geom, B.OP_FWD) == picked
     assert B.conv2d_workspace_bytes(geom, B.OP_FWD) > B.STATIC_SCRATCH_BYTES
+    assert 0 < B.conv2d_workspace_bytes(geom, B.OP_FWD, B.ALGO_WINOGRAD) <= B.STATIC_SCRATCH_BYTES
     x, w, b, yshape = _tensors(geom, 7200, dev)
     y_ref = torch.full(yshape, float("nan"), device=dev)
     y_new = torch.full(yshape, float("nan"), device=dev)
@@ -92,9 +96,9 @@ def test_static_scratch_auto_falls_back_to_the_fused_kernels():
     assert rc == 0, B.status_string(rc)
     torch.cuda.synchronize()
     assert max_err_ratio(y_new.cpu().numpy(), y_ref.cpu().numpy().astype(np.float64)) <= TOL_WINOGRAD
-    # asked for by name, the unfused path is refused here
+    # asked for by name, the path AUTO would take is refused here
     assert lib.conv2d_fwd_static(C.byref(d), x.data_ptr(), w.data_ptr(), b.data_ptr(), y_new.data_ptr(),
-                                 B.ALGO_WINOGRAD4, None) == -6
+                                 picked, None) == -6
 
 
 def test_static_scratch_limit_and_argument_errors():
